@@ -1,0 +1,128 @@
+/*
+ * CPU oracle for the LoRDS inference path in plain C, fp64.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A second, library-free statement of the same definitions as lords_oracle.py
+ * (no BLAS, no blocking, no reordering: every sum runs over its index in
+ * increasing order).  It exists so that (a) full-size layers can be checked in
+ * seconds and (b) the benchmark can time "the oracle on the host cores" beside
+ * the GPU.  Rows of W_hat are independent, so they are handed to OpenMP
+ * threads; nothing else is parallel.  It shares no code with the HIP path and
+ * the product never links it.
+ *
+ *   q[n][k]   = bits [bits*k, bits*k+bits) of packed row n, the row being a
+ *               little-endian bit string (bit b = bit b%8 of byte b/8)
+ *   S[n][k]   = sum_j B[n][j] * A[j][k]                 (paper Sec. 3.2, Eq. 3)
+ *   W[n][k]   = C[q[n][k]] * S[n][k]                    (paper Sec. 3.3 objective,
+ *               W_hat = Q (.) (BA) with Q_ij a level of the look-up table)
+ *   Y[m][n]   = sum_k X[m][k] * W[n][k]                 (the linear layer, Sec. 4.4)
+ *
+ * Inputs are float (bf16-exact where the layer stores bf16) and are widened to
+ * double before use.  Return value: 0 on success, -1 on a bad argument.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int code_at(const uint8_t *row, long k, int bits)
+{
+    int q = 0;
+    for (int b = 0; b < bits; ++b) {
+        long bit = (long)bits * k + b;
+        q |= ((row[bit >> 3] >> (bit & 7)) & 1) << b;
+    }
+    return q;
+}
+
+static int bad_shape(long N, long K, long r, int bits)
+{
+    return N < 0 || K < 0 || r < 0 || (bits != 2 && bits != 3 && bits != 4) || ((K * bits) % 8) != 0;
+}
+
+int lords_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+int lords_oracle_unpack(const uint8_t *codes, uint8_t *q, long N, long K, int bits)
+{
+    if (!codes || !q || bad_shape(N, K, 0, bits)) return -1;
+    const long rb = K * bits / 8;
+#pragma omp parallel for schedule(static)
+    for (long n = 0; n < N; ++n)
+        for (long k = 0; k < K; ++k)
+            q[n * K + k] = (uint8_t)code_at(codes + n * rb, k, bits);
+    return 0;
+}
+
+/* one row of W_hat into w[0..K) */
+static void dequant_row(const uint8_t *row, const float *codebook, const float *Brow,
+                        const float *A, double *w, long K, long r, int bits)
+{
+    for (long k = 0; k < K; ++k) {
+        double s = 0.0;
+        for (long j = 0; j < r; ++j)
+            s += (double)Brow[j] * (double)A[j * K + k];
+        w[k] = (double)codebook[code_at(row, k, bits)] * s;
+    }
+}
+
+int lords_oracle_dequant(const uint8_t *codes, const float *codebook, const float *B,
+                         const float *A, double *W, long N, long K, long r, int bits)
+{
+    if (!codes || !codebook || !B || !A || !W || bad_shape(N, K, r, bits)) return -1;
+    const long rb = K * bits / 8;
+#pragma omp parallel for schedule(static)
+    for (long n = 0; n < N; ++n)
+        dequant_row(codes + n * rb, codebook, B + n * r, A, W + n * K, K, r, bits);
+    return 0;
+}
+
+/* Y[m][i] for the out-features rows[i] (rows == NULL: all N rows, i == n).
+ * Y is M x nrows, row-major. */
+int lords_oracle_matmul_rows(const float *X, const uint8_t *codes, const float *codebook,
+                             const float *B, const float *A, double *Y,
+                             long M, long N, long K, long r, int bits,
+                             const long *rows, long nrows)
+{
+    if (!X || !codes || !codebook || !B || !A || !Y || M < 0 || bad_shape(N, K, r, bits)) return -1;
+    if (!rows) nrows = N;
+    for (long i = 0; rows && i < nrows; ++i)
+        if (rows[i] < 0 || rows[i] >= N) return -1;
+    const long rb = K * bits / 8;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *w = (double *)malloc(sizeof(double) * (size_t)(K > 0 ? K : 1));
+        if (!w) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(static)
+        for (long i = 0; i < nrows; ++i) {
+            if (!w) continue;
+            const long n = rows ? rows[i] : i;
+            dequant_row(codes + n * rb, codebook, B + n * r, A, w, K, r, bits);
+            for (long m = 0; m < M; ++m) {
+                double acc = 0.0;
+                for (long k = 0; k < K; ++k)
+                    acc += (double)X[m * K + k] * w[k];
+                Y[m * nrows + i] = acc;
+            }
+        }
+        free(w);
+    }
+    return failed ? -1 : 0;
+}
+
+int lords_oracle_matmul(const float *X, const uint8_t *codes, const float *codebook,
+                        const float *B, const float *A, double *Y,
+                        long M, long N, long K, long r, int bits)
+{
+    return lords_oracle_matmul_rows(X, codes, codebook, B, A, Y, M, N, K, r, bits, (const long *)0, N);
+}

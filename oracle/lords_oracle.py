@@ -1,0 +1,111 @@
+"""CPU oracle for the LoRDS inference path, in fp64.  TEST INFRASTRUCTURE ONLY.
+
+This file is the yardstick the GPU kernels are checked against.  It is plain,
+slow and written straight from the definitions; it shares no code with the HIP
+path and must never be imported by the product package.  Only tests, the smoke
+check and the benchmark's CPU-baseline leg may use it.
+
+What it computes (notation: W_hat is N x K with N out-features and K
+in-features; the paper's n x m):
+
+  q[n,k]      = the k-th `bits`-wide code of packed row n          (integer)
+  S           = B A            B: N x r, A: r x K      (paper Sec. 3.2, Eq. 3)
+  W_hat       = C[q] (.) S     element-wise            (paper Sec. 3.3, the
+                 objective || W - (BA) (.) Q ||_F^2, and Fig. 1b: the scale
+                 is absorbed into dequantisation; Q_ij is a level of the
+                 look-up table, Alg. 1 step 2.1)
+  Y           = X W_hat^T      the linear layer the kernel replaces
+                 (Sec. 4.4, operator benchmark on q_proj)
+
+Packed row format (the build's storage format, not the paper's): a row is a
+little-endian bit string, bit b of the row being bit (b mod 8) of byte
+(b div 8); code k occupies bits [bits*k, bits*k + bits).  For 4 bits this is
+"low nibble first", for 2 bits four codes per byte from the low end, for
+3 bits 32 codes per 12 bytes.
+
+All floating-point inputs are widened to fp64 before any arithmetic; bf16
+inputs arrive as fp32 arrays holding bf16-exact values, so widening is exact.
+
+Pins (see tests/test_oracle_pins.py): hand-derived byte vectors for the
+unpacker, scalar brute force on tiny inputs, the block-wise special case
+(paper Sec. 3.1), identity activations, the rank-1 closed form, the all-ones
+table (plain low-rank product), linearity, and the paper's rank table
+(Appendix A, Table 7) for `equivalent_rank`.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def unpack_codes(codes: np.ndarray, K: int, bits: int) -> np.ndarray:
+    """codes: uint8 [N, K*bits/8] -> uint8 [N, K] of level indices."""
+    if bits not in (2, 3, 4):
+        raise ValueError("bits must be 2, 3 or 4")
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, nbytes = codes.shape
+    if nbytes * 8 != K * bits:
+        raise ValueError("row length does not match K*bits/8")
+    # the row as a little-endian bit string, then `bits` consecutive bits per code
+    bitstr = np.unpackbits(codes, axis=1, bitorder="little")       # [N, K*bits]
+    fields = bitstr.reshape(N, K, bits).astype(np.uint8)
+    q = np.zeros((N, K), dtype=np.uint8)
+    for b in range(bits):
+        q |= fields[:, :, b] << b
+    return q
+
+
+def scale_matrix(B: np.ndarray, A: np.ndarray) -> np.ndarray:
+    """S = B A in fp64 (Eq. 3)."""
+    B64 = np.asarray(B, dtype=np.float64)
+    A64 = np.asarray(A, dtype=np.float64)
+    if B64.shape[1] != A64.shape[0]:
+        raise ValueError("rank mismatch between B and A")
+    return B64 @ A64
+
+
+def dequant(codes, codebook, B, A, bits: int) -> np.ndarray:
+    """W_hat = C[q] (.) (B A), fp64 [N, K]."""
+    K = np.asarray(A).shape[1]
+    q = unpack_codes(codes, K, bits)
+    C = np.asarray(codebook, dtype=np.float64)
+    if C.shape != (1 << bits,):
+        raise ValueError("codebook must have 2^bits entries")
+    return C[q] * scale_matrix(B, A)
+
+
+def matmul(X, codes, codebook, B, A, bits: int) -> np.ndarray:
+    """Y = X W_hat^T, fp64 [M, N]."""
+    W = dequant(codes, codebook, B, A, bits)
+    return np.asarray(X, dtype=np.float64) @ W.T
+
+
+def matmul_rows(X, codes, codebook, B, A, bits: int, rows) -> np.ndarray:
+    """Columns `rows` of Y (i.e. Y[:, rows]): the definition restricted to the
+    chosen out-features.  Used to check full-size GPU runs on sampled outputs
+    without forming all of W_hat."""
+    rows = np.asarray(rows, dtype=np.int64)
+    return matmul(X, np.asarray(codes)[rows], codebook, np.asarray(B)[rows], A, bits)
+
+
+def equivalent_rank(N: int, K: int, group: int) -> int:
+    """Rank whose factor budget r (N + K) matches the block-wise scale budget
+    N K / group: r = floor(N K / (group (N + K)))  (Sec. 3.2; Appendix A)."""
+    return (int(N) * int(K)) // (int(group) * (int(N) + int(K)))
+
+
+# ----------------------------------------------------------------------------
+# error measures used by the parity gates
+# ----------------------------------------------------------------------------
+def rel_fro(got, want) -> float:
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    denom = np.linalg.norm(want)
+    return float(np.linalg.norm(got - want) / denom) if denom > 0 else float(np.linalg.norm(got))
+
+
+def max_abs_over_rms(got, want) -> float:
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    rms = np.sqrt(np.mean(want * want))
+    err = np.max(np.abs(got - want)) if want.size else 0.0
+    return float(err / rms) if rms > 0 else float(err)

@@ -1,0 +1,118 @@
+/*
+ * lords.h -- C ABI of the MI355X (gfx950) LoRDS inference library.
+ *
+ * LoRDS ("low-rank decomposed scaling", arXiv 2601.22716) stores a weight matrix
+ * W_hat (N out-features x K in-features) as
+ *      W_hat = C[Q] (.) S ,   S = B A                         (Sec. 3.2 Eq. 3; Sec. 3.3)
+ * where Q holds one k-bit level index per element (k = 2, 3 or 4), C is the
+ * 2^k-entry look-up table of the target data type (Alg. 1, "Require"), and the
+ * element-wise scale S is the product of the rank-r factors B (N x r) and
+ * A (r x K).  S and W_hat are regenerated per tile inside the kernels and are
+ * never written to device memory by lords_matmul.
+ *
+ * Conventions common to every entry point
+ *  - Every data pointer is a DEVICE pointer owned by the caller, at least 16-byte
+ *    aligned, to a dense row-major array.  The library neither keeps nor frees
+ *    them.  `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *    Calls enqueue work on `stream` and return without synchronising.
+ *  - Packed code rows: row n starts at byte n*K*bits/8; a row is a little-endian
+ *    bit string (bit b of the row is bit b%8 of byte b/8) and code k occupies bits
+ *    [bits*k, bits*k+bits).  4 bits: two codes per byte, low nibble first; 2 bits:
+ *    four per byte from the low end; 3 bits: 32 codes per 12 bytes.
+ *  - K must be a multiple of 32 (whole 12-byte groups at 3 bits, whole 16-byte
+ *    loads at 4 bits).  N >= 1, r >= 1 and M >= 0 are otherwise arbitrary.
+ *  - Factors B and A are both bf16 or both fp32 (`factor_dtype`); X is bf16.
+ *  - Outputs are overwritten entirely (no accumulate).
+ *  - Errors are returned, never thrown.  Arguments are checked in the fixed order
+ *    NULL -> BITS -> SHAPE -> ALIGN -> DTYPE before anything is launched, so a bad
+ *    call touches no memory.  A launch failure reported by the runtime gives
+ *    LORDS_ERR_LAUNCH.
+ *  - lords_matmul may use a per-device workspace that the library allocates on
+ *    first need and keeps until the process ends; calls that overlap in time on
+ *    one device must therefore not be issued from different streams.
+ */
+#ifndef LORDS_H
+#define LORDS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LORDS_OK = 0,
+    LORDS_ERR_NULL = 1,    /* a required pointer is NULL */
+    LORDS_ERR_BITS = 2,    /* bits is not 2, 3 or 4 */
+    LORDS_ERR_SHAPE = 3,   /* N < 1, r < 1, M < 0, K < 32, K % 32 != 0, or a size overflows int */
+    LORDS_ERR_ALIGN = 4,   /* a pointer is not 16-byte aligned */
+    LORDS_ERR_DTYPE = 5,   /* unknown lords_dtype / lords_path value */
+    LORDS_ERR_LAUNCH = 6,  /* the HIP runtime refused the launch or a workspace allocation */
+    LORDS_ERR_UNSUPPORTED = 7 /* the forced path cannot run this shape */
+} lords_status;
+
+typedef enum { LORDS_BF16 = 0, LORDS_F32 = 1 } lords_dtype;
+
+/* Which kernel family lords_matmul_ex runs.  AUTO picks by M. */
+typedef enum {
+    LORDS_PATH_AUTO = 0,
+    LORDS_PATH_DECODE = 1,   /* memory-bound small-M path (M <= 16 per pass) */
+    LORDS_PATH_PREFILL = 2   /* bf16 MFMA GEMM with the dequantised tile as operand */
+} lords_path;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int lords_version(void);
+
+/* Static, NUL-terminated description of a lords_status value. */
+const char *lords_status_string(int status);
+
+/* Bytes of one packed row of K codes (K*bits/8); 0 if bits or K is invalid. */
+size_t lords_row_bytes(int K, int bits);
+
+/* Rank whose factor budget r(N+K) matches a block-wise scale budget NK/group:
+ * floor(NK / (group (N+K)))  (Sec. 3.2; Appendix A, Table 7).  -1 on bad input. */
+long lords_equivalent_rank(long N, long K, long group);
+
+/* Bit-unpack only: idx[n*K + k] = code k of row n.  (The storage side of Q; Alg. 1's
+ * quantised matrix holds one level per element.)
+ *   codes  in   N x K*bits/8 bytes
+ *   idx    out  N x K uint8
+ */
+int lords_unpack(const void *codes, uint8_t *idx, int N, int K, int bits, void *stream);
+
+/* Dequantise: W[n*K + k] = codebook[q[n][k]] * sum_j B[n][j] A[j][k]
+ * (W_hat = Q (.) (BA), Sec. 3.3; scale absorbed into dequantisation, Fig. 1b).
+ *   codebook  in   2^bits fp32
+ *   B, A      in   N x r and r x K, dtype `factor_dtype`
+ *   W         out  N x K, dtype `w_dtype`; the scale is accumulated in fp32 and the
+ *                  product rounded once on store.
+ * A parity artefact: the fast path (lords_matmul) never writes W.
+ */
+int lords_dequant(const void *codes, const float *codebook, const void *B, const void *A,
+                  void *W, int N, int K, int r, int bits,
+                  lords_dtype factor_dtype, lords_dtype w_dtype, void *stream);
+
+/* Fused dequantise-and-multiply: Y[m*N + n] = sum_k X[m][k] * W_hat[n][k]
+ * (the linear layer the paper's inference kernel replaces, Sec. 4.4; Fig. 1b).
+ *   X   in   M x K bf16
+ *   Y   out  M x N, dtype `y_dtype`; accumulation is fp32.
+ * M == 0 returns LORDS_OK without launching.  Small M takes the memory-bound
+ * decode kernels, large M the MFMA GEMM; results are run-to-run deterministic.
+ */
+int lords_matmul(const void *X, const void *codes, const float *codebook,
+                 const void *B, const void *A, void *Y,
+                 int M, int N, int K, int r, int bits,
+                 lords_dtype factor_dtype, lords_dtype y_dtype, void *stream);
+
+/* Same, with the kernel family forced (for cross-over sweeps and tests). */
+int lords_matmul_ex(const void *X, const void *codes, const float *codebook,
+                    const void *B, const void *A, void *Y,
+                    int M, int N, int K, int r, int bits,
+                    lords_dtype factor_dtype, lords_dtype y_dtype, void *stream,
+                    lords_path path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORDS_H */

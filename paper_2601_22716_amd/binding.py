@@ -1,0 +1,128 @@
+"""ctypes binding of liblords.so.  Same names as include/lords.h; argument
+marshalling only (tensor -> device pointer, current stream -> void*)."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblords.so")
+_lib = None
+
+LORDS_BF16, LORDS_F32 = 0, 1
+LORDS_PATH_AUTO, LORDS_PATH_DECODE, LORDS_PATH_PREFILL = 0, 1, 2
+STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LORDS_ERR_SHAPE",
+                4: "LORDS_ERR_ALIGN", 5: "LORDS_ERR_DTYPE", 6: "LORDS_ERR_LAUNCH", 7: "LORDS_ERR_UNSUPPORTED"}
+
+EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank",
+           "lords_unpack", "lords_dequant", "lords_matmul", "lords_matmul_ex"]
+
+
+class LordsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({lords_status_string(status)})")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def library():
+    """Load liblords.so (built in-tree by paper_2601_22716_amd.build). Fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2601_22716_amd.build` "
+                "(there is no fallback implementation)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, ci, cl = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
+        lib.lords_version.restype = ci
+        lib.lords_version.argtypes = []
+        lib.lords_status_string.restype = ctypes.c_char_p
+        lib.lords_status_string.argtypes = [ci]
+        lib.lords_row_bytes.restype = ctypes.c_size_t
+        lib.lords_row_bytes.argtypes = [ci, ci]
+        lib.lords_equivalent_rank.restype = cl
+        lib.lords_equivalent_rank.argtypes = [cl, cl, cl]
+        lib.lords_unpack.restype = ci
+        lib.lords_unpack.argtypes = [vp, vp, ci, ci, ci, vp]
+        lib.lords_dequant.restype = ci
+        lib.lords_dequant.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
+        lib.lords_matmul.restype = ci
+        lib.lords_matmul.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+        lib.lords_matmul_ex.restype = ci
+        lib.lords_matmul_ex.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci]
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or a raw int / None passed through)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to the library must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return LORDS_BF16
+    if t.dtype == torch.float32:
+        return LORDS_F32
+    raise TypeError(f"unsupported dtype {t.dtype}: the library takes bfloat16 or float32")
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise LordsError(status, where)
+
+
+def lords_version() -> int:
+    return int(library().lords_version())
+
+
+def lords_status_string(status: int) -> str:
+    return library().lords_status_string(int(status)).decode()
+
+
+def lords_row_bytes(K: int, bits: int) -> int:
+    return int(library().lords_row_bytes(K, bits))
+
+
+def lords_equivalent_rank(N: int, K: int, group: int) -> int:
+    return int(library().lords_equivalent_rank(N, K, group))
+
+
+def lords_unpack(codes, idx, N: int, K: int, bits: int, stream=None) -> None:
+    _check(library().lords_unpack(_ptr(codes), _ptr(idx), N, K, bits, _stream(stream)), "lords_unpack")
+
+
+def lords_dequant(codes, codebook, B, A, W, N: int, K: int, r: int, bits: int, stream=None) -> None:
+    _check(library().lords_dequant(_ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(W), N, K, r, bits,
+                                   _dtype_code(B), _dtype_code(W), _stream(stream)), "lords_dequant")
+
+
+def lords_matmul(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int, stream=None) -> None:
+    _check(library().lords_matmul(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
+                                  _dtype_code(B), _dtype_code(Y), _stream(stream)), "lords_matmul")
+
+
+def lords_matmul_ex(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int,
+                    path: int = LORDS_PATH_AUTO, stream=None) -> None:
+    _check(library().lords_matmul_ex(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
+                                     _dtype_code(B), _dtype_code(Y), _stream(stream), path), "lords_matmul_ex")

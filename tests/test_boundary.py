@@ -1,0 +1,125 @@
+"""Boundary checks that need no GPU: the C-ABI library loads, exports every
+symbol the header declares, and rejects bad arguments in the documented order
+before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2601_22716_amd as L
+from tests.helpers import read_rank_table
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 4096   # a fake, 16-byte aligned, non-null "device pointer": never dereferenced on the error paths
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lords.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lords_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree():
+    names = declared_functions()
+    assert set(names) == set(L.binding.EXPORTS)
+    lib = ctypes.CDLL(L.library_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/lords.h but not exported"
+
+
+def test_version_and_strings():
+    assert L.lords_version() >= 100
+    for s in range(0, 8):
+        assert L.lords_status_string(s)
+    assert "unknown" in L.lords_status_string(99)
+
+
+def test_row_bytes():
+    assert L.lords_row_bytes(4096, 4) == 2048
+    assert L.lords_row_bytes(4096, 3) == 1536
+    assert L.lords_row_bytes(8192, 2) == 2048
+    assert L.lords_row_bytes(32, 3) == 12
+    assert L.lords_row_bytes(4096, 5) == 0
+    assert L.lords_row_bytes(48, 4) == 0
+    assert L.lords_row_bytes(0, 4) == 0
+
+
+def test_equivalent_rank_matches_table7(golden_dir):
+    for _, _, N, K, r128, r256 in read_rank_table(os.path.join(golden_dir, "table7_ranks.txt")):
+        assert L.lords_equivalent_rank(N, K, 128) == r128
+        assert L.lords_equivalent_rank(N, K, 256) == r256
+    assert L.lords_equivalent_rank(4096, 4096, 64) == 32
+    assert L.lords_equivalent_rank(0, 4096, 64) == -1
+    assert L.lords_equivalent_rank(4096, 4096, 0) == -1
+
+
+def test_unpack_argument_checks():
+    f = L.library().lords_unpack
+    assert f(None, P, 4, 64, 4, None) == 1
+    assert f(P, None, 4, 64, 4, None) == 1
+    assert f(P, P, 4, 64, 5, None) == 2
+    assert f(P, P, 4, 64, 1, None) == 2
+    assert f(P, P, 0, 64, 4, None) == 3
+    assert f(P, P, 4, 48, 4, None) == 3
+    assert f(P, P, 4, 0, 4, None) == 3
+    assert f(P + 8, P, 4, 64, 4, None) == 4
+    assert f(P, P + 1, 4, 64, 4, None) == 4
+    # order: NULL before BITS before SHAPE before ALIGN
+    assert f(None, P + 1, 0, 48, 7, None) == 1
+    assert f(P + 1, P, 0, 48, 7, None) == 2
+    assert f(P + 1, P, 0, 48, 4, None) == 3
+
+
+def test_dequant_argument_checks():
+    f = L.library().lords_dequant
+    ok = [P, P, P, P, P, 8, 64, 4, 4, 0, 1, None]
+    for i in range(5):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[8] = 8
+    assert f(*a) == 2
+    for i, v in ((5, 0), (6, 40), (7, 0)):
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    a = list(ok); a[2] = P + 4
+    assert f(*a) == 4
+    a = list(ok); a[9] = 2
+    assert f(*a) == 5
+    a = list(ok); a[10] = -1
+    assert f(*a) == 5
+    a = list(ok); a[0] = None; a[8] = 9; a[6] = 1; a[9] = 7
+    assert f(*a) == 1
+
+
+def test_matmul_argument_checks():
+    f = L.library().lords_matmul
+    fx = L.library().lords_matmul_ex
+    ok = [P, P, P, P, P, P, 1, 8, 64, 4, 4, 0, 1, None]
+    for i in range(6):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[10] = 0
+    assert f(*a) == 2
+    for i, v in ((6, -1), (7, 0), (8, 16), (8, 100), (9, 0)):
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    a = list(ok); a[5] = P + 2
+    assert f(*a) == 4
+    a = list(ok); a[11] = 3
+    assert f(*a) == 5
+    a = list(ok); a[12] = 3
+    assert f(*a) == 5
+    assert fx(*ok, 9) == 5
+    # M == 0 is a no-op that succeeds without touching the device
+    a = list(ok); a[6] = 0
+    assert f(*a) == 0
+    # a rank beyond what the kernels hold in registers is reported, not launched
+    a = list(ok); a[9] = 100000
+    assert f(*a) == 7
+
+
+def test_binding_raises_with_status_name():
+    with pytest.raises(L.LordsError) as e:
+        L.binding._check(4, "lords_matmul")
+    assert "LORDS_ERR_ALIGN" in str(e.value)

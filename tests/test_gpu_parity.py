@@ -1,0 +1,186 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle
+on the same seeded inputs.
+
+Gates: unpacked indices bit-exact; W within relative Frobenius error 1e-3;
+Y within relative Frobenius error 5e-3 and max |dY| <= 2e-2 * rms(Y_oracle).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import lords_inputs as li
+from oracle import lords_oracle as onp
+from oracle import lords_oracle_c as oc
+
+pytestmark = pytest.mark.gpu
+
+W_TOL, Y_TOL, Y_MAX_TOL = 1e-3, 5e-3, 2e-2
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from tests import gpu_util
+    return gpu_util
+
+
+def check_y(Y, want, what):
+    rf, mx = onp.rel_fro(Y, want), onp.max_abs_over_rms(Y, want)
+    say(f"   {what}: rel_fro={rf:.2e} max/rms={mx:.2e}")
+    assert np.isfinite(Y).all(), what
+    assert rf <= Y_TOL, (what, rf)
+    assert mx <= Y_MAX_TOL, (what, mx)
+
+
+# ------------------------------------------------------------------ unpack
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K", [(1, 32), (5, 96), (67, 416), (512, 256)])
+def test_unpack_bit_exact(gpu, bits, N, K):
+    say(f"unpack bits={bits} N={N} K={K}")
+    cs = li.make_case("tiny", N=N, K=K, bits=bits, r=1, seed=11)
+    got = gpu.DeviceCase(cs).unpack()
+    np.testing.assert_array_equal(got, onp.unpack_codes(cs.codes, K, bits))
+
+
+# ----------------------------------------------------------------- dequant
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("fdt", ["bf16", "f32"])
+@pytest.mark.parametrize("N,K,r", [(3, 32, 1), (70, 160, 5), (512, 256, 4), (129, 4128, 48)])
+def test_dequant_parity(gpu, bits, fdt, N, K, r):
+    say(f"dequant bits={bits} factors={fdt} N={N} K={K} r={r}")
+    cs = li.make_case("tiny", N=N, K=K, bits=bits, r=r, factor_dtype=fdt, seed=5, signed_factors=True)
+    W = gpu.DeviceCase(cs).dequant()
+    want = onp.dequant(cs.codes, cs.codebook, cs.B_f32, cs.A_f32, bits)
+    rf = onp.rel_fro(W, want)
+    say(f"   rel_fro={rf:.2e}")
+    assert rf <= W_TOL
+
+
+def test_dequant_bf16_output_is_rounded_oracle(gpu):
+    import torch
+    cs = li.make_case("tiny", seed=2)
+    W = gpu.DeviceCase(cs).dequant(dtype=torch.bfloat16)
+    want = onp.dequant(cs.codes, cs.codebook, cs.B_f32, cs.A_f32, 4)
+    _, want_bf = li.to_bf16(want.astype(np.float32))
+    # exact, or one bf16 ulp where fp32 rounding of the scale moved a tie
+    ulp = np.abs(want_bf) * 2.0 ** -7
+    assert np.all(np.abs(W - want_bf) <= ulp)
+    assert np.mean(W == want_bf) > 0.99
+
+
+@pytest.mark.parametrize("bits,group", [(4, 32), (2, 64), (3, 32)])
+def test_dequant_blockwise_case_is_bit_exact(gpu, bits, group):
+    """A = group indicator, B = block scales: one non-zero term per sum, so the
+    fp32 GPU result must equal C[q]*s rounded once -- the block-wise dequantiser
+    (paper Sec. 3.1) -- to the last bit."""
+    say(f"dequant blockwise bits={bits} group={group}")
+    cs = li.make_blockwise_case(96, 256, bits, group, seed=4)
+    W = gpu.DeviceCase(cs).dequant()
+    q = onp.unpack_codes(cs.codes, cs.K, bits)
+    s = np.repeat(cs.extra["block_scales"], group, axis=1)
+    want = (cs.codebook[q].astype(np.float32) * s.astype(np.float32)).astype(np.float32)
+    np.testing.assert_array_equal(W, want)
+
+
+# ------------------------------------------------------------------ matmul
+SHAPES = [
+    # N, K, r, M
+    (16, 32, 1, 1),
+    (70, 160, 5, 3),
+    (512, 256, 4, 4),
+    (257, 544, 48, 16),
+    (130, 1056, 64, 2),
+    (300, 288, 33, 7),
+]
+
+
+@pytest.mark.parametrize("path", ["decode", "prefill"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("fdt", ["bf16", "f32"])
+@pytest.mark.parametrize("N,K,r,M", SHAPES)
+def test_matmul_parity_small(gpu, path, bits, fdt, N, K, r, M):
+    import paper_2601_22716_amd as L
+    say(f"matmul path={path} bits={bits} factors={fdt} N={N} K={K} r={r} M={M}")
+    cs = li.make_case("tiny", M=M, N=N, K=K, bits=bits, r=r, factor_dtype=fdt, seed=9, signed_factors=(r % 2 == 1))
+    Y = gpu.DeviceCase(cs).matmul(path=L.LORDS_PATH_DECODE if path == "decode" else L.LORDS_PATH_PREFILL)
+    want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, bits)
+    check_y(Y, want, "Y")
+
+
+@pytest.mark.parametrize("M", [1, 17, 40, 130, 300])
+def test_matmul_parity_ragged_tokens(gpu, M):
+    import paper_2601_22716_amd as L
+    say(f"matmul ragged M={M}")
+    cs = li.make_case("tiny", M=M, N=200, K=512, bits=4, r=32, factor_dtype="bf16", seed=3)
+    d = gpu.DeviceCase(cs)
+    want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, 4)
+    check_y(d.matmul(path=L.LORDS_PATH_AUTO), want, "auto")
+    check_y(d.matmul(path=L.LORDS_PATH_DECODE), want, "decode")
+    check_y(d.matmul(path=L.LORDS_PATH_PREFILL), want, "prefill")
+
+
+def test_matmul_tiny_config(gpu):
+    import torch
+    cs = li.make_case("tiny")
+    d = gpu.DeviceCase(cs)
+    want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, 4)
+    check_y(d.matmul(), want, "fp32 Y")
+    check_y(d.matmul(dtype=torch.bfloat16), want, "bf16 Y")
+    # identity activations: Y = W_hat^T
+    X = torch.eye(cs.K, dtype=torch.bfloat16, device="cuda")
+    Wt = d.matmul(X=X, M=cs.K)
+    check_y(Wt, onp.dequant(cs.codes, cs.codebook, cs.B_f32, cs.A_f32, 4).T, "identity X")
+
+
+def test_matmul_is_deterministic(gpu):
+    cs = li.make_case("qproj_4b", M=4, N=1024)
+    d = gpu.DeviceCase(cs)
+    y1, y2 = d.matmul(), d.matmul()
+    np.testing.assert_array_equal(y1, y2)
+
+
+@pytest.mark.parametrize("bits,group", [(4, 64), (2, 64)])
+def test_matmul_blockwise_case(gpu, bits, group):
+    """r = K/group with the indicator A: the block-wise quantised layer."""
+    say(f"matmul blockwise bits={bits}")
+    cs = li.make_blockwise_case(320, 2048, bits, group, M=3, seed=6)
+    assert cs.r == 32
+    d = gpu.DeviceCase(cs)
+    want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, bits)
+    check_y(d.matmul(), want, "blockwise Y")
+
+
+# ------------------------------------------------- full-size layers, sampled
+FULL = [
+    ("qproj_4b", 1), ("qproj_4b", 16),
+    ("gateup_3b", 1), ("down_3b", 16),
+    ("gateup_4b", 1), ("gateup_4b", 2048), ("down_4b", 2048),
+    ("l70b_2b", 1), ("l70b_2b", 256),
+]
+
+
+@pytest.mark.parametrize("name,M", FULL)
+def test_matmul_full_size_sampled(gpu, name, M):
+    """The benchmark's launch configuration at full layer size, checked on sampled
+    out-features (all tokens) that the C oracle computes one row at a time."""
+    say(f"full-size {name} M={M}")
+    cs = li.make_case(name, M=M)
+    d = gpu.DeviceCase(cs)
+    Y = d.matmul()
+    rng = np.random.default_rng(123)
+    rows = np.unique(np.concatenate([[0, 1, 15, 16, cs.N - 1], rng.integers(0, cs.N, 250)]))
+    Xs = cs.X_f32 if M <= 64 else cs.X_f32
+    want = oc.matmul(Xs, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, cs.bits, rows=rows)
+    assert np.isfinite(Y).all()
+    check_y(Y[:, rows], want, f"{name} M={M} sampled {rows.size} rows")
+    # indices of the same layer, bit-exact, on a slab of rows
+    if M == cs.cfg.Ms[0]:
+        got = d.unpack()
+        np.testing.assert_array_equal(got[rows], oc.unpack_codes(cs.codes[rows], cs.K, cs.bits))

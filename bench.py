@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the LoRDS fused dequantise-and-multiply on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|prefill|all]
+
+A "step" is one lords_matmul call (the whole hot path: unpack, look-up, scale
+regeneration, dequantise, multiply) on one synthetic Llama-3-8B gate/up layer
+(N = 14336, K = 4096, 4-bit codes, rank 32), M = 1 token: the decode headline.
+Consecutive steps walk through enough distinct weight sets (> 600 MB in total)
+that no step finds its weights in the 256 MB last-level cache.  Inputs are
+resident in HBM before the timed region.  The K timed steps are captured once
+in a HIP graph and replayed, so the number is the GPU's, not the Python
+interpreter's; the eager per-call time is reported beside it.
+
+Prints ONE JSON line.  `value` is decode GB/s (algorithmic bytes / time);
+`prefill` carries TFLOP/s at M = 2048 on the same layer; `roofline` belongs to
+the decode kernel, `prefill.roofline` to the MFMA GEMM; `cpu_baseline` is the
+fp64 C oracle timed on this host's cores (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, vendor figure
+COLD_BYTES = 600e6             # rotate through at least this many weight bytes
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); None = not measured
+DECODE_TRAFFIC_BYTES = None
+PREFILL_TRAFFIC_BYTES = None
+
+
+def algorithmic_bytes(M, N, K, r, bits, factor_bytes=2, y_bytes=4):
+    return N * K * bits // 8 + (N * r + r * K) * factor_bytes + M * K * 2 + M * N * y_bytes + (1 << bits) * 4
+
+
+def make_sets(cfg_name, M, nsets, li, torch):
+    """nsets independent weight sets of one layer shape + one activation matrix."""
+    import paper_2601_22716_amd as L
+    bf16_tensor = L.bf16_from_bits
+    sets = []
+    cs0 = None
+    for s in range(nsets):
+        cs = li.make_case(cfg_name, M=M, seed=1000 + s)
+        if cs0 is None:
+            cs0 = cs
+        sets.append((torch.from_numpy(cs.codes).cuda(), bf16_tensor(cs.B_bf16), bf16_tensor(cs.A_bf16)))
+    X = bf16_tensor(cs0.X_bf16)
+    codebook = torch.from_numpy(cs0.codebook.copy()).cuda()
+    return cs0, sets, X, codebook
+
+
+def time_steps(run_step, steps, warmup, torch, use_graph=True):
+    """Returns (wall seconds for `steps` steps, event milliseconds for the same region, eager s/step)."""
+    for i in range(warmup):
+        run_step(i)
+    torch.cuda.synchronize()
+    # eager timing (Python + launch overhead included), for context
+    n_eager = min(steps, 50)
+    t0 = time.perf_counter()
+    for i in range(n_eager):
+        run_step(i)
+    torch.cuda.synchronize()
+    eager = (time.perf_counter() - t0) / n_eager
+
+    stream = torch.cuda.Stream()
+    graph = None
+    if use_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(stream):
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(steps):
+                    run_step(i)
+            graph.replay()                      # untimed: first replay uploads the graph
+        torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(stream):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        if graph is not None:
+            graph.replay()
+        else:
+            for i in range(steps):
+                run_step(i)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    return wall, ev0.elapsed_time(ev1), eager
+
+
+def bench_decode(args, L, li, torch):
+    name, M = "gateup_4b", 1
+    cfg = li.CONFIGS[name]
+    per_set = cfg.N * cfg.K * cfg.bits // 8
+    nsets = int(-(-COLD_BYTES // per_set))
+    cs, sets, X, codebook = make_sets(name, M, nsets, li, torch)
+    Y = torch.zeros((M, cfg.N), dtype=torch.float32, device="cuda")
+
+    def run_step(i):
+        codes, B, A = sets[i % nsets]
+        L.lords_matmul(X, codes, codebook, B, A, Y, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+
+    wall, ev_ms, eager = time_steps(run_step, args.steps, args.warmup, torch, use_graph=not args.no_graph)
+    ab = algorithmic_bytes(M, cfg.N, cfg.K, cfg.r, cfg.bits)
+    sec_per_step = wall / args.steps
+    ev_per_launch = ev_ms * 1e-3 / args.steps
+    achieved = ab / ev_per_launch / 1e9
+    out = {
+        "value": ab / sec_per_step / 1e9,
+        "ms_per_step": sec_per_step * 1e3,
+        "eager_ms_per_step": eager * 1e3,
+        "config": {"workload": f"decode M={M}, Llama-3-8B gate/up shape N={cfg.N} K={cfg.K}, {cfg.bits}-bit codes, rank {cfg.r}, "
+                               f"bf16 factors, fp32 Y; {nsets} rotating weight sets (cold last-level cache)",
+                   "algorithmic_bytes_per_step": ab, "weight_sets": nsets, "hip_graph": not args.no_graph},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": DECODE_TRAFFIC_BYTES,
+                     "kernel": "lords::fused_kernel<4,1,...> (small-M path)", "us_per_launch": ev_per_launch * 1e6},
+    }
+    return out, cs, sets[0], X, codebook
+
+
+def bench_prefill(args, L, li, torch):
+    name, M = "gateup_4b", 2048
+    cfg = li.CONFIGS[name]
+    cs, sets, X, codebook = make_sets(name, M, 2, li, torch)
+    Y = torch.zeros((M, cfg.N), dtype=torch.bfloat16, device="cuda")
+
+    def run_step(i):
+        codes, B, A = sets[i % 2]
+        L.lords_matmul(X, codes, codebook, B, A, Y, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+
+    steps = max(1, min(args.steps, 20))
+    wall, ev_ms, eager = time_steps(run_step, steps, min(args.warmup, 3), torch, use_graph=not args.no_graph)
+    flops = 2.0 * M * cfg.N * cfg.K
+    ev_per_launch = ev_ms * 1e-3 / steps
+    achieved = flops / ev_per_launch / 1e12
+    return {
+        "metric": "prefill TFLOP/s (2MNK / time)", "value": flops / (wall / steps) / 1e12, "unit": "TFLOP/s",
+        "steps": steps, "ms_per_step": wall / steps * 1e3, "dtype": "bf16",
+        "config": {"workload": f"prefill M={M}, N={cfg.N} K={cfg.K}, {cfg.bits}-bit codes, rank {cfg.r}, bf16 Y"},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": PREFILL_TRAFFIC_BYTES,
+                     "kernel": "lords::fused_kernel<4,1,...> (MFMA GEMM path)", "us_per_launch": ev_per_launch * 1e6},
+    }
+
+
+def cpu_baseline(li, ab):
+    """The fp64 C oracle, as it stands, on the decode workload (M = 1, whole layer), host cores."""
+    from oracle import lords_oracle_c as oc
+    cs = li.make_case("gateup_4b", M=1, seed=1000)
+    threads = oc.threads()
+    oc.matmul(cs.X_f32, cs.codes[:256], cs.codebook, cs.B_f32[:256], cs.A_f32, cs.bits)     # warm-up, small slab
+    reps, t_total = 0, 0.0
+    while reps < 3 or (t_total < 2.0 and reps < 20):
+        t0 = time.perf_counter()
+        oc.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, cs.bits)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    sec = t_total / reps
+    return {"value": ab / sec / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{reps} passes of the whole decode layer (M=1, N=14336, K=4096, 4-bit, r=32) through the "
+                      f"plain-C fp64 oracle with OpenMP over rows; {sec * 1e3:.1f} ms per pass",
+            "ms_per_step": sec * 1e3}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", choices=["decode", "prefill", "all"], default="all")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are part of it)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import lords_inputs as li
+    import paper_2601_22716_amd as L
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    L.library()      # fail loudly if liblords.so is missing: there is no fallback
+
+    line = {"metric": "decode GB/s (algorithmic bytes / time, M=1)", "value": None, "unit": "GB/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": None, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+    ab = algorithmic_bytes(1, 14336, 4096, 32, 4)
+    if args.workload in ("decode", "all"):
+        d, *_ = bench_decode(args, L, li, torch)
+        line.update(d)
+    if args.workload in ("prefill", "all"):
+        p = bench_prefill(args, L, li, torch)
+        if args.workload == "prefill":
+            line.update({k: p[k] for k in ("metric", "value", "unit", "steps", "ms_per_step", "config", "roofline")})
+        else:
+            line["prefill"] = p
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(li, ab)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

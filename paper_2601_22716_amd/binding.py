@@ -36,6 +36,9 @@ def library():
             raise FileNotFoundError(
                 f"{_LIB_PATH} is missing: build it with `python -m paper_2601_22716_amd.build` "
                 "(there is no fallback implementation)")
+        # PyTorch-ROCm ships its own HIP runtime; load it first so that the library, torch's
+        # allocator and torch's streams all live in ONE runtime instance.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(_LIB_PATH)
         vp, ci, cl = ctypes.c_void_p, ctypes.c_int, ctypes.c_long
         lib.lords_version.restype = ci
@@ -56,6 +59,14 @@ def library():
         lib.lords_matmul_ex.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci]
         _lib = lib
     return _lib
+
+
+def bf16_from_bits(bits_u16, device="cuda"):
+    """numpy uint16 bf16 bit patterns -> torch.bfloat16 tensor on `device` (a reinterpretation, no arithmetic)."""
+    import numpy as np
+    import torch
+    a = np.ascontiguousarray(bits_u16, dtype=np.uint16)
+    return torch.from_numpy(a.view(np.int16).copy()).to(device).view(torch.bfloat16)
 
 
 def _ptr(t):

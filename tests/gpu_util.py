@@ -8,7 +8,7 @@ import paper_2601_22716_amd as L
 
 
 def bf16_tensor(bits_u16: np.ndarray) -> torch.Tensor:
-    return torch.from_numpy(bits_u16.view(np.int16).copy()).cuda().view(torch.bfloat16)
+    return L.bf16_from_bits(bits_u16)
 
 
 class DeviceCase:

@@ -41,6 +41,8 @@ int get_workspace(size_t need, void **out)
         }
         size_t want = need < (size_t)(8u << 20) ? (size_t)(8u << 20) : need;
         if (hipMalloc(&w.ptr, want) != hipSuccess) { w.ptr = nullptr; return LORDS_ERR_LAUNCH; }
+        // arrival tickets at the front of the buffer must start at zero; kernels leave them at zero
+        if (hipMemset(w.ptr, 0, want) != hipSuccess || hipDeviceSynchronize() != hipSuccess) return LORDS_ERR_LAUNCH;
         w.bytes = want;
     }
     *out = w.ptr;
@@ -128,9 +130,12 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook, con
     hipError_t e;
     if (path == LORDS_PATH_DECODE) {
         void *ws = nullptr;
-        const int rc = get_workspace(lords::decode_workspace_bytes(p), &ws);
+        const bool fast = lords::decode_fast_supported(p);
+        const int rc = get_workspace(fast ? lords::decode_fast_workspace_bytes(p)
+                                          : lords::kTicketBytes + lords::decode_workspace_bytes(p), &ws);
         if (rc != LORDS_OK) return rc;
-        e = lords::launch_decode(p, ws, (hipStream_t)stream);
+        e = fast ? lords::launch_decode_fast(p, ws, (hipStream_t)stream)
+                 : lords::launch_decode(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream);
     } else {
         e = lords::launch_prefill(p, (hipStream_t)stream);
     }

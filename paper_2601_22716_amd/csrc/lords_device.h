@@ -79,6 +79,18 @@ __device__ __forceinline__ uint16_t factorA_bits(const Factors &f, int jj, int k
     return seg == 1 ? bf16_bits(x - bf16_to_f32(hi)) : hi;
 }
 
+// Same as factorA_bits for the product A[j][k] * x (one-token path: the activation is folded
+// into the A tile).  fp32 factors: the fp32 product is split hi/lo like a factor.
+__device__ __forceinline__ uint16_t factorAx_bits(const Factors &f, int jj, int k, float x)
+{
+    if (jj >= f.r_eff || k >= f.K) return 0;
+    if (!f.f32) return bf16_bits(bf16_to_f32(reinterpret_cast<const uint16_t *>(f.A)[(size_t)jj * f.K + k]) * x);
+    const int seg = jj / f.r, j = jj - seg * f.r;
+    const float p = reinterpret_cast<const float *>(f.A)[(size_t)j * f.K + k] * x;
+    const uint16_t hi = bf16_bits(p);
+    return seg == 1 ? bf16_bits(p - bf16_to_f32(hi)) : hi;
+}
+
 __device__ __forceinline__ uint16_t factorB_bits(const Factors &f, int n, int jj)
 {
     if (jj >= f.r_eff || n >= f.N) return 0;

@@ -22,9 +22,18 @@ struct MatmulProblem {
     bool f32fact, f32out;
 };
 
-// Bytes of fp32 workspace the decode path needs for this problem (0 if none).
+// The front of the per-device workspace is reserved for arrival tickets (always zero between calls).
+constexpr size_t kTicketBytes = 16384;
+
+// Small-M path, ranks up to 128 contraction columns (lords_decode.hip).  The workspace holds
+// the arrival tickets (zero when handed over, left at zero) followed by fp32 partial sums.
+bool decode_fast_supported(const MatmulProblem &p);
+size_t decode_fast_workspace_bytes(const MatmulProblem &p);
+hipError_t launch_decode_fast(const MatmulProblem &p, void *workspace, hipStream_t st);
+
+// Small-M path for any rank (lords_fused.hip): K split over workgroups, partial sums added
+// by a second kernel.  `workspace` must hold decode_workspace_bytes(p) bytes.
 size_t decode_workspace_bytes(const MatmulProblem &p);
-// Small-M path.  `workspace` must hold decode_workspace_bytes(p) bytes (may be null if 0).
 hipError_t launch_decode(const MatmulProblem &p, void *workspace, hipStream_t st);
 // MFMA GEMM path for large M.
 hipError_t launch_prefill(const MatmulProblem &p, hipStream_t st);

@@ -31,66 +31,9 @@
 // 8..15).  v_fma_mix_f32 multiplies the fp16 level by the fp32 scale directly;
 // the product is rounded once to bf16 for the MFMA.  fp16 holds the levels of
 // the NF / INT tables to 2^-12 relative; levels must lie within fp16 range.
-#include "lords_device.h"
-#include "lords_launch.h"
+#include "lords_decode_common.h"
 
 namespace lords {
-
-constexpr int kNS = 8;       // max slabs (of 16 rows) per workgroup
-constexpr int kDepth = 3;    // slabs whose loads are in flight ahead of the one computed
-
-struct DecodeArgs {
-    const uint16_t *X;
-    const uint8_t *codes;
-    const float *codebook;
-    Factors f;
-    void *Y;
-    float *partial;        // [splits][M][N] fp32, used when splits > 1
-    unsigned *counters;    // one ticket per slab chunk (gridDim.x), zero between calls
-    int M, N, K;
-    int y_f32;
-    int row_bytes;
-    int nslabs;            // ceil(N / 16)
-    int ns;                // slabs per workgroup, <= kNS
-    int splits;            // gridDim.z
-    int b_vec_ok;
-};
-
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4_t;
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-
-template <int AST>
-__device__ __forceinline__ bf16x8 tr_read_pair_d(const uint16_t *tile, int row, int col)
-{
-    const uint16_t *p0 = tile + row * AST + col;
-    const uint16_t *p1 = p0 + 4 * AST;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p0);
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p1);
-    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
-    s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, both);
-}
-
-// LDS byte address of the table entry of code pair p (codes 2p, 2p+1) of a 32-code group.
-template <int BITS>
-__device__ __forceinline__ uint32_t pair_addr(const uint32_t (&w)[BITS], int p, uint32_t laneoff)
-{
-    if (BITS == 4) {
-        // result byte1 = byte (p&3) of dword p>>2, byte0 = laneoff, bytes 2,3 = 0
-        return __builtin_amdgcn_perm(w[p >> 2], laneoff, 0x0C0C0000u | ((4u + (p & 3)) << 8));
-    }
-    const int o = 2 * BITS * p, d = o >> 5, s = o & 31;
-    uint32_t v = w[d] >> s;
-    if (s + 2 * BITS > 32) v |= w[(d + 1) < BITS ? d + 1 : d] << (32 - s);
-    return ((v & ((1u << (2 * BITS)) - 1u)) << 8) | laneoff;
-}
-
-__device__ __forceinline__ uint32_t lds_load_u32(uint32_t byte_addr)
-{
-    // The kernels below declare no static LDS, so their dynamic LDS starts at address 0 and
-    // a table offset is an LDS address.
-    return *reinterpret_cast<const __attribute__((address_space(3))) uint32_t *>((uintptr_t)byte_addr);
-}
 
 // M1 = true : one token.  The activations are folded into the A tile (A[j][k] * x[k], rounded
 //             to bf16) so the scale MFMAs deliver S[n][k] * x[k]; the product with the level
@@ -154,6 +97,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
         }
     };
 
+    LORDS_STAMP(0);
     // ---- 0. first loads of the row stream go out before any set-up --------------------------
 #pragma unroll
     for (int i = 0; i < kDepth; ++i) issue(i);
@@ -225,6 +169,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
         }
     }
 
+    LORDS_STAMP(1);
     // ---- 2. level table: entry idx = (code_hi << BITS) | code_lo, 64 copies ------------------
     __syncthreads();
     {
@@ -240,6 +185,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
     }
     __syncthreads();
 
+    LORDS_STAMP(2);
     // ---- 3. activations of this block: b-operands of the product MFMAs -----------------------
     bf16x8 Xop[M1 ? 1 : G][4];
     if (!M1) {
@@ -305,8 +251,10 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
         }
     }
 
+    LORDS_STAMP(3);
     // ---- 5. add the four column blocks of this workgroup (fixed order) -------------------------
     __syncthreads();                               // the table is dead from here on
+    LORDS_STAMP(4);
     if (M1) {
         float *red = reinterpret_cast<float *>(smem);  // [4][kNS][64]
 #pragma unroll
@@ -354,6 +302,7 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
         }
     }
 
+    LORDS_STAMP(5);
     // ---- 6. column blocks held by other workgroups: the last one to arrive adds them -----------
     if (a.splits > 1) {
         // The partial sums were written with device-coherent (write-through) stores, so waiting
@@ -382,7 +331,9 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
             }
         }
     }
+    LORDS_STAMP(6);
 }
+
 
 // ---------------------------------------------------------------------------------------------
 // host side

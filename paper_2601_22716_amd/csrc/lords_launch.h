@@ -25,6 +25,11 @@ struct MatmulProblem {
 // The front of the per-device workspace is reserved for arrival tickets (always zero between calls).
 constexpr size_t kTicketBytes = 16384;
 
+// One-token path (lords_decode_m1.hip); same workspace convention as below.
+bool decode_m1_supported(const MatmulProblem &p);
+size_t decode_m1_workspace_bytes(const MatmulProblem &p);
+hipError_t launch_decode_m1(const MatmulProblem &p, void *workspace, hipStream_t st);
+
 // Small-M path, ranks up to 128 contraction columns (lords_decode.hip).  The workspace holds
 // the arrival tickets (zero when handed over, left at zero) followed by fp32 partial sums.
 bool decode_fast_supported(const MatmulProblem &p);

@@ -122,7 +122,7 @@ def bench_decode(args, L, li, torch):
                    "algorithmic_bytes_per_step": ab, "weight_sets": nsets, "hip_graph": not args.no_graph},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": DECODE_TRAFFIC_BYTES,
-                     "kernel": "lords::fused_kernel<4,1,...> (small-M path)", "us_per_launch": ev_per_launch * 1e6},
+                     "kernel": "lords::decode_m1_kernel<4,1,2,true>", "us_per_launch": ev_per_launch * 1e6},
     }
     return out, cs, sets[0], X, codebook
 
@@ -148,7 +148,7 @@ def bench_prefill(args, L, li, torch):
         "config": {"workload": f"prefill M={M}, N={cfg.N} K={cfg.K}, {cfg.bits}-bit codes, rank {cfg.r}, bf16 Y"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": PREFILL_TRAFFIC_BYTES,
-                     "kernel": "lords::fused_kernel<4,1,...> (MFMA GEMM path)", "us_per_launch": ev_per_launch * 1e6},
+                     "kernel": "lords::fused_kernel<4,1,2,8,true,false>", "us_per_launch": ev_per_launch * 1e6},
     }
 
 

@@ -141,7 +141,8 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook, con
         else if (fast) e = lords::launch_decode_fast(p, ws, (hipStream_t)stream);
         else e = lords::launch_decode(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream);
     } else {
-        e = lords::launch_prefill(p, (hipStream_t)stream);
+        e = lords::prefill_fast_supported(p) ? lords::launch_prefill_fast(p, (hipStream_t)stream)
+                                             : lords::launch_prefill(p, (hipStream_t)stream);
     }
     return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
 }

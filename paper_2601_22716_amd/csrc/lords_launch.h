@@ -40,7 +40,10 @@ hipError_t launch_decode_fast(const MatmulProblem &p, void *workspace, hipStream
 // by a second kernel.  `workspace` must hold decode_workspace_bytes(p) bytes.
 size_t decode_workspace_bytes(const MatmulProblem &p);
 hipError_t launch_decode(const MatmulProblem &p, void *workspace, hipStream_t st);
-// MFMA GEMM path for large M.
+// MFMA GEMM path for large M: bf16 factors up to 128 rank columns (lords_prefill.hip) ...
+bool prefill_fast_supported(const MatmulProblem &p);
+hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st);
+// ... and the general variant (fp32 factors, any rank; lords_fused.hip).
 hipError_t launch_prefill(const MatmulProblem &p, hipStream_t st);
 
 }  // namespace lords

@@ -1,0 +1,330 @@
+// Large-M (prefill) kernel of  Y = X (C[Q] (.) (B A))^T  on gfx950: a bf16 MFMA GEMM whose weight
+// operand is dequantised on the fly and never leaves the registers.
+//
+// Tiling.  A workgroup (4 waves, one per SIMD) owns a 256-row x BM-token tile of Y (BM = 256, or
+// 128 for padded ranks above 32) and walks K in tiles of 128 columns.  Wave w owns rows
+// 64w .. 64w+63 (four 16-row slabs) and ALL tokens of the tile, so every weight is dequantised by
+// exactly one wave and reused for BM tokens; its accumulators (4 slabs x BM/16 token blocks x 4
+// registers) stay in registers over the whole K range.
+//
+// Per K tile the X tile (BM x 128 bf16) and the A tile (padded rank x 128 bf16) are brought from
+// global memory straight into LDS (global_load_lds_dwordx4, no registers), double-buffered, one
+// barrier per tile.  Both tiles are row-major with the 16-byte chunks of a row XOR-swizzled by the
+// row number (slot = chunk ^ (row & 15)), which makes the b-operand reads of X (ds_read_b128) and
+// the transposing reads of A (ds_read_b64_tr_b16) bank-conflict free.
+//
+// Lane mapping as in the decode kernels (v_mfma_f32_16x16x32_bf16, lane l = (c = l%16, g = l/16)):
+// the lane holds the 32 codes of row n0+c at columns kb + 32g ..; scale MFMA t gives it the scales
+// of codes 4t..4t+3; product MFMA u contracts columns 32g + 8u .. +8 with
+// a-operand = the lane's 8 dequantised weights and b-operand = X[token c][same 8 columns].
+// A K tile is processed in four stages u = 0..3 (scale MFMAs 2u, 2u+1 -> dequantise 8 weights per
+// slab -> BM/16 x 4 product MFMAs), written so that stage u+1's dequantisation can be scheduled
+// under stage u's product MFMAs.
+//
+// Level look-up: two codes index an LDS table of fp16 pairs, 8 copies (address =
+// index*32 + (lane%8)*4); v_fma_mix_f32 multiplies fp16 level by fp32 scale; one rounding to bf16.
+#include "lords_decode_common.h"
+
+namespace lords {
+
+struct PrefillArgs {
+    const uint16_t *X;
+    const uint8_t *codes;
+    const float *codebook;
+    const uint16_t *B;     // N x r bf16
+    const uint16_t *A;     // r x K bf16
+    void *Y;
+    int M, N, K, r;
+    int y_f32;
+    int row_bytes;
+    int nt, mt;            // tiles along N and M
+    int ntiles_k;          // ceil(K / 128)
+};
+
+constexpr int kPfCopies = 8;
+
+__device__ __forceinline__ void lds_direct_16(const void *gsrc, void *lds_wave_base)
+{
+    // every active lane fetches 16 bytes from its own address; they land at lds_wave_base + 16*lane
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+template <int BITS>
+__device__ __forceinline__ uint32_t pair_index(const uint32_t (&w)[BITS], int p)
+{
+    const int o = 2 * BITS * p, d = o >> 5, s = o & 31;
+    uint32_t v = w[d] >> s;
+    if (s + 2 * BITS > 32) v |= w[(d + 1) < BITS ? d + 1 : d] << (32 - s);
+    return v & ((1u << (2 * BITS)) - 1u);
+}
+
+template <int BITS, int SS, int MB>
+__global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
+{
+    constexpr int R = 4, BM = 16 * MB, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
+    constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *Xs = smem;                                   // [2][BM][256 B]
+    unsigned char *As = smem + 2 * XBUF;                        // [2][RP][256 B]
+    uint32_t *lut = reinterpret_cast<uint32_t *>(smem + 2 * XBUF + 2 * ABUF);   // [NE][8]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int M = a.M, N = a.N, K = a.K;
+
+    // ---- tile of this workgroup: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
+    //      contiguous range of tiles (n fastest): its workgroups then share X panels in its L2 ----------
+    const int total = a.nt * a.mt;
+    const int per_xcd = (total + 7) / 8;
+    const int T = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per_xcd || T >= total) return;
+    const int m_blk = (T / a.nt) * BM, n_blk = (T % a.nt) * 256;
+    const int n_wave = n_blk + 64 * wave;
+
+    // ---- level table --------------------------------------------------------------------------------
+    for (int id = tid; id < NE * kPfCopies; id += 256) {
+        const int idx = id / kPfCopies;
+        f16x2 h;
+        h[0] = (_Float16)a.codebook[idx & (NL - 1)];
+        h[1] = (_Float16)a.codebook[idx >> BITS];
+        lut[id] = __builtin_bit_cast(uint32_t, h);
+    }
+    // ---- zero the A buffers once: rank rows >= r are never loaded and must read as zero --------------
+    for (int id = tid; id < 2 * ABUF / 16; id += 256) reinterpret_cast<u32x4 *>(As)[id] = u32x4{0u, 0u, 0u, 0u};
+    if (K & 127)                                               // ragged last K tile: stale X must at least be finite
+        for (int id = tid; id < 2 * XBUF / 16; id += 256) reinterpret_cast<u32x4 *>(Xs)[id] = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+
+    // ---- B operands of the scale MFMAs: rows n_wave + 16 rho + c, rank entries 32 s + 8 g .. ----------
+    bf16x8 Bop[R][SS];
+#pragma unroll
+    for (int rho = 0; rho < R; ++rho) {
+        const int n = n_wave + 16 * rho + c;
+#pragma unroll
+        for (int s = 0; s < SS; ++s) {
+            const int jj0 = 32 * s + 8 * g;
+            typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+            s16x8 t;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] = 0;
+            if (n < N) {
+                if ((a.r & 7) == 0) {
+                    if (jj0 + 8 <= a.r) t = *reinterpret_cast<const s16x8 *>(a.B + (size_t)n * a.r + jj0);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (jj0 + e < a.r) t[e] = (short)a.B[(size_t)n * a.r + jj0 + e];
+                }
+            }
+            Bop[rho][s] = __builtin_bit_cast(bf16x8, t);
+        }
+    }
+
+    // ---- staging of one K tile into buffer p (direct to LDS) and of its codes into registers ---------
+    auto stage = [&](int kt, int p) {
+        const int kb = kt * 128;
+        // X tile: BM rows x 16 chunks; one wave instruction covers 4 rows
+#pragma unroll
+        for (int q = 0; q < BM / 16; ++q) {
+            const int ii = wave + 4 * q;                      // 4-row group
+            const int m = 4 * ii + (lane >> 4), kc = (lane & 15) ^ (m & 15), k = kb + 8 * kc;
+            if (m_blk + m < M && k < K)
+                lds_direct_16(a.X + (size_t)(m_blk + m) * K + k, Xs + p * XBUF + ii * 1024);
+        }
+        // A tile: RP rows x 16 chunks
+#pragma unroll
+        for (int q = 0; q < RP / 16; ++q) {
+            const int ii = wave + 4 * q;
+            const int j = 4 * ii + (lane >> 4), kc = (lane & 15) ^ (j & 15), k = kb + 8 * kc;
+            if (j < a.r && k < K) {
+                lds_direct_16(a.A + (size_t)j * K + k, As + p * ABUF + ii * 1024);
+            } else if (kb + 128 > K && j < a.r) {
+                // ragged last tile: columns >= K of a live rank row must read as zero
+                *reinterpret_cast<u32x4 *>(As + p * ABUF + ii * 1024 + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+    };
+    const int ngroups = K >> 5;
+    auto load_codes = [&](int kt, uint32_t (&cw)[R][BITS]) {
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho) {
+            const int n = min(n_wave + 16 * rho + c, N - 1);
+            const int grp = min(kt * 4 + g, ngroups - 1);
+            load_group<BITS>(a.codes + (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS), cw[rho]);
+        }
+    };
+
+    f32x4 acc[R][MB];
+#pragma unroll
+    for (int rho = 0; rho < R; ++rho)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[rho][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    uint32_t cw[R][BITS], cwn[R][BITS];
+    stage(0, 0);
+    load_codes(0, cw);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+
+    // per-lane LDS offsets
+    uint32_t xoff[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) xoff[u] = (uint32_t)(c * 256 + (((4 * g + u) ^ c) * 16));
+    const uint32_t lutoff = (uint32_t)(2 * XBUF + 2 * ABUF) + (uint32_t)(lane & 7) * 4u;
+
+    for (int kt = 0; kt < a.ntiles_k; ++kt) {
+        const int p = kt & 1;
+        if (kt + 1 < a.ntiles_k) {
+            stage(kt + 1, p ^ 1);
+            load_codes(kt + 1, cwn);
+        }
+        const unsigned char *Xp = Xs + p * XBUF;
+        const unsigned char *Ap = As + p * ABUF;
+
+        // a-operands of the scale MFMAs for this tile: A columns transposed out of LDS
+        bf16x8 Aop[SS][8];
+#pragma unroll
+        for (int s = 0; s < SS; ++s)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+                const int row0 = 32 * s + 8 * g + (c >> 2);                 // +4 for the second half
+                const int kc = 4 * (c & 3) + (t >> 1);
+                const unsigned char *p0 = Ap + row0 * 256 + ((kc ^ (row0 & 15)) * 16) + (t & 1) * 8;
+                const unsigned char *p1 = Ap + (row0 + 4) * 256 + ((kc ^ ((row0 + 4) & 15)) * 16) + (t & 1) * 8;
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p0);
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p1);
+                Aop[s][t] = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            }
+
+        auto dequant_stage = [&](int u, bf16x8 (&W)[R]) {
+#pragma unroll
+            for (int rho = 0; rho < R; ++rho) {
+                f32x4 S0 = f32x4{0.f, 0.f, 0.f, 0.f}, S1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < SS; ++s) {
+                    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop[s][2 * u], Bop[rho][s], S0, 0, 0, 0);
+                    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop[s][2 * u + 1], Bop[rho][s], S1, 0, 0, 0);
+                }
+#pragma unroll
+                for (int pp = 0; pp < 4; ++pp) {
+                    const uint32_t idx = pair_index<BITS>(cw[rho], 4 * u + pp);
+                    const f16x2 h = __builtin_bit_cast(f16x2, lds_load_u32((idx << 5) + lutoff));
+                    const float s0 = pp < 2 ? S0[2 * pp] : S1[2 * pp - 4];
+                    const float s1 = pp < 2 ? S0[2 * pp + 1] : S1[2 * pp - 3];
+                    W[rho][2 * pp] = (__bf16)__builtin_fmaf((float)h[0], s0, 0.0f);
+                    W[rho][2 * pp + 1] = (__bf16)__builtin_fmaf((float)h[1], s1, 0.0f);
+                }
+            }
+        };
+
+        bf16x8 Wcur[R], Wnext[R];
+        dequant_stage(0, Wcur);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u + 1 < 4) dequant_stage(u + 1, Wnext);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const bf16x8 Xop = *reinterpret_cast<const bf16x8 *>(Xp + mb * 4096 + xoff[u]);
+#pragma unroll
+                for (int rho = 0; rho < R; ++rho)
+                    acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wcur[rho], Xop, acc[rho][mb], 0, 0, 0);
+            }
+#pragma unroll
+            for (int rho = 0; rho < R; ++rho) Wcur[rho] = Wnext[rho];
+        }
+
+        __builtin_amdgcn_s_waitcnt(0);          // the next tile has landed in LDS, the next codes in registers
+        __syncthreads();
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho)
+#pragma unroll
+            for (int q = 0; q < BITS; ++q) cw[rho][q] = cwn[rho][q];
+    }
+
+    // ---- epilogue: lane (c,g) holds token 16 mb + c, rows 16 rho + 4 g + {0..3} ------------------------
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int m = m_blk + 16 * mb + c;
+        if (m >= M) continue;
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho) {
+            const int n = n_wave + 16 * rho + 4 * g;
+            if (n + 3 < N && (N & 3) == 0) {
+                if (a.y_f32) {
+                    *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.Y) + (size_t)m * N + n) = acc[rho][mb];
+                } else {
+                    typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+                    u32x2 o;
+                    o[0] = (uint32_t)bf16_bits(acc[rho][mb][0]) | ((uint32_t)bf16_bits(acc[rho][mb][1]) << 16);
+                    o[1] = (uint32_t)bf16_bits(acc[rho][mb][2]) | ((uint32_t)bf16_bits(acc[rho][mb][3]) << 16);
+                    *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(a.Y) + (size_t)m * N + n) = o;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (n + e >= N) continue;
+                    if (a.y_f32) reinterpret_cast<float *>(a.Y)[(size_t)m * N + n + e] = acc[rho][mb][e];
+                    else reinterpret_cast<uint16_t *>(a.Y)[(size_t)m * N + n + e] = bf16_bits(acc[rho][mb][e]);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static int pf_ss(int r)
+{
+    const int rp = (r + 31) / 32;
+    return rp <= 1 ? 1 : rp <= 2 ? 2 : rp <= 4 ? 4 : 0;
+}
+
+bool prefill_fast_supported(const MatmulProblem &p) { return !p.f32fact && pf_ss(p.r) != 0; }
+
+template <int BITS, int SS, int MB>
+static hipError_t launch_pf_t(const PrefillArgs &a, int grid, hipStream_t st)
+{
+    const size_t smem = (size_t)2 * (16 * MB) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, MB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((prefill_kernel<BITS, SS, MB>), dim3(grid), dim3(256), smem, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
+{
+    const int ss = pf_ss(p.r);
+    const int BM = ss == 1 ? 256 : 128;
+    PrefillArgs a;
+    a.X = (const uint16_t *)p.X;
+    a.codes = (const uint8_t *)p.codes;
+    a.codebook = p.codebook;
+    a.B = (const uint16_t *)p.B;
+    a.A = (const uint16_t *)p.A;
+    a.Y = p.Y;
+    a.M = p.M; a.N = p.N; a.K = p.K; a.r = p.r;
+    a.y_f32 = p.f32out ? 1 : 0;
+    a.row_bytes = p.K / 8 * p.bits;
+    a.nt = (p.N + 255) / 256;
+    a.mt = (p.M + BM - 1) / BM;
+    a.ntiles_k = (p.K + 127) / 128;
+    const int total = a.nt * a.mt;
+    const int grid = ((total + 7) / 8) * 8;
+#define LORDS_PCASE(B_, S_, M_) \
+    if (p.bits == B_ && ss == S_) return launch_pf_t<B_, S_, M_>(a, grid, st);
+    LORDS_PCASE(2, 1, 16) LORDS_PCASE(2, 2, 8) LORDS_PCASE(2, 4, 8)
+    LORDS_PCASE(3, 1, 16) LORDS_PCASE(3, 2, 8) LORDS_PCASE(3, 4, 8)
+    LORDS_PCASE(4, 1, 16) LORDS_PCASE(4, 2, 8) LORDS_PCASE(4, 4, 8)
+#undef LORDS_PCASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace lords

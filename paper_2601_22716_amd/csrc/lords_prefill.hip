@@ -1,11 +1,14 @@
 // Large-M (prefill) kernel of  Y = X (C[Q] (.) (B A))^T  on gfx950: a bf16 MFMA GEMM whose weight
 // operand is dequantised on the fly and never leaves the registers.
 //
-// Tiling.  A workgroup (4 waves, one per SIMD) owns a 256-row x BM-token tile of Y (BM = 256, or
-// 128 for padded ranks above 32) and walks K in tiles of 128 columns.  Wave w owns rows
-// 64w .. 64w+63 (four 16-row slabs) and ALL tokens of the tile, so every weight is dequantised by
-// exactly one wave and reused for BM tokens; its accumulators (4 slabs x BM/16 token blocks x 4
-// registers) stay in registers over the whole K range.
+// Tiling.  A workgroup owns a 256-row x (128*WM)-token tile of Y and walks K in tiles of 128
+// columns.  It has 4*WM waves: wave (wn, wm) owns rows 64 wn .. 64 wn + 63 (four 16-row slabs) and
+// tokens 128 wm .. 128 wm + 127, so each dequantised weight is reused for 128 tokens from
+// registers; the accumulators (4 slabs x 8 token blocks x 4 registers) stay in registers over the
+// whole K range.  WM = 2 (8 waves, two per SIMD) for padded ranks up to 32: the two waves of a SIMD
+// then overlap one's look-ups and conversions with the other's MFMAs, and the kernel is compiled
+// for at most 256 registers so that every MFMA writes plain VGPRs (results of the scale MFMAs are
+// read by vector ALU instructions, which cannot read the accumulation registers).
 //
 // Per K tile the X tile (BM x 128 bf16) and the A tile (padded rank x 128 bf16) are brought from
 // global memory straight into LDS (global_load_lds_dwordx4, no registers), double-buffered, one
@@ -59,10 +62,10 @@ __device__ __forceinline__ uint32_t pair_index(const uint32_t (&w)[BITS], int p)
     return v & ((1u << (2 * BITS)) - 1u);
 }
 
-template <int BITS, int SS, int MB>
-__global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
+template <int BITS, int SS, int WM>
+__global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(PrefillArgs a)
 {
-    constexpr int R = 4, BM = 16 * MB, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
+    constexpr int R = 4, MB = 8, BM = 128 * WM, NT = 256 * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
     constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *Xs = smem;                                   // [2][BM][256 B]
@@ -80,10 +83,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
     const int T = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || T >= total) return;
     const int m_blk = (T / a.nt) * BM, n_blk = (T % a.nt) * 256;
-    const int n_wave = n_blk + 64 * wave;
+    const int wn = wave & 3, wm = wave >> 2;
+    const int n_wave = n_blk + 64 * wn;
+    const int m_wave = m_blk + 128 * wm;
 
     // ---- level table --------------------------------------------------------------------------------
-    for (int id = tid; id < NE * kPfCopies; id += 256) {
+    for (int id = tid; id < NE * kPfCopies; id += NT) {
         const int idx = id / kPfCopies;
         f16x2 h;
         h[0] = (_Float16)a.codebook[idx & (NL - 1)];
@@ -91,9 +96,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
         lut[id] = __builtin_bit_cast(uint32_t, h);
     }
     // ---- zero the A buffers once: rank rows >= r are never loaded and must read as zero --------------
-    for (int id = tid; id < 2 * ABUF / 16; id += 256) reinterpret_cast<u32x4 *>(As)[id] = u32x4{0u, 0u, 0u, 0u};
+    for (int id = tid; id < 2 * ABUF / 16; id += NT) reinterpret_cast<u32x4 *>(As)[id] = u32x4{0u, 0u, 0u, 0u};
     if (K & 127)                                               // ragged last K tile: stale X must at least be finite
-        for (int id = tid; id < 2 * XBUF / 16; id += 256) reinterpret_cast<u32x4 *>(Xs)[id] = u32x4{0u, 0u, 0u, 0u};
+        for (int id = tid; id < 2 * XBUF / 16; id += NT) reinterpret_cast<u32x4 *>(Xs)[id] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
 
     // ---- B operands of the scale MFMAs: rows n_wave + 16 rho + c, rank entries 32 s + 8 g .. ----------
@@ -122,26 +127,33 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
     }
 
     // ---- staging of one K tile into buffer p (direct to LDS) and of its codes into registers ---------
+    // The loops over the 4-row groups are kept rolled on purpose: unrolled, their loop-invariant
+    // row addresses get hoisted into dozens of registers that the accumulators need.
+    const int xm0 = 4 * wave + (lane >> 4);                   // first tile row this lane fetches; then +16*WM per step
+    const int xkc = (lane & 15) ^ (xm0 & 15);                 // its column chunk (same for every step)
     auto stage = [&](int kt, int p) {
         const int kb = kt * 128;
-        // X tile: BM rows x 16 chunks; one wave instruction covers 4 rows
-#pragma unroll
-        for (int q = 0; q < BM / 16; ++q) {
-            const int ii = wave + 4 * q;                      // 4-row group
-            const int m = 4 * ii + (lane >> 4), kc = (lane & 15) ^ (m & 15), k = kb + 8 * kc;
-            if (m_blk + m < M && k < K)
-                lds_direct_16(a.X + (size_t)(m_blk + m) * K + k, Xs + p * XBUF + ii * 1024);
+        {
+            const int k = min(kb + 8 * xkc, K - 8);            // ragged last tile: any finite data will do
+            unsigned char *dst = Xs + p * XBUF + wave * 1024;
+#pragma nounroll
+            for (int q = 0; q < BM / (16 * WM); ++q) {
+                const int m = min(m_blk + xm0 + 16 * WM * q, M - 1);   // rows >= M: a copy of the last row, never stored
+                lds_direct_16(a.X + (size_t)m * K + k, dst + q * (4096 * WM));
+            }
         }
-        // A tile: RP rows x 16 chunks
-#pragma unroll
-        for (int q = 0; q < RP / 16; ++q) {
-            const int ii = wave + 4 * q;
-            const int j = 4 * ii + (lane >> 4), kc = (lane & 15) ^ (j & 15), k = kb + 8 * kc;
-            if (j < a.r && k < K) {
-                lds_direct_16(a.A + (size_t)j * K + k, As + p * ABUF + ii * 1024);
-            } else if (kb + 128 > K && j < a.r) {
-                // ragged last tile: columns >= K of a live rank row must read as zero
-                *reinterpret_cast<u32x4 *>(As + p * ABUF + ii * 1024 + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
+        {
+            const int k = kb + 8 * xkc;
+            unsigned char *dst = As + p * ABUF + wave * 1024;
+#pragma nounroll
+            for (int q = 0; q < (RP + 16 * WM - 1) / (16 * WM); ++q) {
+                const int j = xm0 + 16 * WM * q;
+                if (j < a.r && k < K) {
+                    lds_direct_16(a.A + (size_t)j * K + k, dst + q * (4096 * WM));
+                } else if (kb + 128 > K && j < a.r) {
+                    // ragged last tile: columns >= K of a live rank row must read as zero
+                    *reinterpret_cast<u32x4 *>(dst + q * (4096 * WM) + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
+                }
             }
         }
     };
@@ -179,33 +191,32 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
             stage(kt + 1, p ^ 1);
             load_codes(kt + 1, cwn);
         }
-        const unsigned char *Xp = Xs + p * XBUF;
+        const unsigned char *Xp = Xs + p * XBUF + wm * (128 * 256);
         const unsigned char *Ap = As + p * ABUF;
 
-        // a-operands of the scale MFMAs for this tile: A columns transposed out of LDS
-        bf16x8 Aop[SS][8];
-#pragma unroll
-        for (int s = 0; s < SS; ++s)
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
-                const int row0 = 32 * s + 8 * g + (c >> 2);                 // +4 for the second half
-                const int kc = 4 * (c & 3) + (t >> 1);
-                const unsigned char *p0 = Ap + row0 * 256 + ((kc ^ (row0 & 15)) * 16) + (t & 1) * 8;
-                const unsigned char *p1 = Ap + (row0 + 4) * 256 + ((kc ^ ((row0 + 4) & 15)) * 16) + (t & 1) * 8;
-                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p0);
-                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p1);
-                Aop[s][t] = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
+        // a-operand of scale MFMA t: 8 rank entries of 16 A columns, transposed out of LDS
+        auto read_Aop = [&](int s, int t) -> bf16x8 {
+            typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+            const int row0 = 32 * s + 8 * g + (c >> 2);                 // +4 for the second half
+            const int kc = 4 * (c & 3) + (t >> 1);
+            const unsigned char *p0 = Ap + row0 * 256 + ((kc ^ (row0 & 15)) * 16) + (t & 1) * 8;
+            const unsigned char *p1 = Ap + (row0 + 4) * 256 + ((kc ^ ((row0 + 4) & 15)) * 16) + (t & 1) * 8;
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p0);
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p1);
+            return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
 
         auto dequant_stage = [&](int u, bf16x8 (&W)[R]) {
+            bf16x8 Aop0[SS], Aop1[SS];
+#pragma unroll
+            for (int s = 0; s < SS; ++s) { Aop0[s] = read_Aop(s, 2 * u); Aop1[s] = read_Aop(s, 2 * u + 1); }
 #pragma unroll
             for (int rho = 0; rho < R; ++rho) {
                 f32x4 S0 = f32x4{0.f, 0.f, 0.f, 0.f}, S1 = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int s = 0; s < SS; ++s) {
-                    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop[s][2 * u], Bop[rho][s], S0, 0, 0, 0);
-                    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop[s][2 * u + 1], Bop[rho][s], S1, 0, 0, 0);
+                    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop0[s], Bop[rho][s], S0, 0, 0, 0);
+                    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop1[s], Bop[rho][s], S1, 0, 0, 0);
                 }
 #pragma unroll
                 for (int pp = 0; pp < 4; ++pp) {
@@ -219,20 +230,17 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
             }
         };
 
-        bf16x8 Wcur[R], Wnext[R];
-        dequant_stage(0, Wcur);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (u + 1 < 4) dequant_stage(u + 1, Wnext);
+            bf16x8 W[R];
+            dequant_stage(u, W);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 const bf16x8 Xop = *reinterpret_cast<const bf16x8 *>(Xp + mb * 4096 + xoff[u]);
 #pragma unroll
                 for (int rho = 0; rho < R; ++rho)
-                    acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wcur[rho], Xop, acc[rho][mb], 0, 0, 0);
+                    acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W[rho], Xop, acc[rho][mb], 0, 0, 0);
             }
-#pragma unroll
-            for (int rho = 0; rho < R; ++rho) Wcur[rho] = Wnext[rho];
         }
 
         __builtin_amdgcn_s_waitcnt(0);          // the next tile has landed in LDS, the next codes in registers
@@ -246,7 +254,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PrefillArgs a)
     // ---- epilogue: lane (c,g) holds token 16 mb + c, rows 16 rho + 4 g + {0..3} ------------------------
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        const int m = m_blk + 16 * mb + c;
+        const int m = m_wave + 16 * mb + c;
         if (m >= M) continue;
 #pragma unroll
         for (int rho = 0; rho < R; ++rho) {
@@ -284,18 +292,18 @@ static int pf_ss(int r)
 
 bool prefill_fast_supported(const MatmulProblem &p) { return !p.f32fact && pf_ss(p.r) != 0; }
 
-template <int BITS, int SS, int MB>
+template <int BITS, int SS, int WM>
 static hipError_t launch_pf_t(const PrefillArgs &a, int grid, hipStream_t st)
 {
-    const size_t smem = (size_t)2 * (16 * MB) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
+    const size_t smem = (size_t)2 * (128 * WM) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, MB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((prefill_kernel<BITS, SS, MB>), dim3(grid), dim3(256), smem, st, a);
+    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM>), dim3(grid), dim3(256 * WM), smem, st, a);
     return hipGetLastError();
 }
 
@@ -320,9 +328,9 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
     const int grid = ((total + 7) / 8) * 8;
 #define LORDS_PCASE(B_, S_, M_) \
     if (p.bits == B_ && ss == S_) return launch_pf_t<B_, S_, M_>(a, grid, st);
-    LORDS_PCASE(2, 1, 16) LORDS_PCASE(2, 2, 8) LORDS_PCASE(2, 4, 8)
-    LORDS_PCASE(3, 1, 16) LORDS_PCASE(3, 2, 8) LORDS_PCASE(3, 4, 8)
-    LORDS_PCASE(4, 1, 16) LORDS_PCASE(4, 2, 8) LORDS_PCASE(4, 4, 8)
+    LORDS_PCASE(2, 1, 2) LORDS_PCASE(2, 2, 1) LORDS_PCASE(2, 4, 1)
+    LORDS_PCASE(3, 1, 2) LORDS_PCASE(3, 2, 1) LORDS_PCASE(3, 4, 1)
+    LORDS_PCASE(4, 1, 2) LORDS_PCASE(4, 2, 1) LORDS_PCASE(4, 4, 1)
 #undef LORDS_PCASE
     return hipErrorInvalidValue;
 }

@@ -62,10 +62,10 @@ __device__ __forceinline__ uint32_t pair_index(const uint32_t (&w)[BITS], int p)
     return v & ((1u << (2 * BITS)) - 1u);
 }
 
-template <int BITS, int SS, int WM>
+template <int BITS, int SS, int WM, int R>
 __global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(PrefillArgs a)
 {
-    constexpr int R = 4, MB = 8, BM = 128 * WM, NT = 256 * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
+    constexpr int MB = 8, BN = 64 * R, BM = 128 * WM, NT = 256 * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
     constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *Xs = smem;                                   // [2][BM][256 B]
@@ -82,9 +82,9 @@ __global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int per_xcd = (total + 7) / 8;
     const int T = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || T >= total) return;
-    const int m_blk = (T / a.nt) * BM, n_blk = (T % a.nt) * 256;
+    const int m_blk = (T / a.nt) * BM, n_blk = (T % a.nt) * BN;
     const int wn = wave & 3, wm = wave >> 2;
-    const int n_wave = n_blk + 64 * wn;
+    const int n_wave = n_blk + 16 * R * wn;
     const int m_wave = m_blk + 128 * wm;
 
     // ---- level table --------------------------------------------------------------------------------
@@ -206,27 +206,45 @@ __global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))
             return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         };
 
+        // Stage u of the dequantisation, two slabs at a time.  The LDS reads of a pair of slabs
+        // (table entries, transposed A columns) are all issued before the first use, so that the
+        // wave pays two LDS round trips per pair rather than one per table entry.
         auto dequant_stage = [&](int u, bf16x8 (&W)[R]) {
             bf16x8 Aop0[SS], Aop1[SS];
 #pragma unroll
             for (int s = 0; s < SS; ++s) { Aop0[s] = read_Aop(s, 2 * u); Aop1[s] = read_Aop(s, 2 * u + 1); }
 #pragma unroll
-            for (int rho = 0; rho < R; ++rho) {
-                f32x4 S0 = f32x4{0.f, 0.f, 0.f, 0.f}, S1 = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int hp = 0; hp < R / 2; ++hp) {
+                uint32_t lv[2][4];
 #pragma unroll
-                for (int s = 0; s < SS; ++s) {
-                    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop0[s], Bop[rho][s], S0, 0, 0, 0);
-                    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop1[s], Bop[rho][s], S1, 0, 0, 0);
-                }
+                for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int pp = 0; pp < 4; ++pp) {
-                    const uint32_t idx = pair_index<BITS>(cw[rho], 4 * u + pp);
-                    const f16x2 h = __builtin_bit_cast(f16x2, lds_load_u32((idx << 5) + lutoff));
-                    const float s0 = pp < 2 ? S0[2 * pp] : S1[2 * pp - 4];
-                    const float s1 = pp < 2 ? S0[2 * pp + 1] : S1[2 * pp - 3];
-                    W[rho][2 * pp] = (__bf16)__builtin_fmaf((float)h[0], s0, 0.0f);
-                    W[rho][2 * pp + 1] = (__bf16)__builtin_fmaf((float)h[1], s1, 0.0f);
+                    for (int pp = 0; pp < 4; ++pp) {
+                        uint32_t idx = pair_index<BITS>(cw[2 * hp + q], 4 * u + pp);
+                        lv[q][pp] = lds_load_u32((idx << 5) + lutoff);
+                    }
+                f32x4 S0[2], S1[2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    S0[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    S1[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < SS; ++s) {
+                        S0[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop0[s], Bop[2 * hp + q][s], S0[q], 0, 0, 0);
+                        S1[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop1[s], Bop[2 * hp + q][s], S1[q], 0, 0, 0);
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int pp = 0; pp < 4; ++pp) {
+                        const f16x2 h = __builtin_bit_cast(f16x2, lv[q][pp]);
+                        const float s0 = pp < 2 ? S0[q][2 * pp] : S1[q][2 * pp - 4];
+                        const float s1 = pp < 2 ? S0[q][2 * pp + 1] : S1[q][2 * pp - 3];
+                        W[2 * hp + q][2 * pp] = (__bf16)__builtin_fmaf((float)h[0], s0, 0.0f);
+                        W[2 * hp + q][2 * pp + 1] = (__bf16)__builtin_fmaf((float)h[1], s1, 0.0f);
+                    }
             }
         };
 
@@ -236,7 +254,11 @@ __global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))
             dequant_stage(u, W);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
+#ifdef LORDS_EXP_NOXCONF
+                const bf16x8 Xop = *reinterpret_cast<const bf16x8 *>(Xp + mb * 4096 + lane * 16 + u * 1024);   // experiment only
+#else
                 const bf16x8 Xop = *reinterpret_cast<const bf16x8 *>(Xp + mb * 4096 + xoff[u]);
+#endif
 #pragma unroll
                 for (int rho = 0; rho < R; ++rho)
                     acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W[rho], Xop, acc[rho][mb], 0, 0, 0);
@@ -292,25 +314,30 @@ static int pf_ss(int r)
 
 bool prefill_fast_supported(const MatmulProblem &p) { return !p.f32fact && pf_ss(p.r) != 0; }
 
-template <int BITS, int SS, int WM>
+template <int BITS, int SS, int WM, int R>
 static hipError_t launch_pf_t(const PrefillArgs &a, int grid, hipStream_t st)
 {
     const size_t smem = (size_t)2 * (128 * WM) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM, R>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM>), dim3(grid), dim3(256 * WM), smem, st, a);
+    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM, R>), dim3(grid), dim3(256 * WM), smem, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
 {
     const int ss = pf_ss(p.r);
-    const int BM = ss == 1 ? 256 : 128;
+    const int wm = ss == 1 ? 2 : 1;
+    const int BM = 128 * wm;
+    // Four slabs per wave (256-row tiles) when that still gives every CU a tile and the B operands
+    // fit the register budget; two slabs (128-row tiles) otherwise.
+    const int mt = (p.M + BM - 1) / BM;
+    const int R = (ss == 1 && (long)((p.N + 255) / 256) * mt >= 224) ? 4 : 2;
     PrefillArgs a;
     a.X = (const uint16_t *)p.X;
     a.codes = (const uint8_t *)p.codes;
@@ -321,13 +348,14 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
     a.M = p.M; a.N = p.N; a.K = p.K; a.r = p.r;
     a.y_f32 = p.f32out ? 1 : 0;
     a.row_bytes = p.K / 8 * p.bits;
-    a.nt = (p.N + 255) / 256;
-    a.mt = (p.M + BM - 1) / BM;
+    a.nt = (p.N + 64 * R - 1) / (64 * R);
+    a.mt = mt;
     a.ntiles_k = (p.K + 127) / 128;
     const int total = a.nt * a.mt;
     const int grid = ((total + 7) / 8) * 8;
-#define LORDS_PCASE(B_, S_, M_) \
-    if (p.bits == B_ && ss == S_) return launch_pf_t<B_, S_, M_>(a, grid, st);
+#define LORDS_PCASE(B_, S_, M_)                                              \
+    if (p.bits == B_ && ss == S_)                                            \
+        return R == 4 ? launch_pf_t<B_, S_, M_, (S_ == 1 ? 4 : 2)>(a, grid, st) : launch_pf_t<B_, S_, M_, 2>(a, grid, st);
     LORDS_PCASE(2, 1, 2) LORDS_PCASE(2, 2, 1) LORDS_PCASE(2, 4, 1)
     LORDS_PCASE(3, 1, 2) LORDS_PCASE(3, 2, 1) LORDS_PCASE(3, 4, 1)
     LORDS_PCASE(4, 1, 2) LORDS_PCASE(4, 2, 1) LORDS_PCASE(4, 4, 1)

@@ -126,7 +126,7 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook, con
     if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
 
     lords::MatmulProblem p{X, codes, codebook, B, A, Y, M, N, K, r, bits, f32fact, y_dtype == LORDS_F32};
-    if (path == LORDS_PATH_AUTO) path = (M <= 16) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL;
+    if (path == LORDS_PATH_AUTO) path = (M <= 32) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL;   // measured cross-over
     hipError_t e;
     if (path == LORDS_PATH_DECODE) {
         void *ws = nullptr;

@@ -93,21 +93,20 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
             Bop[i][s] = __builtin_bit_cast(bf16x8, t);
         }
     };
-    // ---- 0. the first loads of the row stream go out before any set-up --------------------------
-#pragma unroll
-    for (int i = 0; i < kDepth; ++i) issue(i);
-    __builtin_amdgcn_sched_barrier(0);
-
     LORDS_STAMP_WG(0);
     LORDS_STAMP_ALL(8, atomicMin);
     LORDS_STAMP_ALL(9, atomicMax);
-    // ---- 1. the A tile of this column block, activations folded in ----------------------------
+    // ---- 1. set-up loads (A tile of this column block, activations, levels: all L2-resident) go
+    //         out FIRST, the first slabs of the row stream (HBM) right behind them.  A wave's loads
+    //         return in order, so the other way round the set-up would wait for HBM. --------------
+    constexpr int NCH = SS * 32 * CPR / kM1Threads;           // 16-byte chunks of the A tile per thread
+    constexpr int NIT = (NE * 16 + kM1Threads - 1) / kM1Threads;
+    const int kc = tid % CPR, k0 = kb + 8 * kc;               // the thread's column chunk is fixed
+    u32x4 xv = u32x4{0u, 0u, 0u, 0u};
+    u32x4 tmp[NCH];
+    float lo[NIT], hi[NIT];
     if (!a.f.f32) {
-        constexpr int NCH = SS * 32 * CPR / kM1Threads;       // 16-byte chunks per thread
-        const int kc = tid % CPR, k0 = kb + 8 * kc;           // the thread's column chunk is fixed
-        u32x4 xv = u32x4{0u, 0u, 0u, 0u};
         if (k0 < K) xv = *reinterpret_cast<const u32x4 *>(a.X + k0);
-        u32x4 tmp[NCH];
 #pragma unroll
         for (int q = 0; q < NCH; ++q) {
             const int jj = (tid + kM1Threads * q) / CPR;
@@ -115,15 +114,33 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
             if (jj < a.f.r && k0 < K)
                 tmp[q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.f.A) + (size_t)jj * K + k0);
         }
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int id = tid + kM1Threads * it, idx = (id >> 4) & (NE - 1);
+        lo[it] = a.codebook[idx & (NL - 1)];
+        hi[it] = a.codebook[idx >> BITS];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#ifdef LORDS_M1_SETUP_FIRST
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+#pragma unroll
+    for (int i = 0; i < kDepth; ++i) issue(i);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- 2. the A tile, activations folded in: A[j][k] * x[k] rounded to bf16 ------------------
+    if (!a.f.f32) {
 #pragma unroll
         for (int q = 0; q < NCH; ++q) {
             const int jj = (tid + kM1Threads * q) / CPR;
             u32x4 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float lo = __builtin_bit_cast(float, tmp[q][e] << 16) * __builtin_bit_cast(float, xv[e] << 16);
-                const float hi = __builtin_bit_cast(float, tmp[q][e] & 0xFFFF0000u) * __builtin_bit_cast(float, xv[e] & 0xFFFF0000u);
-                o[e] = (uint32_t)bf16_bits(lo) | ((uint32_t)bf16_bits(hi) << 16);
+                const float l = __builtin_bit_cast(float, tmp[q][e] << 16) * __builtin_bit_cast(float, xv[e] << 16);
+                const float h = __builtin_bit_cast(float, tmp[q][e] & 0xFFFF0000u) * __builtin_bit_cast(float, xv[e] & 0xFFFF0000u);
+                o[e] = (uint32_t)bf16_bits(l) | ((uint32_t)bf16_bits(h) << 16);
             }
             *reinterpret_cast<u32x4 *>(As + jj * AST + 8 * kc) = o;
         }
@@ -134,17 +151,9 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
             As[jj * AST + kk] = factorAx_bits(a.f, jj, kb + kk, x);
         }
     }
-    // ---- 2. level table: entry idx = (code_hi << BITS) | code_lo, one dword column per lane ----
+    // ---- 3. level table: entry idx = (code_hi << BITS) | code_lo, one dword column per lane ----
     {
         uint32_t *lut32 = reinterpret_cast<uint32_t *>(smem);
-        constexpr int NIT = (NE * 16 + kM1Threads - 1) / kM1Threads;
-        float lo[NIT], hi[NIT];
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int id = tid + kM1Threads * it, idx = (id >> 4) & (NE - 1);
-            lo[it] = a.codebook[idx & (NL - 1)];
-            hi[it] = a.codebook[idx >> BITS];
-        }
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int id = tid + kM1Threads * it, idx = id >> 4, q = id & 15;
@@ -219,13 +228,19 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
         LORDS_STAMP(3);
     LORDS_STAMP_WG(3);
 
-        // ---- 4. add the four lanes of each row, hand the row sums over ---------------------------
+        // ---- 4. add the four lanes of each row (two cross-lane steps, each issued for all slabs
+        //         before its results are used), hand the row sums over -------------------------------
+        float t16[kNS];
+#pragma unroll
+        for (int i = 0; i < kNS; ++i) t16[i] = __shfl_xor(acc1[i], 16);
+#pragma unroll
+        for (int i = 0; i < kNS; ++i) acc1[i] += t16[i];
+#pragma unroll
+        for (int i = 0; i < kNS; ++i) t16[i] = __shfl_xor(acc1[i], 32);
 #pragma unroll
         for (int i = 0; i < kNS; ++i) {
             if (i < nsw) {
-                float v = acc1[i];
-                v += __shfl_xor(v, 16);
-                v += __shfl_xor(v, 32);
+                const float v = acc1[i] + t16[i];
                 const int n = (slab0 + i) * 16 + c;
                 if (g == 0 && n < N) {
                     if (a.kblocks > 1)

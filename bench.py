@@ -32,9 +32,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, vendor figure
 COLD_BYTES = 600e6             # rotate through at least this many weight bytes
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); None = not measured
-DECODE_TRAFFIC_BYTES = None
-PREFILL_TRAFFIC_BYTES = None
+# HBM bytes per launch: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE readings (KiB per dispatch) of these two
+# kernels, each scaled by what the same counter reads for a plain 256 MiB -> 256 MiB elementwise kernel
+# (--calibrate-copy): FETCH_SIZE x 1.9998, WRITE_SIZE x 1.0.  The summary is under profiles/.
+DECODE_TRAFFIC_BYTES = int((16748.1 * 1.9998 + 960.5) * 1024)
+PREFILL_TRAFFIC_BYTES = int((136892.5 * 1.9998 + 57348.3) * 1024)
 
 
 def algorithmic_bytes(M, N, K, r, bits, factor_bytes=2, y_bytes=4):
@@ -148,7 +150,7 @@ def bench_prefill(args, L, li, torch):
         "config": {"workload": f"prefill M={M}, N={cfg.N} K={cfg.K}, {cfg.bits}-bit codes, rank {cfg.r}, bf16 Y"},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": PREFILL_TRAFFIC_BYTES,
-                     "kernel": "lords::fused_kernel<4,1,2,8,true,false>", "us_per_launch": ev_per_launch * 1e6},
+                     "kernel": "lords::prefill_kernel<4,1,2,4>", "us_per_launch": ev_per_launch * 1e6},
     }
 
 
@@ -179,6 +181,9 @@ def main():
     ap.add_argument("--workload", choices=["decode", "prefill", "all"], default="all")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain elementwise kernel that reads and writes 256 MiB each (the known-size "
+                         "reference for scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are part of it)",
@@ -206,6 +211,14 @@ def main():
             line.update({k: p[k] for k in ("metric", "value", "unit", "steps", "ms_per_step", "config", "roofline")})
         else:
             line["prefill"] = p
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        line["calibration"] = {"kernel": "torch elementwise add, fp32", "read_bytes": src.numel() * 4,
+                               "write_bytes": dst.numel() * 4, "launches": 3}
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(li, ab)
     print(json.dumps(line))

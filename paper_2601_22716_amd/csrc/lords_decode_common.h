@@ -79,14 +79,8 @@ static __device__ unsigned long long lords_wg_times[4096][8];
     } while (0)
 #else
 #define LORDS_STAMP(k) do { } while (0)
-static __device__ unsigned long long lords_wg_times[4096][8];
-#define LORDS_STAMP_WG(k)                                                                          \
-    do {                                                                                           \
-        const unsigned wg_ = blockIdx.x + gridDim.x * blockIdx.z;                                  \
-        if (threadIdx.x == 0 && wg_ < 4096) lords_wg_times[wg_][k] = wall_clock64();               \
-    } while (0)
-#define LORDS_STAMP_ALL(k, op) do { } while (0)
 #define LORDS_STAMP_WG(k) do { } while (0)
+#define LORDS_STAMP_ALL(k, op) do { } while (0)
 #endif
 
 __device__ __forceinline__ uint32_t lds_load_u32(uint32_t byte_addr)

@@ -1,39 +1,54 @@
 // One-token (M = 1) decode kernel of  y = (C[Q] (.) (B A)) x  on gfx950: the GEMV.
 //
+// Arithmetic.  With one activation vector the scale never has to be formed per element:
+//      y[n] = sum_k C[q[n][k]] * (sum_j B[n][j] A[j][k]) * x[k]
+//           = sum_j B[n][j] * T[n][j],      T = C[Q] (A (.) x)^T        (Sec. 3.3, regrouped)
+// T is a dense N x K by K x r contraction, so it runs on the matrix cores: the b-operand is the
+// looked-up level of each code (bf16), the a-operand the A tile with the activation folded in
+// (A[j][k] * x[k], bf16; fp32 factors: the fp32 product split into a bf16 hi and a lo tile).
+// The only per-element vector work left is the table look-up itself; the B factor enters once
+// per row and rank entry, in fp32, on the fp32 accumulator.
+//
 // Work split.  A workgroup of eight waves owns ONE block of KT = 128*G columns and a chunk of
 // 8*ns slabs of 16 rows; wave w streams down slabs w*ns .. w*ns+ns-1 of the chunk.  Because the
-// eight waves share the column block, the A tile of the block is staged once per workgroup:
-// A[j][k] * x[k] (the activation folded in, rounded to bf16) goes row-major into LDS, and each
-// wave fetches its scale-MFMA a-operands from it with the transposing ds_read_b64_tr_b16 and
-// keeps them in registers for the whole row stream.  The scale MFMAs then deliver S[n][k]*x[k];
-// the lane multiplies by the level of its code (v_fma_mix_f32, fp16 level x fp32 scale) and
-// accumulates its partial dot product of row n0+c in fp32.  Nothing is rounded to bf16 after the
-// A tile.  At the end of a chunk the four lanes of a row are added with two cross-lane
-// shuffles and the column blocks (gridDim.z of them) meet in a workspace: device-coherent
-// stores, one arrival ticket per chunk, the last workgroup adds the blocks in increasing order,
-// so results are run-to-run identical.
+// eight waves share the column block, the folded A tile is staged once per workgroup, row-major
+// in LDS, with coalesced loads; each wave then reads its MFMA a-operands from it (lane (i, g)
+// needs eight consecutive columns of tile row i, the layout the MFMA wants) and keeps them in
+// registers for the whole row stream.  Memory instructions are the scarce resource of this
+// kernel (a wave-level load occupies the address unit for at least 16 cycles, far longer when
+// its lanes touch many cache lines), so every stream load is a full 16 bytes per lane: G loads
+// of codes and one of B per slab.
 //
-// Lane mapping and look-up table: as in lords_decode.hip (lane (c,g) holds the G*32 codes of
-// row n0+c at columns kb + 32*(G*g+v); scale MFMA t, accumulator i <-> code 4t+i).
+// Rank order.  Tile row i of a-operand tile t stands for rank entry j = QW*(i/4) + 4*t + i%4
+// (QW = rank entries per lane group), so that accumulator lane (c, g) ends up with T[n0+c][j]
+// for the CONTIGUOUS run j = QW*g .. QW*g+QW-1 and its share of B[n0+c][.] is one vector load.
+//
+// At the end of a chunk the four lanes of a row are added with two cross-lane steps and the
+// column blocks (gridDim.z of them) meet in a workspace: device-coherent stores, one arrival
+// ticket per chunk, the last workgroup adds the blocks in increasing order, so results are
+// run-to-run identical.
+//
+// Lane mapping and look-up table: lane (c, g) = (lane % 16, lane / 16) holds the G 32-code
+// groups of row n0+c at columns kb + 32*(G*g+v); MFMA (v, u) contracts codes 8u..8u+7 of group
+// v of all four lane groups.  Table entry (code_hi << BITS) | code_lo holds the two levels as a
+// bf16 pair, replicated once per lane (address = entry*256 + lane*4: no bank conflicts).
 #include "lords_decode_common.h"
 
 namespace lords {
 
-#ifndef LORDS_M1_WAVES
-#define LORDS_M1_WAVES 8
-#endif
-constexpr int kM1Waves = LORDS_M1_WAVES;
+constexpr int kM1Waves = 8;
 constexpr int kM1Threads = 64 * kM1Waves;
 
 struct M1Args {
     const uint16_t *X;
     const uint8_t *codes;
     const float *codebook;
-    Factors f;
+    const void *A;         // r x K
+    const void *B;         // N x r
     void *Y;
     float *partial;        // [kblocks][N] fp32, used when kblocks > 1
     unsigned *counters;    // one ticket per chunk, zero between calls
-    int N, K;
+    int N, K, r;
     int y_f32;
     int row_bytes;
     int nslabs;            // ceil(N / 16)
@@ -42,31 +57,37 @@ struct M1Args {
     int kblocks;           // gridDim.z
 };
 
-template <int BITS, int SS, int G, bool BVEC>
-__global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
+// BITS: code width.  JT: 16-row a-operand tiles (bf16 factors: one per 16 rank entries, 2 or 4;
+// fp32 factors: the hi tiles, then as many lo tiles).  G: 32-code groups per lane.  BVEC: the B
+// run of a lane can be read with 16-byte loads.  F32: fp32 factors.
+template <int BITS, int JT, int G, bool BVEC, bool F32>
+__global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_m1_kernel(M1Args a)
 {
     constexpr int KT = 128 * G, AST = KT + 8, NL = 1 << BITS, NE = 1 << (2 * BITS), CPR = KT / 8;
-    constexpr int LUT_BYTES = NE * 256, A_BYTES = SS * 32 * AST * 2;
+    constexpr int JR = F32 ? JT / 2 : JT;                   // tiles of the rank itself
+    constexpr int QW = 4 * JR;                              // rank entries per lane group
+    constexpr int BW = F32 ? QW : QW / 2;                   // dwords of B per lane and slab
+    constexpr int LUT_BYTES = NE * 256, A_BYTES = JT * 16 * AST * 2;
     extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t *As = reinterpret_cast<uint16_t *>(smem + LUT_BYTES);        // [SS*32][AST]
+    uint16_t *As = reinterpret_cast<uint16_t *>(smem + LUT_BYTES);        // [JT*16][AST]
     int *flag = reinterpret_cast<int *>(smem + LUT_BYTES + A_BYTES);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
     const int kb = blockIdx.z * KT;
-    const int N = a.N, K = a.K;
+    const int N = a.N, K = a.K, r = a.r;
     const uint32_t laneoff = (uint32_t)lane * 4u;
     const int ngroups = K >> 5;
 
-    LORDS_STAMP(0);
+    LORDS_STAMP_WG(0);
     // Loads of slab i of the current chunk, branch-free (addresses clamped into the arrays) so that
-    // they can run kDepth slabs ahead: codes of columns >= K meet zero scales, rank entries >= r of
-    // B meet zero rows of the A tile, rows >= N are dropped at the store.
+    // they can run kDepth slabs ahead: codes of columns >= K meet zero a-operands, rank entries
+    // >= r meet zero rows of the A tile (and are zeroed here), rows >= N are dropped at the store.
     int chunk = blockIdx.x;
     int slab0 = (chunk * kM1Waves + wave) * a.ns;                    // this wave's first slab
     uint32_t cw[kNS][G][BITS];
-    bf16x8 Bop[kNS][SS];
-    auto issue = [&](int i) {
+    uint32_t Bq[kNS][BW];
+    auto issue = [&](int i) __attribute__((always_inline)) {
         const int n = min((slab0 + i) * 16 + c, N - 1);
 #pragma unroll
         for (int v = 0; v < G; ++v) {
@@ -75,44 +96,50 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
         }
         if (BVEC) {
 #pragma unroll
-            for (int s = 0; s < SS; ++s) {
-                const int jj0 = 32 * s + 8 * g;
-                Bop[i][s] = *reinterpret_cast<const bf16x8 *>(
-                    reinterpret_cast<const uint16_t *>(a.f.B) + (size_t)n * a.f.r + (jj0 + 8 <= a.f.r ? jj0 : 0));
+            for (int h = 0; h < BW / 4; ++h) {
+                const int j0 = QW * g + (F32 ? 4 : 8) * h;
+                const int jc = j0 < r ? j0 : 0;
+                u32x4 t;
+                if (F32) t = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const float *>(a.B) + (size_t)n * r + jc);
+                else t = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.B) + (size_t)n * r + jc);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) Bq[i][4 * h + e] = t[e];      // (masked at use: a select here would wait for the load)
             }
         }
     };
-    auto gather_B = [&](int i) {
-        const int row = (slab0 + i) * 16 + c;
+    // B run of a lane when it cannot be read as vectors: entry by entry, zero beyond the rank
+    auto gather_B = [&](int i) __attribute__((always_inline)) {
+        const int n = min((slab0 + i) * 16 + c, N - 1);
+        uint32_t t[QW];
 #pragma unroll
-        for (int s = 0; s < SS; ++s) {
-            typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
-            s16x8 t;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) t[e] = (short)factorB_bits(a.f, row, 32 * s + 8 * g + e);
-            Bop[i][s] = __builtin_bit_cast(bf16x8, t);
+        for (int e = 0; e < QW; ++e) {
+            const int j = QW * g + e, jc = j < r ? j : 0;
+            const uint32_t raw = F32 ? reinterpret_cast<const uint32_t *>(a.B)[(size_t)n * r + jc]
+                                     : (uint32_t)reinterpret_cast<const uint16_t *>(a.B)[(size_t)n * r + jc];
+            t[e] = j < r ? raw : 0u;
         }
+#pragma unroll
+        for (int e = 0; e < BW; ++e) Bq[i][e] = F32 ? t[e % QW] : (t[(2 * e) % QW] | (t[(2 * e + 1) % QW] << 16));
     };
-    LORDS_STAMP_WG(0);
-    LORDS_STAMP_ALL(8, atomicMin);
-    LORDS_STAMP_ALL(9, atomicMax);
-    // ---- 1. set-up loads (A tile of this column block, activations, levels: all L2-resident) go
-    //         out FIRST, the first slabs of the row stream (HBM) right behind them.  A wave's loads
-    //         return in order, so the other way round the set-up would wait for HBM. --------------
-    constexpr int NCH = SS * 32 * CPR / kM1Threads;           // 16-byte chunks of the A tile per thread
+
+    // ---- 1. set-up loads (A tile of this column block, activations, levels) go out FIRST, the
+    //         first slabs of the row stream right behind them.  A wave's loads return in order,
+    //         so the other way round the set-up would wait for the stream. --------------------------
+    constexpr int NCH = JT * 16 * CPR / kM1Threads;           // 16-byte chunks of the A tile per thread
     constexpr int NIT = (NE * 16 + kM1Threads - 1) / kM1Threads;
     const int kc = tid % CPR, k0 = kb + 8 * kc;               // the thread's column chunk is fixed
     u32x4 xv = u32x4{0u, 0u, 0u, 0u};
-    u32x4 tmp[NCH];
+    u32x4 tmp[F32 ? 1 : NCH];
     float lo[NIT], hi[NIT];
-    if (!a.f.f32) {
+    if (!F32) {
         if (k0 < K) xv = *reinterpret_cast<const u32x4 *>(a.X + k0);
 #pragma unroll
         for (int q = 0; q < NCH; ++q) {
-            const int jj = (tid + kM1Threads * q) / CPR;
+            const int jj = (tid + kM1Threads * q) / CPR, t = jj >> 4, i = jj & 15;
+            const int j = QW * (i >> 2) + 4 * t + (i & 3);
             tmp[q] = u32x4{0u, 0u, 0u, 0u};
-            if (jj < a.f.r && k0 < K)
-                tmp[q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.f.A) + (size_t)jj * K + k0);
+            if (j < r && k0 < K)
+                tmp[q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.A) + (size_t)j * K + k0);
         }
     }
 #pragma unroll
@@ -122,16 +149,12 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
         hi[it] = a.codebook[idx >> BITS];
     }
     __builtin_amdgcn_sched_barrier(0);
-#ifdef LORDS_M1_SETUP_FIRST
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-#endif
 #pragma unroll
     for (int i = 0; i < kDepth; ++i) issue(i);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- 2. the A tile, activations folded in: A[j][k] * x[k] rounded to bf16 ------------------
-    if (!a.f.f32) {
+    if (!F32) {
 #pragma unroll
         for (int q = 0; q < NCH; ++q) {
             const int jj = (tid + kM1Threads * q) / CPR;
@@ -145,42 +168,43 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
             *reinterpret_cast<u32x4 *>(As + jj * AST + 8 * kc) = o;
         }
     } else {
-        for (int id = tid; id < SS * 32 * KT; id += kM1Threads) {
-            const int jj = id / KT, kk = id % KT;
-            const float x = (kb + kk < K) ? bf16_to_f32(a.X[kb + kk]) : 0.f;
-            As[jj * AST + kk] = factorAx_bits(a.f, jj, kb + kk, x);
+        // fp32 factors (not the fast case): the fp32 product, split into a bf16 hi and lo tile
+        for (int id = tid; id < JR * 16 * KT; id += kM1Threads) {
+            const int jj = id / KT, kk = id % KT, t = jj >> 4, i = jj & 15;
+            const int j = QW * (i >> 2) + 4 * t + (i & 3);
+            float p = 0.f;
+            if (j < r && kb + kk < K)
+                p = reinterpret_cast<const float *>(a.A)[(size_t)j * K + kb + kk] * bf16_to_f32(a.X[kb + kk]);
+            const uint16_t ph = bf16_bits(p);
+            As[jj * AST + kk] = ph;
+            As[(JR * 16 + jj) * AST + kk] = bf16_bits(p - bf16_to_f32(ph));
         }
     }
-    // ---- 3. level table: entry idx = (code_hi << BITS) | code_lo, one dword column per lane ----
+    // ---- 3. level table ------------------------------------------------------------------------
     {
         uint32_t *lut32 = reinterpret_cast<uint32_t *>(smem);
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int id = tid + kM1Threads * it, idx = id >> 4, q = id & 15;
             if (idx < NE) {
-                f16x2 h;
-                h[0] = (_Float16)lo[it];
-                h[1] = (_Float16)hi[it];
-                const uint32_t pv = __builtin_bit_cast(uint32_t, h);
+                const uint32_t pv = (uint32_t)bf16_bits(lo[it]) | ((uint32_t)bf16_bits(hi[it]) << 16);
                 *reinterpret_cast<u32x4 *>(lut32 + idx * 64 + 4 * q) = u32x4{pv, pv, pv, pv};
             }
         }
     }
     __syncthreads();
-    LORDS_STAMP(1);
     LORDS_STAMP_WG(1);
-    bf16x8 Aop[G][SS][8];
+    bf16x8 Aop[G][4][JT];
 #pragma unroll
-    for (int s = 0; s < SS; ++s)
+    for (int v = 0; v < G; ++v)
 #pragma unroll
-        for (int v = 0; v < G; ++v)
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-                Aop[v][s][t] = tr_read_pair_d<AST>(As, 32 * s + 8 * g + (c >> 2), 32 * (G * (c & 3) + v) + 4 * t);
-    LORDS_STAMP(2);
+            for (int t = 0; t < JT; ++t)
+                Aop[v][u][t] = *reinterpret_cast<const bf16x8 *>(As + (16 * t + c) * AST + 32 * (G * g + v) + 8 * u);
     LORDS_STAMP_WG(2);
 
-    // ---- 3. the row stream, chunk by chunk ------------------------------------------------------
+    // ---- 4. the row stream, chunk by chunk ------------------------------------------------------
     for (; chunk < a.nchunks; chunk += gridDim.x) {
         if (chunk != (int)blockIdx.x) {
             slab0 = (chunk * kM1Waves + wave) * a.ns;
@@ -189,58 +213,69 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
         }
         const int nsw = max(0, min(a.ns, a.nslabs - slab0));
 
-
-        float acc1[kNS];
+        float ysum[kNS];
 #pragma unroll
         for (int i = 0; i < kNS; ++i) {
-            acc1[i] = 0.f;
+            ysum[i] = 0.f;
             if (i < nsw) {
                 if (i + kDepth < kNS) issue(i + kDepth);
                 __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of this slab's arithmetic
                 if (!BVEC) gather_B(i);
-                float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;
+                // one accumulator per tile, first MFMA on a literal zero; the two tiles (and the
+                // other wave of the SIMD) hide the latency of the dependent chain
+                // one accumulator chain per (group, tile): independent chains keep the matrix pipe busy
+                f32x4 acc[G][JT];
 #pragma unroll
-                for (int v = 0; v < G; ++v) {
+                for (int u = 0; u < 4; ++u)
 #pragma unroll
-                    for (int hh = 0; hh < 2; ++hh) {       // half a group: scale MFMAs 4hh .. 4hh+3
-                        f32x4 S[4];
+                    for (int v = 0; v < G; ++v) {
+                        u32x4 w;
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) S[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        for (int d = 0; d < 4; ++d) w[d] = lds_load_u32(pair_addr<BITS>(cw[i][v], 4 * u + d, laneoff));
+                        const bf16x8 Wop = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
-                        for (int s = 0; s < SS; ++s)
-#pragma unroll
-                            for (int t = 0; t < 4; ++t)
-                                S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop[v][s][4 * hh + t], Bop[i][s], S[t], 0, 0, 0);
-#pragma unroll
-                        for (int pq = 0; pq < 8; ++pq) {   // code pairs 8hh .. 8hh+7 of the group
-                            const uint32_t ad = pair_addr<BITS>(cw[i][v], 8 * hh + pq, laneoff);
-                            const f16x2 h = __builtin_bit_cast(f16x2, lds_load_u32(ad));
-                            const float s0 = S[pq >> 1][(2 * pq) & 3], s1 = S[pq >> 1][(2 * pq + 1) & 3];
-                            if (pq & 1) { p2 = __builtin_fmaf((float)h[0], s0, p2); p3 = __builtin_fmaf((float)h[1], s1, p3); }
-                            else        { p0 = __builtin_fmaf((float)h[0], s0, p0); p1 = __builtin_fmaf((float)h[1], s1, p1); }
-                        }
+                        for (int t = 0; t < JT; ++t)
+                            acc[v][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop[v][u][t], Wop,
+                                                                                u == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[v][t], 0, 0, 0);
                     }
-                }
-                acc1[i] = (p0 + p1) + (p2 + p3);
+                // accumulator element e of tile t is T[n][QW*g + 4t + e]: weigh with the lane's B run
+                float y0 = 0.f, y1 = 0.f;
+#pragma unroll
+                for (int t = 0; t < JR; ++t)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float s = acc[0][t][e];
+                        if (G == 2) s += acc[G - 1][t][e];
+                        if (F32) {
+                            s += acc[0][JT - JR + t][e];
+                            if (G == 2) s += acc[G - 1][JT - JR + t][e];
+                        }
+                        const int q = 4 * t + e;                       // position in the lane's run
+                        const uint32_t raw = F32 ? Bq[i][q % BW] : ((q & 1) ? (Bq[i][(q >> 1) % BW] & 0xFFFF0000u) : (Bq[i][(q >> 1) % BW] << 16));
+                        float b = __builtin_bit_cast(float, raw);
+                        if (BVEC) b = (QW * g + (F32 ? 4 * t : 8 * (t >> 1))) < r ? b : 0.f;
+                        if (e & 1) y1 = __builtin_fmaf(s, b, y1);
+                        else y0 = __builtin_fmaf(s, b, y0);
+                    }
+                ysum[i] = y0 + y1;
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        LORDS_STAMP(3);
-    LORDS_STAMP_WG(3);
+        LORDS_STAMP_WG(3);
 
-        // ---- 4. add the four lanes of each row (two cross-lane steps, each issued for all slabs
+        // ---- 5. add the four lanes of each row (two cross-lane steps, each issued for all slabs
         //         before its results are used), hand the row sums over -------------------------------
         float t16[kNS];
 #pragma unroll
-        for (int i = 0; i < kNS; ++i) t16[i] = __shfl_xor(acc1[i], 16);
+        for (int i = 0; i < kNS; ++i) t16[i] = __shfl_xor(ysum[i], 16);
 #pragma unroll
-        for (int i = 0; i < kNS; ++i) acc1[i] += t16[i];
+        for (int i = 0; i < kNS; ++i) ysum[i] += t16[i];
 #pragma unroll
-        for (int i = 0; i < kNS; ++i) t16[i] = __shfl_xor(acc1[i], 32);
+        for (int i = 0; i < kNS; ++i) t16[i] = __shfl_xor(ysum[i], 32);
 #pragma unroll
         for (int i = 0; i < kNS; ++i) {
             if (i < nsw) {
-                const float v = acc1[i] + t16[i];
+                const float v = ysum[i] + t16[i];
                 const int n = (slab0 + i) * 16 + c;
                 if (g == 0 && n < N) {
                     if (a.kblocks > 1)
@@ -250,9 +285,8 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
                 }
             }
         }
-        LORDS_STAMP(4);
-    LORDS_STAMP_WG(4);
-        // ---- 5. other column blocks: the last workgroup to arrive adds them in order --------------
+        LORDS_STAMP_WG(4);
+        // ---- 6. other column blocks: the last workgroup to arrive adds them in order --------------
         if (a.kblocks > 1) {
             // The partial sums went out as device-coherent (write-through) stores: once they have
             // completed they are visible to every workgroup, without an L2 write-back or invalidate.
@@ -296,16 +330,13 @@ __global__ __launch_bounds__(kM1Threads) void decode_m1_kernel(M1Args a)
                 }
             }
         }
-        LORDS_STAMP(5);
-    LORDS_STAMP_WG(5);
+        LORDS_STAMP_WG(5);
     }
-    LORDS_STAMP(6);
     LORDS_STAMP_WG(6);
-    LORDS_STAMP_ALL(10, atomicMin);
-    LORDS_STAMP_ALL(11, atomicMax);
 }
 
 #ifdef LORDS_PHASE_TIMING
+// Development aid, never part of the shipped library: read back the time stamps.
 extern "C" int lords_debug_phase_times(unsigned long long *out)
 {
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(lords_phase_times), sizeof(unsigned long long) * 32);
@@ -318,7 +349,6 @@ extern "C" int lords_debug_reset()
 {
     unsigned long long init[32];
     for (int i = 0; i < 32; ++i) init[i] = 0ull;
-    init[16 + 8] = ~0ull; init[16 + 10] = ~0ull;
     return (int)hipMemcpyToSymbol(HIP_SYMBOL(lords_phase_times), init, sizeof(init));
 }
 #endif
@@ -327,21 +357,21 @@ extern "C" int lords_debug_reset()
 // host side
 // ---------------------------------------------------------------------------------------------
 struct M1Plan {
-    int ss, G, KT, kblocks, ns, nchunks, gx;
+    int jt, G, KT, kblocks, ns, nchunks, gx;
 };
 
-static int m1_ss(const MatmulProblem &p)
+// a-operand tiles: bf16 factors need ceil(r/16), fp32 factors twice that (hi and lo); 2 or 4 are built
+static int m1_jt(const MatmulProblem &p)
 {
-    const int r_eff = p.f32fact ? 3 * p.r : p.r;
-    const int rp = (r_eff + 31) / 32;
-    return rp <= 1 ? 1 : rp <= 2 ? 2 : rp <= 4 ? 4 : 0;
+    const int tiles = (p.r + 15) / 16 * (p.f32fact ? 2 : 1);
+    return tiles <= 2 ? 2 : tiles <= 4 ? 4 : 0;
 }
 
 static M1Plan m1_plan(const MatmulProblem &p)
 {
     M1Plan d;
-    d.ss = m1_ss(p);
-    d.G = d.ss == 1 ? 2 : 1;
+    d.jt = m1_jt(p);
+    d.G = d.jt == 2 ? 2 : 1;
     d.KT = 128 * d.G;
     d.kblocks = (p.K + d.KT - 1) / d.KT;
     const int nslabs = (p.N + 15) / 16;
@@ -358,7 +388,7 @@ static M1Plan m1_plan(const MatmulProblem &p)
 
 bool decode_m1_supported(const MatmulProblem &p)
 {
-    if (p.M != 1 || m1_ss(p) == 0) return false;
+    if (p.M != 1 || m1_jt(p) == 0) return false;
     const M1Plan d = m1_plan(p);
     return (size_t)d.nchunks * sizeof(unsigned) <= kTicketBytes && d.kblocks <= 65535;
 }
@@ -370,20 +400,27 @@ size_t decode_m1_workspace_bytes(const MatmulProblem &p)
     return kTicketBytes + (size_t)d.kblocks * p.N * sizeof(float);
 }
 
-template <int BITS, int SS, int G, bool BVEC>
+template <int BITS, int JT, int G, bool BVEC, bool F32>
 static hipError_t launch_m1_t(const M1Args &a, dim3 grid, hipStream_t st)
 {
     constexpr int KT = 128 * G, AST = KT + 8;
-    const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)SS * 32 * AST * 2 + 64;
+    const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)JT * 16 * AST * 2 + 64;
     static bool attr_set = false;
     if (!attr_set && smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_m1_kernel<BITS, SS, G, BVEC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_m1_kernel<BITS, JT, G, BVEC, F32>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((decode_m1_kernel<BITS, SS, G, BVEC>), grid, dim3(kM1Threads), smem, st, a);
+    hipLaunchKernelGGL((decode_m1_kernel<BITS, JT, G, BVEC, F32>), grid, dim3(kM1Threads), smem, st, a);
     return hipGetLastError();
+}
+
+template <int BITS, int JT, int G>
+static hipError_t launch_m1_b(const M1Args &a, dim3 grid, bool bvec, bool f32, hipStream_t st)
+{
+    if (f32) return bvec ? launch_m1_t<BITS, JT, G, true, true>(a, grid, st) : launch_m1_t<BITS, JT, G, false, true>(a, grid, st);
+    return bvec ? launch_m1_t<BITS, JT, G, true, false>(a, grid, st) : launch_m1_t<BITS, JT, G, false, false>(a, grid, st);
 }
 
 hipError_t launch_decode_m1(const MatmulProblem &p, void *workspace, hipStream_t st)
@@ -393,27 +430,27 @@ hipError_t launch_decode_m1(const MatmulProblem &p, void *workspace, hipStream_t
     a.X = (const uint16_t *)p.X;
     a.codes = (const uint8_t *)p.codes;
     a.codebook = p.codebook;
-    a.f.B = p.B; a.f.A = p.A; a.f.N = p.N; a.f.K = p.K; a.f.r = p.r;
-    a.f.f32 = p.f32fact ? 1 : 0;
-    a.f.r_eff = p.f32fact ? 3 * p.r : p.r;
+    a.A = p.A;
+    a.B = p.B;
     a.Y = p.Y;
     a.counters = (unsigned *)workspace;
     a.partial = workspace ? (float *)((unsigned char *)workspace + kTicketBytes) : nullptr;
-    a.N = p.N; a.K = p.K;
+    a.N = p.N; a.K = p.K; a.r = p.r;
     a.y_f32 = p.f32out ? 1 : 0;
     a.row_bytes = p.K / 8 * p.bits;
     a.nslabs = (p.N + 15) / 16;
     a.ns = d.ns;
     a.nchunks = d.nchunks;
     a.kblocks = d.kblocks;
-    const bool bvec = !p.f32fact && (p.r % 8) == 0;
+    // 16-byte loads of a lane's B run: the run starts at a multiple of 8 (bf16) or 4 (fp32) entries
+    const bool bvec = p.f32fact ? (p.r % 4) == 0 : (p.r % 8) == 0;
     const dim3 grid(d.gx, 1, d.kblocks);
     hipError_t e = hipErrorInvalidValue;
-#define LORDS_M1CASE(B_, S_, G_) \
-    if (p.bits == B_ && d.ss == S_) e = bvec ? launch_m1_t<B_, S_, G_, true>(a, grid, st) : launch_m1_t<B_, S_, G_, false>(a, grid, st);
-    LORDS_M1CASE(2, 1, 2) LORDS_M1CASE(2, 2, 1) LORDS_M1CASE(2, 4, 1)
-    LORDS_M1CASE(3, 1, 2) LORDS_M1CASE(3, 2, 1) LORDS_M1CASE(3, 4, 1)
-    LORDS_M1CASE(4, 1, 2) LORDS_M1CASE(4, 2, 1) LORDS_M1CASE(4, 4, 1)
+#define LORDS_M1CASE(B_, J_, G_) \
+    if (p.bits == B_ && d.jt == J_) e = launch_m1_b<B_, J_, G_>(a, grid, bvec, p.f32fact, st);
+    LORDS_M1CASE(2, 2, 2) LORDS_M1CASE(2, 4, 1)
+    LORDS_M1CASE(3, 2, 2) LORDS_M1CASE(3, 4, 1)
+    LORDS_M1CASE(4, 2, 2) LORDS_M1CASE(4, 4, 1)
 #undef LORDS_M1CASE
     return e;
 }

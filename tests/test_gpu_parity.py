@@ -98,6 +98,14 @@ SHAPES = [
     (257, 544, 48, 16),
     (130, 1056, 64, 2),
     (300, 288, 33, 7),
+    # one-token shapes: ranks on both sides of the 16/32/64 tile edges, several column blocks,
+    # a ragged last slab, K not a multiple of a wave's column block
+    (200, 512, 8, 1),
+    (1000, 2592, 20, 1),
+    (130, 4128, 32, 1),
+    (77, 288, 33, 1),
+    (300, 2080, 64, 1),
+    (64, 320, 72, 1),
 ]
 
 

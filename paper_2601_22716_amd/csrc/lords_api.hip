@@ -131,13 +131,16 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook, con
     if (path == LORDS_PATH_DECODE) {
         void *ws = nullptr;
         const bool one = lords::decode_m1_supported(p);
-        const bool fast = !one && lords::decode_fast_supported(p);
+        const bool few = !one && M > 1 && lords::decode_mx_supported(p);
+        const bool fast = !one && !few && lords::decode_fast_supported(p);
         const size_t need = one ? lords::decode_m1_workspace_bytes(p)
+                          : few ? lords::decode_mx_workspace_bytes(p)
                           : fast ? lords::decode_fast_workspace_bytes(p)
                                  : lords::kTicketBytes + lords::decode_workspace_bytes(p);
         const int rc = get_workspace(need, &ws);
         if (rc != LORDS_OK) return rc;
         if (one) e = lords::launch_decode_m1(p, ws, (hipStream_t)stream);
+        else if (few) e = lords::launch_decode_mx(p, ws, (hipStream_t)stream);
         else if (fast) e = lords::launch_decode_fast(p, ws, (hipStream_t)stream);
         else e = lords::launch_decode(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream);
     } else {

@@ -1,0 +1,404 @@
+// Few-token (2 <= M <= 16 per pass) decode kernel of  Y = X (C[Q] (.) (B A))^T  on gfx950,
+// bf16 factors, contraction length up to 64.  Memory-bound by design: every packed code is read
+// from HBM exactly once per pass and shared by the (up to) 16 tokens.
+//
+// Work split.  A workgroup of eight waves owns 4*KT consecutive columns (KT = 128*G) and a chunk
+// of 2*ns slabs of 16 rows.  Wave w owns column block w%4 and the slabs of half w/4, so two waves
+// per SIMD share the register file (256 VGPRs each, all MFMAs in VGPR form).  The A tile of the
+// 4*KT columns is staged ONCE per workgroup, row-major in LDS, with coalesced loads; each wave
+// reads its scale-MFMA a-operands from it with the transposing ds_read_b64_tr_b16.  The X tile
+// (16 tokens x 4*KT columns) then goes through the same LDS region and comes back as the
+// b-operands of the product MFMAs.  Both operand sets stay in registers for the whole row stream.
+//
+// Per slab a wave loads the lane's G*32 packed codes and 8*SS rank entries of its row of B (all
+// 16-byte loads), forms the scales S = B A of its 16 x KT block with G*8*SS scale MFMAs, looks up
+// the fp16 level pair of every two codes (replicated LDS table, one dword column per lane),
+// multiplies level and scale (v_fma_mix_f32), rounds the product once to bf16 and feeds G*4 product
+// MFMAs (rows x tokens).  The four column blocks of a workgroup meet in LDS and are added in block
+// order; column blocks of other workgroups (gridDim.z of them) meet in a workspace: device-coherent
+// stores, one arrival ticket per chunk, the last workgroup adds the blocks in increasing order.
+// Results are run-to-run identical.
+//
+// Lane mapping (v_mfma_f32_16x16x32_bf16; lane l = (c = l%16, g = l/16)):
+//   scale MFMA t of group v:  D[i][j],  j <-> row n0+j,
+//                             i <-> column kb + 32*(G*(i/4)+v) + 4t + i%4,
+//   so lane (c,g) gets, in accumulator i of MFMA t, the scale of code 4t+i of the 32-code group
+//   it holds (columns kb + 32*(G*g+v) ...).
+//   product MFMA u of group v: a-operand = the lane's 8 dequantised weights 8u..8u+7 of the
+//   group, b-operand = X[c][the same 8 columns]; D[i][j] with i <-> row, j <-> token.
+#include "lords_decode_common.h"
+
+namespace lords {
+
+constexpr int kMxWaves = 8;
+constexpr int kMxThreads = 64 * kMxWaves;
+
+struct MxArgs {
+    const uint16_t *X;     // M x K bf16, M <= 16
+    const uint8_t *codes;
+    const float *codebook;
+    const uint16_t *A;     // r x K bf16
+    const uint16_t *B;     // N x r bf16
+    void *Y;
+    float *partial;        // [splits][M][N] fp32, used when splits > 1
+    unsigned *counters;    // one ticket per chunk, zero between calls
+    int M, N, K, r;
+    int y_f32;
+    int row_bytes;
+    int nslabs;            // ceil(N / 16)
+    int ns;                // slabs per wave per chunk, <= kNS
+    int nchunks;           // chunks of 2*ns slabs
+    int splits;            // gridDim.z
+};
+
+template <int BITS, int SS, int G, bool BVEC>
+__global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_mx_kernel(MxArgs a)
+{
+    constexpr int KT = 128 * G, WK = 4 * KT, AST = WK + 8, NL = 1 << BITS, NE = 1 << (2 * BITS), CPR = WK / 8;
+    constexpr int LUT_BYTES = NE * 256, A_BYTES = SS * 32 * AST * 2;
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t *As = reinterpret_cast<uint16_t *>(smem + LUT_BYTES);        // [SS*32][AST], then X [16][AST], then sums
+    int *flag = reinterpret_cast<int *>(smem + LUT_BYTES + A_BYTES);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int cb = wave & 3, half = wave >> 2;
+    const int kw = blockIdx.z * WK;                            // first column of the workgroup
+    const int kb = kw + cb * KT;                               // first column of this wave's block
+    const int N = a.N, K = a.K, M = a.M, r = a.r;
+    const uint32_t laneoff = (uint32_t)lane * 4u;
+    const int ngroups = K >> 5;
+
+    // Loads of slab i of the current chunk, branch-free (addresses clamped into the arrays) so that
+    // they can run kDepth slabs ahead: codes of columns >= K meet zero scales, rank entries >= r of
+    // B meet zero rows of the A tile, rows >= N are dropped at the store.
+    int chunk = blockIdx.x;
+    int slab0 = (chunk * 2 + half) * a.ns;                     // this wave's first slab
+    uint32_t cw[kNS][G][BITS];
+    bf16x8 Bop[kNS][SS];
+    auto issue = [&](int i) __attribute__((always_inline)) {
+        const int n = min((slab0 + i) * 16 + c, N - 1);
+#pragma unroll
+        for (int v = 0; v < G; ++v) {
+            const int grp = min((kb >> 5) + G * g + v, ngroups - 1);
+            load_group<BITS>(a.codes + (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS), cw[i][v]);
+        }
+        if (BVEC) {
+#pragma unroll
+            for (int s = 0; s < SS; ++s) {
+                const int jj0 = 32 * s + 8 * g;
+                Bop[i][s] = *reinterpret_cast<const bf16x8 *>(a.B + (size_t)n * r + (jj0 + 8 <= r ? jj0 : 0));
+            }
+        }
+    };
+    // rank not a multiple of 8: the B operand is gathered entry by entry at the point of use
+    auto gather_B = [&](int i) __attribute__((always_inline)) {
+        const int n = min((slab0 + i) * 16 + c, N - 1);
+#pragma unroll
+        for (int s = 0; s < SS; ++s) {
+            typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+            s16x8 t;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int j = 32 * s + 8 * g + e;
+                t[e] = j < r ? (short)a.B[(size_t)n * r + j] : (short)0;
+            }
+            Bop[i][s] = __builtin_bit_cast(bf16x8, t);
+        }
+    };
+
+    // ---- 1. set-up loads (A tile, X tile, levels) go out FIRST, the first slabs of the row
+    //         stream right behind them: a wave's loads return in order ---------------------------
+    constexpr int NCA = SS * 32 * CPR / kMxThreads;           // 16-byte chunks of the A tile per thread
+    constexpr int NCX = (16 * CPR + kMxThreads - 1) / kMxThreads;
+    constexpr int NIT = (NE * 16 + kMxThreads - 1) / kMxThreads;
+    const int kc = tid % CPR, k0 = kw + 8 * kc;               // the thread's column chunk is fixed
+    u32x4 ta[NCA], tx[NCX];
+    float lo[NIT], hi[NIT];
+#pragma unroll
+    for (int q = 0; q < NCA; ++q) {
+        const int jj = (tid + kMxThreads * q) / CPR;
+        ta[q] = u32x4{0u, 0u, 0u, 0u};
+        if (jj < r && k0 < K) ta[q] = *reinterpret_cast<const u32x4 *>(a.A + (size_t)jj * K + k0);
+    }
+#pragma unroll
+    for (int q = 0; q < NCX; ++q) {
+        const int m = (tid + kMxThreads * q) / CPR;
+        tx[q] = u32x4{0u, 0u, 0u, 0u};
+        if (m < M && k0 < K) tx[q] = *reinterpret_cast<const u32x4 *>(a.X + (size_t)m * K + k0);
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int id = tid + kMxThreads * it, idx = (id >> 4) & (NE - 1);
+        lo[it] = a.codebook[idx & (NL - 1)];
+        hi[it] = a.codebook[idx >> BITS];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < kDepth; ++i) issue(i);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- 2. A tile and level table into LDS; scale a-operands back, transposed -----------------
+#pragma unroll
+    for (int q = 0; q < NCA; ++q) {
+        const int jj = (tid + kMxThreads * q) / CPR;
+        *reinterpret_cast<u32x4 *>(As + jj * AST + 8 * kc) = ta[q];
+    }
+    {
+        uint32_t *lut32 = reinterpret_cast<uint32_t *>(smem);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int id = tid + kMxThreads * it, idx = id >> 4, q = id & 15;
+            if (idx < NE) {
+                f16x2 h;
+                h[0] = (_Float16)lo[it];
+                h[1] = (_Float16)hi[it];
+                const uint32_t pv = __builtin_bit_cast(uint32_t, h);
+                *reinterpret_cast<u32x4 *>(lut32 + idx * 64 + 4 * q) = u32x4{pv, pv, pv, pv};
+            }
+        }
+    }
+    __syncthreads();
+    bf16x8 Aop[G][SS][8];
+#pragma unroll
+    for (int s = 0; s < SS; ++s)
+#pragma unroll
+        for (int v = 0; v < G; ++v)
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                Aop[v][s][t] = tr_read_pair_d<AST>(As + cb * KT, 32 * s + 8 * g + (c >> 2), 32 * (G * (c & 3) + v) + 4 * t);
+    __syncthreads();                                       // every wave has its A operands
+
+    // ---- 3. X tile through the same region; product b-operands back ----------------------------
+#pragma unroll
+    for (int q = 0; q < NCX; ++q) {
+        const int m = (tid + kMxThreads * q) / CPR;
+        if (m < 16) *reinterpret_cast<u32x4 *>(As + m * AST + 8 * kc) = tx[q];
+    }
+    __syncthreads();
+    bf16x8 Xop[G][4];
+#pragma unroll
+    for (int v = 0; v < G; ++v)
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            Xop[v][u] = *reinterpret_cast<const bf16x8 *>(As + c * AST + cb * KT + 32 * (G * g + v) + 8 * u);
+    __syncthreads();                                       // the region now takes the block sums
+
+    f32x4 *red = reinterpret_cast<f32x4 *>(As);            // [8 waves][kNS][64 lanes]
+
+    // ---- 4. the row stream, chunk by chunk ------------------------------------------------------
+    for (; chunk < a.nchunks; chunk += gridDim.x) {
+        if (chunk != (int)blockIdx.x) {
+            slab0 = (chunk * 2 + half) * a.ns;
+#pragma unroll
+            for (int i = 0; i < kDepth; ++i) issue(i);
+        }
+        const int nsw = max(0, min(a.ns, a.nslabs - slab0));
+#pragma unroll
+        for (int i = 0; i < kNS; ++i) {
+            if (i < nsw) {
+                if (i + kDepth < kNS) issue(i + kDepth);
+                __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of this slab's arithmetic
+                if (!BVEC) gather_B(i);
+                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int v = 0; v < G; ++v) {
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {       // half a group: scale MFMAs 4hh .. 4hh+3
+                        f32x4 S[4];
+#pragma unroll
+                        for (int s = 0; s < SS; ++s)
+#pragma unroll
+                            for (int t = 0; t < 4; ++t)
+                                S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop[v][s][4 * hh + t], Bop[i][s],
+                                                                               s == 0 ? f32x4{0.f, 0.f, 0.f, 0.f} : S[t], 0, 0, 0);
+#pragma unroll
+                        for (int uu = 0; uu < 2; ++uu) {
+                            const int u = 2 * hh + uu;
+                            bf16x8 W;
+#pragma unroll
+                            for (int pp = 0; pp < 4; ++pp) {
+                                const uint32_t ad = pair_addr<BITS>(cw[i][v], 4 * u + pp, laneoff);
+                                const f16x2 h = __builtin_bit_cast(f16x2, lds_load_u32(ad));
+                                const int e0 = 2 * pp, e1 = 2 * pp + 1;
+                                const float s0 = S[2 * uu + (e0 >> 2)][e0 & 3], s1 = S[2 * uu + (e1 >> 2)][e1 & 3];
+                                W[e0] = (__bf16)__builtin_fmaf((float)h[0], s0, 0.0f);
+                                W[e1] = (__bf16)__builtin_fmaf((float)h[1], s1, 0.0f);
+                            }
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W, Xop[v][u], acc, 0, 0, 0);
+                        }
+                    }
+                }
+                red[(wave * kNS + i) * 64 + lane] = acc;
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();
+
+        // ---- 5. add the four column blocks (fixed order); lane (m, gl) of a slab holds rows 4gl..4gl+3
+        const int rows = 2 * a.ns * 16;                    // rows of the chunk
+        const int row0 = chunk * rows;
+        for (int q = tid; q < 2 * a.ns * 64; q += kMxThreads) {
+            const int hf = q / (a.ns * 64), rem = q - hf * (a.ns * 64), i = rem >> 6, l = rem & 63;
+            const int m = l & 15, gl = l >> 4;
+            f32x4 s = red[((hf * 4 + 0) * kNS + i) * 64 + l];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) {
+                const f32x4 t = red[((hf * 4 + w) * kNS + i) * 64 + l];
+                s[0] += t[0]; s[1] += t[1]; s[2] += t[2]; s[3] += t[3];
+            }
+            if (m >= M) continue;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int n = row0 + (hf * a.ns + i) * 16 + 4 * gl + e;
+                if (n >= N) continue;
+                if (a.splits > 1)
+                    __hip_atomic_store(&a.partial[((size_t)blockIdx.z * M + m) * N + n], s[e], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                else if (a.y_f32) reinterpret_cast<float *>(a.Y)[(size_t)m * N + n] = s[e];
+                else reinterpret_cast<uint16_t *>(a.Y)[(size_t)m * N + n] = bf16_bits(s[e]);
+            }
+        }
+        // ---- 6. column blocks held by other workgroups: the last one to arrive adds them.  The
+        // partial sums went out as device-coherent (write-through) stores: once they have completed
+        // they are visible to every workgroup, without an L2 write-back or invalidate.
+        if (a.splits > 1) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_s_waitcnt(0);
+            __syncthreads();
+            if (tid == 0) {
+                const unsigned old = __hip_atomic_fetch_add(&a.counters[chunk], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int last = (old == (unsigned)(a.splits - 1));
+                // every other workgroup of this chunk has passed: hand the ticket back at zero
+                if (last) __hip_atomic_store(&a.counters[chunk], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                *flag = last;
+            }
+            __syncthreads();
+            if (*flag) {
+                for (int q = tid; q < M * rows; q += kMxThreads) {
+                    const int m = q / rows, n = row0 + (q - m * rows);
+                    if (n >= N) continue;
+                    float s = 0.f;
+                    for (int z0 = 0; z0 < a.splits; z0 += 8) {
+                        float t[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int z = min(z0 + u, a.splits - 1);
+                            t[u] = __hip_atomic_load(&a.partial[((size_t)z * M + m) * N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (z0 + u < a.splits) s += t[u];
+                    }
+                    if (a.y_f32) reinterpret_cast<float *>(a.Y)[(size_t)m * N + n] = s;
+                    else reinterpret_cast<uint16_t *>(a.Y)[(size_t)m * N + n] = bf16_bits(s);
+                }
+            }
+        } else {
+            __syncthreads();                               // the sums are rewritten by the next chunk
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct MxPlan {
+    int ss, G, WK, splits, ns, nchunks, gx;
+};
+
+static int mx_ss(const MatmulProblem &p)
+{
+    if (p.f32fact) return 0;
+    const int rp = (p.r + 31) / 32;
+    return rp <= 1 ? 1 : rp <= 2 ? 2 : 0;
+}
+
+static MxPlan mx_plan(const MatmulProblem &p)
+{
+    MxPlan d;
+    d.ss = mx_ss(p);
+    d.G = d.ss == 1 ? 2 : 1;
+    d.WK = 4 * 128 * d.G;
+    d.splits = (p.K + d.WK - 1) / d.WK;
+    const int nslabs = (p.N + 15) / 16;
+    int gx = 256 / d.splits;                           // one resident workgroup per CU
+    if (gx < 1) gx = 1;
+    int ns = (nslabs + 2 * gx - 1) / (2 * gx);
+    if (ns > kNS) ns = kNS;
+    if (ns < 1) ns = 1;
+    d.ns = ns;
+    d.nchunks = (nslabs + 2 * ns - 1) / (2 * ns);
+    d.gx = gx < d.nchunks ? gx : d.nchunks;
+    return d;
+}
+
+bool decode_mx_supported(const MatmulProblem &p)
+{
+    if (p.M < 1 || mx_ss(p) == 0) return false;
+    const MxPlan d = mx_plan(p);
+    return (size_t)d.nchunks * sizeof(unsigned) <= kTicketBytes && d.splits <= 65535;
+}
+
+size_t decode_mx_workspace_bytes(const MatmulProblem &p)
+{
+    const MxPlan d = mx_plan(p);
+    if (d.splits <= 1) return 0;
+    const int mchunk = p.M < 16 ? p.M : 16;
+    return kTicketBytes + (size_t)d.splits * mchunk * p.N * sizeof(float);
+}
+
+template <int BITS, int SS, int G, bool BVEC>
+static hipError_t launch_mx_t(const MxArgs &a, dim3 grid, hipStream_t st)
+{
+    constexpr int WK = 4 * 128 * G, AST = WK + 8;
+    const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)SS * 32 * AST * 2 + 64;
+    static bool attr_set = false;
+    if (!attr_set && smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_mx_kernel<BITS, SS, G, BVEC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((decode_mx_kernel<BITS, SS, G, BVEC>), grid, dim3(kMxThreads), smem, st, a);
+    return hipGetLastError();
+}
+
+// `workspace` must be zero-filled when first handed over (tickets) and hold
+// decode_mx_workspace_bytes(p) bytes; the kernel leaves the tickets at zero again.
+hipError_t launch_decode_mx(const MatmulProblem &p, void *workspace, hipStream_t st)
+{
+    const MxPlan d = mx_plan(p);
+    for (int m0 = 0; m0 < p.M; m0 += 16) {
+        MxArgs a;
+        a.M = (p.M - m0) < 16 ? (p.M - m0) : 16;
+        a.X = (const uint16_t *)p.X + (size_t)m0 * p.K;
+        a.Y = p.f32out ? (void *)((float *)p.Y + (size_t)m0 * p.N) : (void *)((uint16_t *)p.Y + (size_t)m0 * p.N);
+        a.codes = (const uint8_t *)p.codes;
+        a.codebook = p.codebook;
+        a.A = (const uint16_t *)p.A;
+        a.B = (const uint16_t *)p.B;
+        a.counters = (unsigned *)workspace;
+        a.partial = workspace ? (float *)((unsigned char *)workspace + kTicketBytes) : nullptr;
+        a.N = p.N; a.K = p.K; a.r = p.r;
+        a.y_f32 = p.f32out ? 1 : 0;
+        a.row_bytes = p.K / 8 * p.bits;
+        a.nslabs = (p.N + 15) / 16;
+        a.ns = d.ns;
+        a.nchunks = d.nchunks;
+        a.splits = d.splits;
+        const bool bvec = (p.r % 8) == 0;
+        const dim3 grid(d.gx, 1, d.splits);
+        hipError_t e = hipErrorInvalidValue;
+#define LORDS_MXCASE(B_, S_, G_) \
+    if (p.bits == B_ && d.ss == S_) e = bvec ? launch_mx_t<B_, S_, G_, true>(a, grid, st) : launch_mx_t<B_, S_, G_, false>(a, grid, st);
+        LORDS_MXCASE(2, 1, 2) LORDS_MXCASE(2, 2, 1)
+        LORDS_MXCASE(3, 1, 2) LORDS_MXCASE(3, 2, 1)
+        LORDS_MXCASE(4, 1, 2) LORDS_MXCASE(4, 2, 1)
+#undef LORDS_MXCASE
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace lords

@@ -30,6 +30,12 @@ bool decode_m1_supported(const MatmulProblem &p);
 size_t decode_m1_workspace_bytes(const MatmulProblem &p);
 hipError_t launch_decode_m1(const MatmulProblem &p, void *workspace, hipStream_t st);
 
+// Few-token path (2..16 tokens per pass), bf16 factors, ranks up to 64 (lords_decode_mx.hip); same
+// workspace convention.
+bool decode_mx_supported(const MatmulProblem &p);
+size_t decode_mx_workspace_bytes(const MatmulProblem &p);
+hipError_t launch_decode_mx(const MatmulProblem &p, void *workspace, hipStream_t st);
+
 // Small-M path, ranks up to 128 contraction columns (lords_decode.hip).  The workspace holds
 // the arrival tickets (zero when handed over, left at zero) followed by fp32 partial sums.
 bool decode_fast_supported(const MatmulProblem &p);

@@ -106,6 +106,10 @@ SHAPES = [
     (77, 288, 33, 1),
     (300, 2080, 64, 1),
     (64, 320, 72, 1),
+    # few-token shapes: several column splits, ranks on both sides of 32, a rank that is not a multiple of 8
+    (100, 2592, 24, 5),
+    (333, 1056, 40, 16),
+    (48, 3104, 13, 2),
 ]
 
 
@@ -119,6 +123,17 @@ def test_matmul_parity_small(gpu, path, bits, fdt, N, K, r, M):
     cs = li.make_case("tiny", M=M, N=N, K=K, bits=bits, r=r, factor_dtype=fdt, seed=9, signed_factors=(r % 2 == 1))
     Y = gpu.DeviceCase(cs).matmul(path=L.LORDS_PATH_DECODE if path == "decode" else L.LORDS_PATH_PREFILL)
     want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, bits)
+    check_y(Y, want, "Y")
+
+
+@pytest.mark.parametrize("N,K,r,M", [(270000, 32, 4, 1), (70000, 64, 8, 3)])
+def test_matmul_decode_many_rows(gpu, N, K, r, M):
+    """More row chunks than resident workgroups: the decode kernels walk several chunks each."""
+    import paper_2601_22716_amd as L
+    say(f"matmul decode many rows N={N} K={K} r={r} M={M}")
+    cs = li.make_case("tiny", M=M, N=N, K=K, bits=4, r=r, factor_dtype="bf16", seed=21)
+    Y = gpu.DeviceCase(cs).matmul(path=L.LORDS_PATH_DECODE)
+    want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, 4)
     check_y(Y, want, "Y")
 
 

@@ -38,6 +38,7 @@ namespace lords {
 
 constexpr int kM1Waves = 8;
 constexpr int kM1Threads = 64 * kM1Waves;
+constexpr int kM1Tickets = 64;        // chunks whose tickets are taken at once
 
 struct M1Args {
     const uint16_t *X;
@@ -286,23 +287,34 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
             }
         }
         LORDS_STAMP_WG(4);
-        // ---- 6. other column blocks: the last workgroup to arrive adds them in order --------------
-        if (a.kblocks > 1) {
-            // The partial sums went out as device-coherent (write-through) stores: once they have
-            // completed they are visible to every workgroup, without an L2 write-back or invalidate.
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-            if (tid == 0) {
-                const unsigned old = __hip_atomic_fetch_add(&a.counters[chunk], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // ---- 6. other column blocks: for every chunk this workgroup streamed, the last workgroup to
+    //         arrive adds the blocks in order.  Done once, after the last chunk, so that the two
+    //         dependent round trips (stores acknowledged, then the ticket) are paid once.  The
+    //         partial sums went out as device-coherent (write-through) stores: once they have
+    //         completed they are visible to every workgroup, without an L2 write-back or invalidate.
+    if (a.kblocks > 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        const int niter = (a.nchunks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+        for (int base = 0; base < niter; base += kM1Tickets) {
+            const int nt = min(kM1Tickets, niter - base);
+            if (tid < nt) {
+                const int ch = blockIdx.x + (base + tid) * gridDim.x;
+                const unsigned old = __hip_atomic_fetch_add(&a.counters[ch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const int last = (old == (unsigned)(a.kblocks - 1));
                 // every other workgroup of this chunk has passed: hand the ticket back at zero
-                if (last) __hip_atomic_store(&a.counters[chunk], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                *flag = last;
+                if (last) __hip_atomic_store(&a.counters[ch], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                flag[tid] = last;
             }
             __syncthreads();
-            if (*flag) {
-                const int row0 = chunk * kM1Waves * a.ns * 16, rows = kM1Waves * a.ns * 16;
+            LORDS_STAMP_WG(5);
+            for (int t = 0; t < nt; ++t) {
+                if (!flag[t]) continue;
+                const int ch = blockIdx.x + (base + t) * gridDim.x;
+                const int row0 = ch * kM1Waves * a.ns * 16, rows = kM1Waves * a.ns * 16;
                 // two rows per thread and pass, all their loads in flight at once; blocks added in order
                 for (int q = tid; q < rows; q += 2 * kM1Threads) {
                     const int n0 = min(row0 + q, N - 1), n1 = min(row0 + q + kM1Threads, N - 1);
@@ -329,8 +341,8 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
                     }
                 }
             }
+            __syncthreads();                               // the flags are rewritten by the next batch
         }
-        LORDS_STAMP_WG(5);
     }
     LORDS_STAMP_WG(6);
 }
@@ -404,7 +416,7 @@ template <int BITS, int JT, int G, bool BVEC, bool F32>
 static hipError_t launch_m1_t(const M1Args &a, dim3 grid, hipStream_t st)
 {
     constexpr int KT = 128 * G, AST = KT + 8;
-    const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)JT * 16 * AST * 2 + 64;
+    const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)JT * 16 * AST * 2 + kM1Tickets * sizeof(int);
     static bool attr_set = false;
     if (!attr_set && smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_m1_kernel<BITS, JT, G, BVEC, F32>),

@@ -32,6 +32,7 @@ namespace lords {
 
 constexpr int kMxWaves = 8;
 constexpr int kMxThreads = 64 * kMxWaves;
+constexpr int kMxTickets = 64;        // chunks whose tickets are taken at once
 
 struct MxArgs {
     const uint16_t *X;     // M x K bf16, M <= 16
@@ -259,43 +260,54 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 else reinterpret_cast<uint16_t *>(a.Y)[(size_t)m * N + n] = bf16_bits(s[e]);
             }
         }
-        // ---- 6. column blocks held by other workgroups: the last one to arrive adds them.  The
-        // partial sums went out as device-coherent (write-through) stores: once they have completed
-        // they are visible to every workgroup, without an L2 write-back or invalidate.
-        if (a.splits > 1) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-            if (tid == 0) {
-                const unsigned old = __hip_atomic_fetch_add(&a.counters[chunk], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();                                   // the sums are rewritten by the next chunk
+    }
+
+    // ---- 6. column blocks held by other workgroups: for every chunk this workgroup streamed, the
+    //         last workgroup to arrive adds them in order.  Done once, after the last chunk, so that
+    //         the two dependent round trips (stores acknowledged, then the ticket) are paid once.
+    //         The partial sums went out as device-coherent (write-through) stores: once they have
+    //         completed they are visible to every workgroup, without an L2 write-back or invalidate.
+    if (a.splits > 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        const int rows = 2 * a.ns * 16;
+        const int niter = (a.nchunks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+        for (int base = 0; base < niter; base += kMxTickets) {
+            const int nt = min(kMxTickets, niter - base);
+            if (tid < nt) {
+                const int ch = blockIdx.x + (base + tid) * gridDim.x;
+                const unsigned old = __hip_atomic_fetch_add(&a.counters[ch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const int last = (old == (unsigned)(a.splits - 1));
                 // every other workgroup of this chunk has passed: hand the ticket back at zero
-                if (last) __hip_atomic_store(&a.counters[chunk], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                *flag = last;
+                if (last) __hip_atomic_store(&a.counters[ch], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                flag[tid] = last;
             }
             __syncthreads();
-            if (*flag) {
+            for (int t = 0; t < nt; ++t) {
+                if (!flag[t]) continue;
+                const int row0 = (blockIdx.x + (base + t) * gridDim.x) * rows;
                 for (int q = tid; q < M * rows; q += kMxThreads) {
                     const int m = q / rows, n = row0 + (q - m * rows);
                     if (n >= N) continue;
                     float s = 0.f;
                     for (int z0 = 0; z0 < a.splits; z0 += 8) {
-                        float t[8];
+                        float t8[8];
 #pragma unroll
                         for (int u = 0; u < 8; ++u) {
                             const int z = min(z0 + u, a.splits - 1);
-                            t[u] = __hip_atomic_load(&a.partial[((size_t)z * M + m) * N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            t8[u] = __hip_atomic_load(&a.partial[((size_t)z * M + m) * N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
 #pragma unroll
                         for (int u = 0; u < 8; ++u)
-                            if (z0 + u < a.splits) s += t[u];
+                            if (z0 + u < a.splits) s += t8[u];
                     }
                     if (a.y_f32) reinterpret_cast<float *>(a.Y)[(size_t)m * N + n] = s;
                     else reinterpret_cast<uint16_t *>(a.Y)[(size_t)m * N + n] = bf16_bits(s);
                 }
             }
-        } else {
-            __syncthreads();                               // the sums are rewritten by the next chunk
+            __syncthreads();                               // the flags are rewritten by the next batch
         }
     }
 }
@@ -352,7 +364,7 @@ template <int BITS, int SS, int G, bool BVEC>
 static hipError_t launch_mx_t(const MxArgs &a, dim3 grid, hipStream_t st)
 {
     constexpr int WK = 4 * 128 * G, AST = WK + 8;
-    const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)SS * 32 * AST * 2 + 64;
+    const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)SS * 32 * AST * 2 + kMxTickets * sizeof(int);
     static bool attr_set = false;
     if (!attr_set && smem > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_mx_kernel<BITS, SS, G, BVEC>),

@@ -48,9 +48,15 @@ constexpr int kPfCopies = 8;
 
 __device__ __forceinline__ void lds_direct_16(const void *gsrc, void *lds_wave_base)
 {
-    // every active lane fetches 16 bytes from its own address; they land at lds_wave_base + 16*lane
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+    // Every active lane fetches 16 bytes from its own address; they land at lds_wave_base + 16*lane
+    // (M0 holds the wave's LDS base).  Written as assembly on purpose: when the compiler knows of
+    // an outstanding load into LDS it makes the next LDS read wait for ALL outstanding memory
+    // loads, i.e. for the tile that was just requested, which exposes the whole memory latency
+    // once per K tile.  The kernel orders these loads itself: s_waitcnt vmcnt(0) and a barrier
+    // before a buffer is read.
+    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(base), "v"(gsrc) : "memory", "m0");
 }
 
 template <int BITS>

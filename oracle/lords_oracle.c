@@ -18,7 +18,18 @@
  *
  * Inputs are float (bf16-exact where the layer stores bf16) and are widened to
  * double before use.  Return value: 0 on success, -1 on a bad argument.
+ *
+ * The quantisation side (Alg. 1 step 2.1 and the block-wise scale of step 1) is stated here in
+ * fp32, because there floating point decides an integer and both sides of a parity test have to
+ * take that decision in the same precision.  Every operation below is one correctly rounded fp32
+ * operation (fmaf, *, /, comparisons), in the order written; the file is compiled with
+ * -ffp-contract=off so that nothing else gets fused:
+ *   S[n][k]   = fmaf(B[n][r-1], A[r-1][k], ... fmaf(B[n][0], A[0][k], 0) ...)    j increasing
+ *   q[n][k]   = the lowest i minimising e_i = d_i * d_i,  d_i = fmaf(S[n][k], C[i], -W[n][k])
+ *   scale of a block = (max over the block of |W|) / (max over the levels of |C|)
+ * The fp64 statement of the same definitions is in lords_oracle.py; tests pin the two together.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #ifdef _OPENMP
@@ -125,4 +136,69 @@ int lords_oracle_matmul(const float *X, const uint8_t *codes, const float *codeb
                         long M, long N, long K, long r, int bits)
 {
     return lords_oracle_matmul_rows(X, codes, codebook, B, A, Y, M, N, K, r, bits, (const long *)0, N);
+}
+
+/* ---- quantisation side, fp32 (see the header) --------------------------------------------- */
+
+int lords_oracle_pack(const uint8_t *q, uint8_t *codes, long N, long K, int bits)
+{
+    if (!q || !codes || bad_shape(N, K, 0, bits)) return -1;
+    const long rb = K * bits / 8;
+    for (long n = 0; n < N; ++n) {
+        uint8_t *row = codes + n * rb;
+        for (long b = 0; b < rb; ++b) row[b] = 0;
+        for (long k = 0; k < K; ++k) {
+            const int v = q[n * K + k];
+            if (v >> bits) return -1;
+            for (int b = 0; b < bits; ++b) {
+                const long bit = (long)bits * k + b;
+                row[bit >> 3] |= (uint8_t)(((v >> b) & 1) << (bit & 7));
+            }
+        }
+    }
+    return 0;
+}
+
+int lords_oracle_quantize_f32(const float *W, const float *codebook, const float *B, const float *A,
+                              uint8_t *q, long N, long K, long r, int bits)
+{
+    if (!W || !codebook || !B || !A || !q || bad_shape(N, K, r, bits)) return -1;
+    const int nl = 1 << bits;
+#pragma omp parallel for schedule(static)
+    for (long n = 0; n < N; ++n)
+        for (long k = 0; k < K; ++k) {
+            float s = 0.0f;
+            for (long j = 0; j < r; ++j) s = fmaf(B[n * r + j], A[j * K + k], s);
+            const float w = W[n * K + k];
+            int best = 0;
+            float ebest = 0.0f;
+            for (int i = 0; i < nl; ++i) {
+                const float d = fmaf(s, codebook[i], -w);
+                const float e = d * d;
+                if (i == 0 || e < ebest) { best = i; ebest = e; }
+            }
+            q[n * K + k] = (uint8_t)best;
+        }
+    return 0;
+}
+
+int lords_oracle_block_init_f32(const float *W, const float *codebook, float *B, float *A,
+                                long N, long K, long r, int bits)
+{
+    if (!W || !codebook || !B || !A || bad_shape(N, K, r, bits) || r < 1 || (K % r) != 0) return -1;
+    const long g = K / r;
+    float cmax = 0.0f;
+    for (int i = 0; i < (1 << bits); ++i)
+        if (fabsf(codebook[i]) > cmax) cmax = fabsf(codebook[i]);
+    for (long n = 0; n < N; ++n)
+        for (long j = 0; j < r; ++j) {
+            float m = 0.0f;
+            for (long k = j * g; k < (j + 1) * g; ++k)
+                if (fabsf(W[n * K + k]) > m) m = fabsf(W[n * K + k]);
+            B[n * r + j] = m / cmax;
+        }
+    for (long j = 0; j < r; ++j)
+        for (long k = 0; k < K; ++k)
+            A[j * K + k] = (k / g == j) ? 1.0f : 0.0f;
+    return 0;
 }

@@ -26,6 +26,16 @@ little-endian bit string, bit b of the row being bit (b mod 8) of byte
 All floating-point inputs are widened to fp64 before any arithmetic; bf16
 inputs arrive as fp32 arrays holding bf16-exact values, so widening is exact.
 
+The quantisation side (the inverse of the path; Alg. 1 step 2.1 and the
+block-wise scale it starts from):
+
+  quantize    Q_ij = argmin over the levels v of (S_ij v - W_ij)^2, as an index,
+              ties going to the lowest index                (Alg. 1, step 2.1)
+  block_init  S = ComputeScale(W, block size K/r) written as B A with
+              B = the block scales and A = the 0/1 block indicator, which is the
+              same S as the SVD factors of Alg. 1 step 1 (rank(S) <= r, Sec. 3.1)
+  pack_codes  indices -> packed rows (inverse of unpack_codes)
+
 Pins (see tests/test_oracle_pins.py): hand-derived byte vectors for the
 unpacker, scalar brute force on tiny inputs, the block-wise special case
 (paper Sec. 3.1), identity activations, the rank-1 closed form, the all-ones
@@ -96,6 +106,60 @@ def equivalent_rank(N: int, K: int, group: int) -> int:
 # ----------------------------------------------------------------------------
 # error measures used by the parity gates
 # ----------------------------------------------------------------------------
+def pack_codes(q: np.ndarray, bits: int) -> np.ndarray:
+    """uint8 [N, K] of level indices -> packed rows uint8 [N, K*bits/8] (inverse of unpack_codes)."""
+    if bits not in (2, 3, 4):
+        raise ValueError("bits must be 2, 3 or 4")
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    N, K = q.shape
+    if (K * bits) % 8:
+        raise ValueError("K*bits must be a whole number of bytes")
+    if q.size and int(q.max()) >= (1 << bits):
+        raise ValueError("index out of range")
+    fields = np.zeros((N, K, bits), dtype=np.uint8)
+    for b in range(bits):
+        fields[:, :, b] = (q >> b) & 1
+    return np.packbits(fields.reshape(N, K * bits), axis=1, bitorder="little")
+
+
+def quantize(W, codebook, B, A, with_margin: bool = False):
+    """Alg. 1 step 2.1 in fp64: idx[n,k] = argmin_i (S[n,k] * C[i] - W[n,k])^2, ties to the lowest i.
+
+    with_margin=True also returns, per element, (second smallest error - smallest error), which
+    tells a test how close the decision was."""
+    S = scale_matrix(B, A)
+    W64 = np.asarray(W, dtype=np.float64)
+    C = np.asarray(codebook, dtype=np.float64)
+    err = (S[:, :, None] * C[None, None, :] - W64[:, :, None]) ** 2         # [N, K, 2^bits]
+    idx = np.argmin(err, axis=2).astype(np.uint8)                           # first minimum = lowest index
+    if not with_margin:
+        return idx
+    part = np.partition(err, 1, axis=2)
+    return idx, part[:, :, 1] - part[:, :, 0]
+
+
+def block_scales(W, codebook, group: int) -> np.ndarray:
+    """ComputeScale of Alg. 1 step 1, read as symmetric absmax scaling (Sec. 3.1): the scale of a block
+    of `group` consecutive columns of a row is max|W_b| / max|level|.  Returns [N, K/group], fp64."""
+    W64 = np.asarray(W, dtype=np.float64)
+    N, K = W64.shape
+    if K % group:
+        raise ValueError("K must be a multiple of the block size")
+    cmax = float(np.max(np.abs(np.asarray(codebook, dtype=np.float64))))
+    return np.abs(W64).reshape(N, K // group, group).max(axis=2) / cmax
+
+
+def block_init(W, codebook, r: int):
+    """S = ComputeScale(W, block size K/r) as factors: B = block scales (N x r), A = block indicator (r x K)."""
+    K = np.asarray(W).shape[1]
+    if K % r:
+        raise ValueError("K must be a multiple of r")
+    g = K // r
+    B = block_scales(W, codebook, g)
+    A = (np.arange(K)[None, :] // g == np.arange(r)[:, None]).astype(np.float64)
+    return B, A
+
+
 def rel_fro(got, want) -> float:
     want = np.asarray(want, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)

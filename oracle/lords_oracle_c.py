@@ -19,8 +19,8 @@ _lib = None
 
 def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC]
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -36,6 +36,9 @@ def _load():
         lib.lords_oracle_dequant.argtypes = [vp, vp, vp, vp, vp, cl, cl, cl, ci]
         lib.lords_oracle_matmul.argtypes = [vp, vp, vp, vp, vp, vp, cl, cl, cl, cl, ci]
         lib.lords_oracle_matmul_rows.argtypes = [vp, vp, vp, vp, vp, vp, cl, cl, cl, cl, ci, vp, cl]
+        lib.lords_oracle_pack.argtypes = [vp, vp, cl, cl, ci]
+        lib.lords_oracle_quantize_f32.argtypes = [vp, vp, vp, vp, vp, cl, cl, cl, ci]
+        lib.lords_oracle_block_init_f32.argtypes = [vp, vp, vp, vp, cl, cl, cl, ci]
         _lib = lib
     return _lib
 
@@ -90,3 +93,33 @@ def matmul(X, codes, codebook, B, A, bits: int, rows=None) -> np.ndarray:
     if rc != 0:
         raise ValueError("lords_oracle_matmul: bad argument")
     return Y
+
+
+def pack_codes(q, bits: int) -> np.ndarray:
+    q = _c(q, np.uint8)
+    N, K = q.shape
+    codes = np.empty((N, K * bits // 8), dtype=np.uint8)
+    if _load().lords_oracle_pack(_p(q), _p(codes), N, K, bits) != 0:
+        raise ValueError("lords_oracle_pack: bad argument")
+    return codes
+
+
+def quantize_f32(W, codebook, B, A, bits: int) -> np.ndarray:
+    """Level indices chosen in fp32, operation by operation as stated in lords_oracle.c."""
+    W, codebook, B, A = _c(W, np.float32), _c(codebook, np.float32), _c(B, np.float32), _c(A, np.float32)
+    N, K = W.shape
+    r = B.shape[1]
+    q = np.empty((N, K), dtype=np.uint8)
+    if _load().lords_oracle_quantize_f32(_p(W), _p(codebook), _p(B), _p(A), _p(q), N, K, r, bits) != 0:
+        raise ValueError("lords_oracle_quantize_f32: bad argument")
+    return q
+
+
+def block_init_f32(W, codebook, r: int, bits: int):
+    W, codebook = _c(W, np.float32), _c(codebook, np.float32)
+    N, K = W.shape
+    B = np.empty((N, r), dtype=np.float32)
+    A = np.empty((r, K), dtype=np.float32)
+    if _load().lords_oracle_block_init_f32(_p(W), _p(codebook), _p(B), _p(A), N, K, r, bits) != 0:
+        raise ValueError("lords_oracle_block_init_f32: bad argument")
+    return B, A

@@ -93,6 +93,24 @@ int lords_dequant(const void *codes, const float *codebook, const void *B, const
                   void *W, int N, int K, int r, int bits,
                   lords_dtype factor_dtype, lords_dtype w_dtype, void *stream);
 
+/* Quantise (the inverse of lords_dequant; Alg. 1, step 2.1): for every element the index of the level
+ * that minimises (S v - W)^2 over the table, S = sum_j B[n][j] A[j][k]; ties go to the lowest index.
+ * The decision is taken in fp32: S by fused multiply-adds in increasing j, d = fma(S, C[i], -W), d*d compared.
+ *   W      in   N x K, dtype `w_dtype`
+ *   codes  out  N x K*bits/8 bytes, packed as described at the top
+ */
+int lords_quantize(const void *W, const float *codebook, const void *B, const void *A, void *codes,
+                   int N, int K, int r, int bits, lords_dtype w_dtype, lords_dtype factor_dtype, void *stream);
+
+/* Block-wise starting point of Alg. 1 (step 1, ComputeScale with block size K/r, read as symmetric absmax
+ * scaling, Sec. 3.1) written as factors: B[n][j] = max |W[n][jg .. jg+g)| / max_i |C[i]|, g = K/r, and
+ * A[j][k] = 1 if k/g == j else 0, so that B A is the piecewise-constant block scale (rank <= r).
+ * K must be a multiple of r (LORDS_ERR_SHAPE otherwise).
+ *   B      out  N x r,  A  out  r x K, dtype `factor_dtype` (bf16: the fp32 value rounded to nearest even)
+ */
+int lords_block_init(const void *W, const float *codebook, void *B, void *A,
+                     int N, int K, int r, int bits, lords_dtype w_dtype, lords_dtype factor_dtype, void *stream);
+
 /* Fused dequantise-and-multiply: Y[m*N + n] = sum_k X[m][k] * W_hat[n][k]
  * (the linear layer the paper's inference kernel replaces, Sec. 4.4; Fig. 1b).
  *   X   in   M x K bf16

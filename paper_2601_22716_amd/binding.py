@@ -15,7 +15,7 @@ STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LOR
                 4: "LORDS_ERR_ALIGN", 5: "LORDS_ERR_DTYPE", 6: "LORDS_ERR_LAUNCH", 7: "LORDS_ERR_UNSUPPORTED"}
 
 EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank",
-           "lords_unpack", "lords_dequant", "lords_matmul", "lords_matmul_ex"]
+           "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex"]
 
 
 class LordsError(RuntimeError):
@@ -57,6 +57,10 @@ def library():
         lib.lords_matmul.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
         lib.lords_matmul_ex.restype = ci
         lib.lords_matmul_ex.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci]
+        lib.lords_quantize.restype = ci
+        lib.lords_quantize.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
+        lib.lords_block_init.restype = ci
+        lib.lords_block_init.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
         _lib = lib
     return _lib
 
@@ -126,6 +130,16 @@ def lords_unpack(codes, idx, N: int, K: int, bits: int, stream=None) -> None:
 def lords_dequant(codes, codebook, B, A, W, N: int, K: int, r: int, bits: int, stream=None) -> None:
     _check(library().lords_dequant(_ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(W), N, K, r, bits,
                                    _dtype_code(B), _dtype_code(W), _stream(stream)), "lords_dequant")
+
+
+def lords_quantize(W, codebook, B, A, codes, N: int, K: int, r: int, bits: int, stream=None) -> None:
+    _check(library().lords_quantize(_ptr(W), _ptr(codebook), _ptr(B), _ptr(A), _ptr(codes), N, K, r, bits,
+                                    _dtype_code(W), _dtype_code(B), _stream(stream)), "lords_quantize")
+
+
+def lords_block_init(W, codebook, B, A, N: int, K: int, r: int, bits: int, stream=None) -> None:
+    _check(library().lords_block_init(_ptr(W), _ptr(codebook), _ptr(B), _ptr(A), N, K, r, bits,
+                                      _dtype_code(W), _dtype_code(B), _stream(stream)), "lords_block_init")
 
 
 def lords_matmul(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int, stream=None) -> None:

@@ -110,6 +110,30 @@ int lords_dequant(const void *codes, const float *codebook, const void *B, const
                                  w_dtype == LORDS_F32, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
 }
 
+int lords_quantize(const void *W, const float *codebook, const void *B, const void *A, void *codes,
+                   int N, int K, int r, int bits, lords_dtype w_dtype, lords_dtype factor_dtype, void *stream)
+{
+    if (!W || !codebook || !B || !A || !codes) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (bad_nk(N, K) || r < 1) return LORDS_ERR_SHAPE;
+    if (misaligned(W) || misaligned(codebook) || misaligned(B) || misaligned(A) || misaligned(codes)) return LORDS_ERR_ALIGN;
+    if (bad_dtype((int)w_dtype) || bad_dtype((int)factor_dtype)) return LORDS_ERR_DTYPE;
+    return lords::launch_quantize(W, codebook, B, A, codes, N, K, r, bits, w_dtype == LORDS_F32,
+                                  factor_dtype == LORDS_F32, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+}
+
+int lords_block_init(const void *W, const float *codebook, void *B, void *A,
+                     int N, int K, int r, int bits, lords_dtype w_dtype, lords_dtype factor_dtype, void *stream)
+{
+    if (!W || !codebook || !B || !A) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (bad_nk(N, K) || r < 1 || (K % r) != 0) return LORDS_ERR_SHAPE;
+    if (misaligned(W) || misaligned(codebook) || misaligned(B) || misaligned(A)) return LORDS_ERR_ALIGN;
+    if (bad_dtype((int)w_dtype) || bad_dtype((int)factor_dtype)) return LORDS_ERR_DTYPE;
+    return lords::launch_block_init(W, codebook, B, A, N, K, r, bits, w_dtype == LORDS_F32,
+                                    factor_dtype == LORDS_F32, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+}
+
 int lords_matmul_ex(const void *X, const void *codes, const float *codebook, const void *B, const void *A, void *Y,
                     int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype y_dtype,
                     void *stream, lords_path path)

@@ -11,6 +11,12 @@ hipError_t launch_unpack(const void *codes, uint8_t *idx, int N, int K, int bits
 hipError_t launch_dequant(const void *codes, const float *codebook, const void *B, const void *A, void *W,
                           int N, int K, int r, int bits, bool f32fact, bool f32out, hipStream_t st);
 
+// Quantisation side (lords_quant.hip).
+hipError_t launch_quantize(const void *W, const float *codebook, const void *B, const void *A, void *codes,
+                           int N, int K, int r, int bits, bool f32w, bool f32fact, hipStream_t st);
+hipError_t launch_block_init(const void *W, const float *codebook, void *B, void *A,
+                             int N, int K, int r, int bits, bool f32w, bool f32fact, hipStream_t st);
+
 struct MatmulProblem {
     const void *X;          // M x K bf16
     const void *codes;      // N x K*bits/8

@@ -92,6 +92,41 @@ def test_dequant_argument_checks():
     assert f(*a) == 1
 
 
+def test_quantize_argument_checks():
+    f = L.library().lords_quantize
+    ok = [P, P, P, P, P, 8, 64, 4, 4, 1, 0, None]
+    for i in range(5):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[8] = 5
+    assert f(*a) == 2
+    for i, v in ((5, 0), (6, 48), (7, 0)):
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    a = list(ok); a[4] = P + 8
+    assert f(*a) == 4
+    for i in (9, 10):
+        a = list(ok); a[i] = 3
+        assert f(*a) == 5
+
+
+def test_block_init_argument_checks():
+    f = L.library().lords_block_init
+    ok = [P, P, P, P, 8, 64, 4, 4, 1, 0, None]
+    for i in range(4):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[7] = 1
+    assert f(*a) == 2
+    for i, v in ((4, 0), (5, 40), (6, 0), (6, 3)):          # the last: K not a multiple of r
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    a = list(ok); a[2] = P + 2
+    assert f(*a) == 4
+    a = list(ok); a[8] = 9
+    assert f(*a) == 5
+
+
 def test_matmul_argument_checks():
     f = L.library().lords_matmul
     fx = L.library().lords_matmul_ex

@@ -18,6 +18,9 @@
 namespace lords {
 
 // One thread per group of 32 consecutive elements of one row: 32 scales, 32 searches, BITS dwords out.
+// The 128 threads of a workgroup take the SAME 32 columns of 128 consecutive rows, so the A values
+// of a step of the j loop are the same for every lane (scalar loads, operands straight from scalar
+// registers) and only B is read per lane.
 template <int BITS, bool F32FACT, bool F32W>
 __global__ __launch_bounds__(128) void quantize_kernel(const void *__restrict__ Wv, const float *__restrict__ codebook,
                                                        const void *__restrict__ Bv, const void *__restrict__ Av,
@@ -28,10 +31,9 @@ __global__ __launch_bounds__(128) void quantize_kernel(const void *__restrict__ 
     if (threadIdx.x < NL) lut[threadIdx.x] = codebook[threadIdx.x];
     __syncthreads();
     const int gpr = K / 32;                                  // groups per row
-    const int blocks_per_row = (gpr + 127) / 128;
-    const int n = blockIdx.x / blocks_per_row;
-    const int grp = (blockIdx.x % blocks_per_row) * 128 + threadIdx.x;
-    if (grp >= gpr) return;
+    const int grp = blockIdx.y;
+    const int row = blockIdx.x * 128 + threadIdx.x;
+    const int n = row < N ? row : N - 1;                     // rows >= N: recomputed, never stored
     const int k0 = grp * 32;
 
     float s[32];
@@ -108,6 +110,7 @@ __global__ __launch_bounds__(128) void quantize_kernel(const void *__restrict__ 
         out[dw] |= best << sh;
         if (sh + BITS > 32) out[dw + 1 < BITS ? dw + 1 : dw] |= best >> (32 - sh);
     }
+    if (row >= N) return;
     uint32_t *dst = reinterpret_cast<uint32_t *>(codes + ((size_t)n * gpr + grp) * (4 * BITS));
 #pragma unroll
     for (int d = 0; d < BITS; ++d) dst[d] = out[d];
@@ -156,8 +159,7 @@ template <int BITS>
 static hipError_t launch_quantize_bits(const void *W, const float *codebook, const void *B, const void *A, void *codes,
                                        int N, int K, int r, bool f32w, bool f32fact, hipStream_t st)
 {
-    const long blocks_per_row = (K / 32 + 127) / 128;
-    const dim3 grid((unsigned)(blocks_per_row * N)), block(128);
+    const dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / 32)), block(128);
 #define LORDS_QCASE(FF_, FW_) \
     hipLaunchKernelGGL((quantize_kernel<BITS, FF_, FW_>), grid, block, 0, st, W, codebook, B, A, (uint8_t *)codes, N, K, r)
     if (f32fact) { if (f32w) LORDS_QCASE(true, true); else LORDS_QCASE(true, false); }

@@ -64,18 +64,21 @@ struct M1Args {
 template <int BITS, int JT, int G, bool BVEC, bool F32>
 __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_m1_kernel(M1Args a)
 {
-    constexpr int KT = 128 * G, AST = KT + 8, NL = 1 << BITS, NE = 1 << (2 * BITS), CPR = KT / 8;
+    constexpr int CBW = G == 1 ? 4 : 1, NSG = kM1Waves / CBW;        // column blocks per workgroup, waves per block
+    constexpr int KT = 128 * G, WK = CBW * KT, AST = WK + 8, NL = 1 << BITS, NE = 1 << (2 * BITS), CPR = WK / 8;
     constexpr int JR = F32 ? JT / 2 : JT;                   // tiles of the rank itself
     constexpr int QW = 4 * JR;                              // rank entries per lane group
     constexpr int BW = F32 ? QW : QW / 2;                   // dwords of B per lane and slab
     constexpr int LUT_BYTES = NE * 256, A_BYTES = JT * 16 * AST * 2;
     extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t *As = reinterpret_cast<uint16_t *>(smem + LUT_BYTES);        // [JT*16][AST]
+    uint16_t *As = reinterpret_cast<uint16_t *>(smem + LUT_BYTES);        // [JT*16][AST]; later the block sums
     int *flag = reinterpret_cast<int *>(smem + LUT_BYTES + A_BYTES);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
-    const int kb = blockIdx.z * KT;
+    const int cb = wave % CBW, sg = wave / CBW;                // this wave's column block and slab group
+    const int kw = blockIdx.z * WK;                            // first column of the workgroup
+    const int kb = kw + cb * KT;                               // first column of this wave
     const int N = a.N, K = a.K, r = a.r;
     const uint32_t laneoff = (uint32_t)lane * 4u;
     const int ngroups = K >> 5;
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
     // they can run kDepth slabs ahead: codes of columns >= K meet zero a-operands, rank entries
     // >= r meet zero rows of the A tile (and are zeroed here), rows >= N are dropped at the store.
     int chunk = blockIdx.x;
-    int slab0 = (chunk * kM1Waves + wave) * a.ns;                    // this wave's first slab
+    int slab0 = (chunk * NSG + sg) * a.ns;                           // this wave's first slab
     uint32_t cw[kNS][G][BITS];
     uint32_t Bq[kNS][BW];
     auto issue = [&](int i) __attribute__((always_inline)) {
@@ -128,7 +131,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
     //         so the other way round the set-up would wait for the stream. --------------------------
     constexpr int NCH = JT * 16 * CPR / kM1Threads;           // 16-byte chunks of the A tile per thread
     constexpr int NIT = (NE * 16 + kM1Threads - 1) / kM1Threads;
-    const int kc = tid % CPR, k0 = kb + 8 * kc;               // the thread's column chunk is fixed
+    const int kc = tid % CPR, k0 = kw + 8 * kc;               // the thread's column chunk is fixed
     u32x4 xv = u32x4{0u, 0u, 0u, 0u};
     u32x4 tmp[F32 ? 1 : NCH];
     float lo[NIT], hi[NIT];
@@ -170,12 +173,12 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
         }
     } else {
         // fp32 factors (not the fast case): the fp32 product, split into a bf16 hi and lo tile
-        for (int id = tid; id < JR * 16 * KT; id += kM1Threads) {
-            const int jj = id / KT, kk = id % KT, t = jj >> 4, i = jj & 15;
+        for (int id = tid; id < JR * 16 * WK; id += kM1Threads) {
+            const int jj = id / WK, kk = id % WK, t = jj >> 4, i = jj & 15;
             const int j = QW * (i >> 2) + 4 * t + (i & 3);
             float p = 0.f;
-            if (j < r && kb + kk < K)
-                p = reinterpret_cast<const float *>(a.A)[(size_t)j * K + kb + kk] * bf16_to_f32(a.X[kb + kk]);
+            if (j < r && kw + kk < K)
+                p = reinterpret_cast<const float *>(a.A)[(size_t)j * K + kw + kk] * bf16_to_f32(a.X[kw + kk]);
             const uint16_t ph = bf16_bits(p);
             As[jj * AST + kk] = ph;
             As[(JR * 16 + jj) * AST + kk] = bf16_bits(p - bf16_to_f32(ph));
@@ -202,13 +205,14 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
         for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int t = 0; t < JT; ++t)
-                Aop[v][u][t] = *reinterpret_cast<const bf16x8 *>(As + (16 * t + c) * AST + 32 * (G * g + v) + 8 * u);
+                Aop[v][u][t] = *reinterpret_cast<const bf16x8 *>(As + (16 * t + c) * AST + cb * KT + 32 * (G * g + v) + 8 * u);
+    if (CBW > 1) __syncthreads();                          // every wave has its operands: the tile region may be reused
     LORDS_STAMP_WG(2);
 
     // ---- 4. the row stream, chunk by chunk ------------------------------------------------------
     for (; chunk < a.nchunks; chunk += gridDim.x) {
         if (chunk != (int)blockIdx.x) {
-            slab0 = (chunk * kM1Waves + wave) * a.ns;
+            slab0 = (chunk * NSG + sg) * a.ns;
 #pragma unroll
             for (int i = 0; i < kDepth; ++i) issue(i);
         }
@@ -273,18 +277,43 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
         for (int i = 0; i < kNS; ++i) ysum[i] += t16[i];
 #pragma unroll
         for (int i = 0; i < kNS; ++i) t16[i] = __shfl_xor(ysum[i], 32);
+        if (CBW == 1) {
 #pragma unroll
-        for (int i = 0; i < kNS; ++i) {
-            if (i < nsw) {
-                const float v = ysum[i] + t16[i];
-                const int n = (slab0 + i) * 16 + c;
-                if (g == 0 && n < N) {
+            for (int i = 0; i < kNS; ++i) {
+                if (i < nsw) {
+                    const float v = ysum[i] + t16[i];
+                    const int n = (slab0 + i) * 16 + c;
+                    if (g == 0 && n < N) {
+                        if (a.kblocks > 1)
+                            __hip_atomic_store(&a.partial[(size_t)blockIdx.z * N + n], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        else if (a.y_f32) reinterpret_cast<float *>(a.Y)[n] = v;
+                        else reinterpret_cast<uint16_t *>(a.Y)[n] = bf16_bits(v);
+                    }
+                }
+            }
+        } else {
+            // the column blocks of this workgroup meet in LDS (the A tile is dead) and are added in block order
+            float *red = reinterpret_cast<float *>(As);                  // [kM1Waves][kNS*16]
+            if (g == 0) {
+#pragma unroll
+                for (int i = 0; i < kNS; ++i) red[wave * (kNS * 16) + i * 16 + c] = ysum[i] + t16[i];
+            }
+            __syncthreads();
+            const int rows_sg = a.ns * 16;                               // rows of one slab group
+            if (tid < NSG * rows_sg) {
+                const int sgr = tid / rows_sg, rem = tid - sgr * rows_sg;
+                float v = 0.f;
+#pragma unroll
+                for (int w = 0; w < CBW; ++w) v += red[(sgr * CBW + w) * (kNS * 16) + rem];
+                const int n = (chunk * NSG + sgr) * rows_sg + rem;
+                if (n < N) {
                     if (a.kblocks > 1)
                         __hip_atomic_store(&a.partial[(size_t)blockIdx.z * N + n], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     else if (a.y_f32) reinterpret_cast<float *>(a.Y)[n] = v;
                     else reinterpret_cast<uint16_t *>(a.Y)[n] = bf16_bits(v);
                 }
             }
+            __syncthreads();                                             // the sums are rewritten by the next chunk
         }
         LORDS_STAMP_WG(4);
     }
@@ -314,7 +343,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
             for (int t = 0; t < nt; ++t) {
                 if (!flag[t]) continue;
                 const int ch = blockIdx.x + (base + t) * gridDim.x;
-                const int row0 = ch * kM1Waves * a.ns * 16, rows = kM1Waves * a.ns * 16;
+                const int row0 = ch * NSG * a.ns * 16, rows = NSG * a.ns * 16;
                 // two rows per thread and pass, all their loads in flight at once; blocks added in order
                 for (int q = tid; q < rows; q += 2 * kM1Threads) {
                     const int n0 = min(row0 + q, N - 1), n1 = min(row0 + q + kM1Threads, N - 1);
@@ -385,15 +414,16 @@ static M1Plan m1_plan(const MatmulProblem &p)
     d.jt = m1_jt(p);
     d.G = d.jt == 2 ? 2 : 1;
     d.KT = 128 * d.G;
-    d.kblocks = (p.K + d.KT - 1) / d.KT;
+    const int cbw = d.G == 1 ? 4 : 1, nsg = kM1Waves / cbw;      // as in the kernel
+    d.kblocks = (p.K + cbw * d.KT - 1) / (cbw * d.KT);
     const int nslabs = (p.N + 15) / 16;
     int gx = 256 / d.kblocks;                          // one resident workgroup per CU
     if (gx < 1) gx = 1;
-    int ns = (nslabs + kM1Waves * gx - 1) / (kM1Waves * gx);
+    int ns = (nslabs + nsg * gx - 1) / (nsg * gx);
     if (ns > kNS) ns = kNS;
     if (ns < 1) ns = 1;
     d.ns = ns;
-    d.nchunks = (nslabs + kM1Waves * ns - 1) / (kM1Waves * ns);
+    d.nchunks = (nslabs + nsg * ns - 1) / (nsg * ns);
     d.gx = gx < d.nchunks ? gx : d.nchunks;
     return d;
 }
@@ -415,7 +445,7 @@ size_t decode_m1_workspace_bytes(const MatmulProblem &p)
 template <int BITS, int JT, int G, bool BVEC, bool F32>
 static hipError_t launch_m1_t(const M1Args &a, dim3 grid, hipStream_t st)
 {
-    constexpr int KT = 128 * G, AST = KT + 8;
+    constexpr int KT = 128 * G, AST = (G == 1 ? 4 : 1) * KT + 8;
     const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)JT * 16 * AST * 2 + kM1Tickets * sizeof(int);
     static bool attr_set = false;
     if (!attr_set && smem > 48 * 1024) {

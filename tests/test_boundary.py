@@ -158,3 +158,13 @@ def test_binding_raises_with_status_name():
     with pytest.raises(L.LordsError) as e:
         L.binding._check(4, "lords_matmul")
     assert "LORDS_ERR_ALIGN" in str(e.value)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py must say so and exit before touching any device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""

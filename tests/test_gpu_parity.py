@@ -182,10 +182,10 @@ def test_matmul_blockwise_case(gpu, bits, group):
 
 # ------------------------------------------------- full-size layers, sampled
 FULL = [
-    ("qproj_4b", 1), ("qproj_4b", 16),
-    ("gateup_3b", 1), ("down_3b", 16),
+    ("qproj_4b", 1), ("qproj_4b", 4), ("qproj_4b", 16),
+    ("gateup_3b", 1), ("gateup_3b", 16), ("down_3b", 16),
     ("gateup_4b", 1), ("gateup_4b", 2048), ("down_4b", 2048),
-    ("l70b_2b", 1), ("l70b_2b", 256),
+    ("l70b_2b", 1), ("l70b_2b", 16), ("l70b_2b", 256), ("l70b_2b", 4096),
 ]
 
 

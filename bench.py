@@ -160,6 +160,36 @@ def bench_prefill(args, L, li, torch):
     }
 
 
+def bench_other(args, L, li, torch):
+    """Context figures on the same layer: the other token counts the method is quoted at (not the headline)."""
+    name = "gateup_4b"
+    cfg = li.CONFIGS[name]
+    out = []
+    for M in (4, 16, 256, 4096):
+        decode = M <= 32
+        nsets = int(-(-COLD_BYTES // (cfg.N * cfg.K * cfg.bits // 8))) if decode else 2
+        cs, sets, X, codebook = make_sets(name, M, nsets, li, torch)
+        Y = torch.zeros((M, cfg.N), dtype=torch.float32 if decode else torch.bfloat16, device="cuda")
+
+        def run_step(i):
+            codes, B, A = sets[i % nsets]
+            L.lords_matmul(X, codes, codebook, B, A, Y, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+
+        steps = 100 if decode else 10
+        wall, ev_ms, mode, _ = time_steps(run_step, steps, 5, torch, use_graph=not args.no_graph)
+        us = ev_ms * 1e3 / steps
+        if decode:
+            ab = algorithmic_bytes(M, cfg.N, cfg.K, cfg.r, cfg.bits)
+            out.append({"workload": f"decode M={M}", "us_per_launch": us, "value": ab / us / 1e3, "unit": "GB/s",
+                        "frac_of_hbm_peak": ab / us / 1e3 / HBM_PEAK_GBS})
+        else:
+            fl = 2.0 * M * cfg.N * cfg.K
+            out.append({"workload": f"prefill M={M}", "us_per_launch": us, "value": fl / us / 1e6, "unit": "TFLOP/s",
+                        "frac_of_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS})
+        del sets, X, Y
+    return out
+
+
 def cpu_baseline(li, ab):
     """The fp64 C oracle, as it stands, on the decode workload (M = 1, whole layer), host cores."""
     from oracle import lords_oracle_c as oc
@@ -217,6 +247,8 @@ def main():
             line.update({k: p[k] for k in ("metric", "value", "unit", "steps", "ms_per_step", "config", "roofline")})
         else:
             line["prefill"] = p
+    if args.workload == "all" and not args.calibrate_copy:
+        line["other_workloads"] = bench_other(args, L, li, torch)
     if args.calibrate_copy:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

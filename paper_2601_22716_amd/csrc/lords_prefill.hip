@@ -338,12 +338,18 @@ static hipError_t launch_pf_t(const PrefillArgs &a, int grid, hipStream_t st)
 hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
 {
     const int ss = pf_ss(p.r);
-    const int wm = ss == 1 ? 2 : 1;
+    // Tile shapes, largest first: 256 tokens x 256 rows (8 waves, 4 slabs each), 256 x 128, and for
+    // shapes that would leave CUs idle 128 tokens x 128 rows (4 waves).  Padded ranks above 32 take
+    // 128-token tiles only (their B operands need the registers).
+    int wm = ss == 1 ? 2 : 1, R = 2;
+    if (ss == 1) {
+        const long t256 = (long)((p.N + 255) / 256) * ((p.M + 255) / 256);
+        const long t128 = (long)((p.N + 127) / 128) * ((p.M + 255) / 256);
+        if (t256 >= 224) R = 4;
+        else if (t128 < 200) wm = 1;
+    }
     const int BM = 128 * wm;
-    // Four slabs per wave (256-row tiles) when that still gives every CU a tile and the B operands
-    // fit the register budget; two slabs (128-row tiles) otherwise.
     const int mt = (p.M + BM - 1) / BM;
-    const int R = (ss == 1 && (long)((p.N + 255) / 256) * mt >= 224) ? 4 : 2;
     PrefillArgs a;
     a.X = (const uint16_t *)p.X;
     a.codes = (const uint8_t *)p.codes;
@@ -359,12 +365,14 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
     a.ntiles_k = (p.K + 127) / 128;
     const int total = a.nt * a.mt;
     const int grid = ((total + 7) / 8) * 8;
-#define LORDS_PCASE(B_, S_, M_)                                              \
-    if (p.bits == B_ && ss == S_)                                            \
-        return R == 4 ? launch_pf_t<B_, S_, M_, (S_ == 1 ? 4 : 2)>(a, grid, st) : launch_pf_t<B_, S_, M_, 2>(a, grid, st);
-    LORDS_PCASE(2, 1, 2) LORDS_PCASE(2, 2, 1) LORDS_PCASE(2, 4, 1)
-    LORDS_PCASE(3, 1, 2) LORDS_PCASE(3, 2, 1) LORDS_PCASE(3, 4, 1)
-    LORDS_PCASE(4, 1, 2) LORDS_PCASE(4, 2, 1) LORDS_PCASE(4, 4, 1)
+#define LORDS_PCASE(B_, S_)                                                                     \
+    if (p.bits == B_ && ss == S_) {                                                              \
+        if (S_ == 1 && wm == 2) return R == 4 ? launch_pf_t<B_, 1, 2, 4>(a, grid, st) : launch_pf_t<B_, 1, 2, 2>(a, grid, st); \
+        return launch_pf_t<B_, S_, 1, 2>(a, grid, st);                                           \
+    }
+    LORDS_PCASE(2, 1) LORDS_PCASE(2, 2) LORDS_PCASE(2, 4)
+    LORDS_PCASE(3, 1) LORDS_PCASE(3, 2) LORDS_PCASE(3, 4)
+    LORDS_PCASE(4, 1) LORDS_PCASE(4, 2) LORDS_PCASE(4, 4)
 #undef LORDS_PCASE
     return hipErrorInvalidValue;
 }

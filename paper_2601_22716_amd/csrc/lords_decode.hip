@@ -97,7 +97,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
         }
     };
 
-    LORDS_STAMP(0);
     // ---- 0. first loads of the row stream go out before any set-up --------------------------
 #pragma unroll
     for (int i = 0; i < kDepth; ++i) issue(i);
@@ -169,7 +168,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
         }
     }
 
-    LORDS_STAMP(1);
     // ---- 2. level table: entry idx = (code_hi << BITS) | code_lo, 64 copies ------------------
     __syncthreads();
     {
@@ -185,7 +183,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
     }
     __syncthreads();
 
-    LORDS_STAMP(2);
     // ---- 3. activations of this block: b-operands of the product MFMAs -----------------------
     bf16x8 Xop[M1 ? 1 : G][4];
     if (!M1) {
@@ -251,10 +248,8 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
         }
     }
 
-    LORDS_STAMP(3);
     // ---- 5. add the four column blocks of this workgroup (fixed order) -------------------------
     __syncthreads();                               // the table is dead from here on
-    LORDS_STAMP(4);
     if (M1) {
         float *red = reinterpret_cast<float *>(smem);  // [4][kNS][64]
 #pragma unroll
@@ -302,7 +297,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
         }
     }
 
-    LORDS_STAMP(5);
     // ---- 6. column blocks held by other workgroups: the last one to arrive adds them -----------
     if (a.splits > 1) {
         // The partial sums were written with device-coherent (write-through) stores, so waiting
@@ -331,7 +325,6 @@ __global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a)
             }
         }
     }
-    LORDS_STAMP(6);
 }
 
 

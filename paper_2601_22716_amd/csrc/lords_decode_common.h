@@ -7,10 +7,7 @@
 namespace lords {
 
 constexpr int kNS = 8;       // max slabs (of 16 rows) per workgroup
-#ifndef LORDS_DEPTH
-#define LORDS_DEPTH 2
-#endif
-constexpr int kDepth = LORDS_DEPTH;    // slabs whose loads are in flight ahead of the one computed
+constexpr int kDepth = 2;    // slabs whose loads are in flight ahead of the one computed
 
 struct DecodeArgs {
     const uint16_t *X;
@@ -57,31 +54,6 @@ __device__ __forceinline__ uint32_t pair_addr(const uint32_t (&w)[BITS], int p, 
     if (s + 2 * BITS > 32) v |= w[(d + 1) < BITS ? d + 1 : d] << (32 - s);
     return ((v & ((1u << (2 * BITS)) - 1u)) << 8) | laneoff;
 }
-
-#ifdef LORDS_PHASE_TIMING
-// Development aid (never compiled into the shipped library): 100 MHz time stamps of the phases
-// of workgroup (0,0,0) and of the last workgroup, read back by the micro-benchmark.
-static __device__ unsigned long long lords_phase_times[2][16];   // one copy per translation unit
-#define LORDS_STAMP(k)                                                                             \
-    do {                                                                                           \
-        if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.z == 0) lords_phase_times[0][k] = wall_clock64(); \
-        if (threadIdx.x == 0 && blockIdx.x == gridDim.x - 1 && blockIdx.z == gridDim.z - 1) lords_phase_times[1][k] = wall_clock64(); \
-    } while (0)
-static __device__ unsigned long long lords_wg_times[4096][8];
-#define LORDS_STAMP_WG(k)                                                                          \
-    do {                                                                                           \
-        const unsigned wg_ = blockIdx.x + gridDim.x * blockIdx.z;                                  \
-        if (threadIdx.x == 0 && wg_ < 4096) lords_wg_times[wg_][k] = wall_clock64();               \
-    } while (0)
-#define LORDS_STAMP_ALL(k, op)                                                                      \
-    do {                                                                                           \
-        if (threadIdx.x == 0) op(&lords_phase_times[1][k], (unsigned long long)wall_clock64());          \
-    } while (0)
-#else
-#define LORDS_STAMP(k) do { } while (0)
-#define LORDS_STAMP_WG(k) do { } while (0)
-#define LORDS_STAMP_ALL(k, op) do { } while (0)
-#endif
 
 __device__ __forceinline__ uint32_t lds_load_u32(uint32_t byte_addr)
 {

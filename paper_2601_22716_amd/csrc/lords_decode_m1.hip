@@ -83,7 +83,6 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
     const uint32_t laneoff = (uint32_t)lane * 4u;
     const int ngroups = K >> 5;
 
-    LORDS_STAMP_WG(0);
     // Loads of slab i of the current chunk, branch-free (addresses clamped into the arrays) so that
     // they can run kDepth slabs ahead: codes of columns >= K meet zero a-operands, rank entries
     // >= r meet zero rows of the A tile (and are zeroed here), rows >= N are dropped at the store.
@@ -197,7 +196,6 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
         }
     }
     __syncthreads();
-    LORDS_STAMP_WG(1);
     bf16x8 Aop[G][4][JT];
 #pragma unroll
     for (int v = 0; v < G; ++v)
@@ -207,7 +205,6 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
             for (int t = 0; t < JT; ++t)
                 Aop[v][u][t] = *reinterpret_cast<const bf16x8 *>(As + (16 * t + c) * AST + cb * KT + 32 * (G * g + v) + 8 * u);
     if (CBW > 1) __syncthreads();                          // every wave has its operands: the tile region may be reused
-    LORDS_STAMP_WG(2);
 
     // ---- 4. the row stream, chunk by chunk ------------------------------------------------------
     for (; chunk < a.nchunks; chunk += gridDim.x) {
@@ -266,7 +263,6 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        LORDS_STAMP_WG(3);
 
         // ---- 5. add the four lanes of each row (two cross-lane steps, each issued for all slabs
         //         before its results are used), hand the row sums over -------------------------------
@@ -315,7 +311,6 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
             }
             __syncthreads();                                             // the sums are rewritten by the next chunk
         }
-        LORDS_STAMP_WG(4);
     }
 
     // ---- 6. other column blocks: for every chunk this workgroup streamed, the last workgroup to
@@ -339,7 +334,6 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
                 flag[tid] = last;
             }
             __syncthreads();
-            LORDS_STAMP_WG(5);
             for (int t = 0; t < nt; ++t) {
                 if (!flag[t]) continue;
                 const int ch = blockIdx.x + (base + t) * gridDim.x;
@@ -373,26 +367,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
             __syncthreads();                               // the flags are rewritten by the next batch
         }
     }
-    LORDS_STAMP_WG(6);
 }
-
-#ifdef LORDS_PHASE_TIMING
-// Development aid, never part of the shipped library: read back the time stamps.
-extern "C" int lords_debug_phase_times(unsigned long long *out)
-{
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(lords_phase_times), sizeof(unsigned long long) * 32);
-}
-extern "C" int lords_debug_wg_times(unsigned long long *out)
-{
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(lords_wg_times), sizeof(unsigned long long) * 4096 * 8);
-}
-extern "C" int lords_debug_reset()
-{
-    unsigned long long init[32];
-    for (int i = 0; i < 32; ++i) init[i] = 0ull;
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(lords_phase_times), init, sizeof(init));
-}
-#endif
 
 // ---------------------------------------------------------------------------------------------
 // host side

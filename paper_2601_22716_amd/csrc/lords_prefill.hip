@@ -260,11 +260,7 @@ __global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))
             dequant_stage(u, W);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-#ifdef LORDS_EXP_NOXCONF
-                const bf16x8 Xop = *reinterpret_cast<const bf16x8 *>(Xp + mb * 4096 + lane * 16 + u * 1024);   // experiment only
-#else
                 const bf16x8 Xop = *reinterpret_cast<const bf16x8 *>(Xp + mb * 4096 + xoff[u]);
-#endif
 #pragma unroll
                 for (int rho = 0; rho < R; ++rho)
                     acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W[rho], Xop, acc[rho][mb], 0, 0, 0);

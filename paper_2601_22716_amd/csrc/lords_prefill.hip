@@ -68,10 +68,11 @@ __device__ __forceinline__ uint32_t pair_index(const uint32_t (&w)[BITS], int p)
     return v & ((1u << (2 * BITS)) - 1u);
 }
 
-template <int BITS, int SS, int WM, int R>
-__global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(PrefillArgs a)
+template <int BITS, int SS, int WM, int R, int WN = 4>
+__global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(PrefillArgs a)
 {
-    constexpr int MB = 8, BN = 64 * R, BM = 128 * WM, NT = 256 * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
+    constexpr int MB = 8, BN = 16 * R * WN, BM = 128 * WM, NT = 64 * WN * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
+    constexpr int RPP = 4 * WN * WM;                           // tile rows one staging pass of the workgroup covers
     constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *Xs = smem;                                   // [2][BM][256 B]
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int T = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if ((int)(blockIdx.x >> 3) >= per_xcd || T >= total) return;
     const int m_blk = (T / a.nt) * BM, n_blk = (T % a.nt) * BN;
-    const int wn = wave & 3, wm = wave >> 2;
+    const int wn = wave % WN, wm = wave / WN;
     const int n_wave = n_blk + 16 * R * wn;
     const int m_wave = m_blk + 128 * wm;
 
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))
     // ---- staging of one K tile into buffer p (direct to LDS) and of its codes into registers ---------
     // The loops over the 4-row groups are kept rolled on purpose: unrolled, their loop-invariant
     // row addresses get hoisted into dozens of registers that the accumulators need.
-    const int xm0 = 4 * wave + (lane >> 4);                   // first tile row this lane fetches; then +16*WM per step
+    const int xm0 = 4 * wave + (lane >> 4);                   // first tile row this lane fetches; then +RPP per step
     const int xkc = (lane & 15) ^ (xm0 & 15);                 // its column chunk (same for every step)
     auto stage = [&](int kt, int p) {
         const int kb = kt * 128;
@@ -143,22 +144,22 @@ __global__ __launch_bounds__(256 * WM) __attribute__((amdgpu_waves_per_eu(2, 2))
             const int k = min(kb + 8 * xkc, K - 8);            // ragged last tile: any finite data will do
             unsigned char *dst = Xs + p * XBUF + wave * 1024;
 #pragma nounroll
-            for (int q = 0; q < BM / (16 * WM); ++q) {
-                const int m = min(m_blk + xm0 + 16 * WM * q, M - 1);   // rows >= M: a copy of the last row, never stored
-                lds_direct_16(a.X + (size_t)m * K + k, dst + q * (4096 * WM));
+            for (int q = 0; q < BM / RPP; ++q) {
+                const int m = min(m_blk + xm0 + RPP * q, M - 1);   // rows >= M: a copy of the last row, never stored
+                lds_direct_16(a.X + (size_t)m * K + k, dst + q * (RPP * 256));
             }
         }
         {
             const int k = kb + 8 * xkc;
             unsigned char *dst = As + p * ABUF + wave * 1024;
 #pragma nounroll
-            for (int q = 0; q < (RP + 16 * WM - 1) / (16 * WM); ++q) {
-                const int j = xm0 + 16 * WM * q;
+            for (int q = 0; q < (RP + RPP - 1) / RPP; ++q) {
+                const int j = xm0 + RPP * q;
                 if (j < a.r && k < K) {
-                    lds_direct_16(a.A + (size_t)j * K + k, dst + q * (4096 * WM));
+                    lds_direct_16(a.A + (size_t)j * K + k, dst + q * (RPP * 256));
                 } else if (kb + 128 > K && j < a.r) {
                     // ragged last tile: columns >= K of a live rank row must read as zero
-                    *reinterpret_cast<u32x4 *>(dst + q * (4096 * WM) + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
+                    *reinterpret_cast<u32x4 *>(dst + q * (RPP * 256) + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
                 }
             }
         }
@@ -316,18 +317,18 @@ static int pf_ss(int r)
 
 bool prefill_fast_supported(const MatmulProblem &p) { return !p.f32fact && pf_ss(p.r) != 0; }
 
-template <int BITS, int SS, int WM, int R>
+template <int BITS, int SS, int WM, int R, int WN = 4>
 static hipError_t launch_pf_t(const PrefillArgs &a, int grid, hipStream_t st)
 {
     const size_t smem = (size_t)2 * (128 * WM) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM, R>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM, R, WN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM, R>), dim3(grid), dim3(256 * WM), smem, st, a);
+    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM, R, WN>), dim3(grid), dim3(64 * WN * WM), smem, st, a);
     return hipGetLastError();
 }
 
@@ -336,13 +337,17 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
     const int ss = pf_ss(p.r);
     // Tile shapes, largest first: 256 tokens x 256 rows (8 waves, 4 slabs each), 256 x 128, and for
     // shapes that would leave CUs idle 128 tokens x 128 rows (4 waves).  Padded ranks above 32 take
-    // 128-token tiles only (their B operands need the registers).
-    int wm = ss == 1 ? 2 : 1, R = 2;
+    // 128-token tiles only (their B operands need the registers, their A tile the LDS): 8 waves side
+    // by side along N (256 rows) when that still gives every CU a tile, else 4 waves (128 rows).
+    int wm = ss == 1 ? 2 : 1, R = 2, wn = 4;
     if (ss == 1) {
         const long t256 = (long)((p.N + 255) / 256) * ((p.M + 255) / 256);
         const long t128 = (long)((p.N + 127) / 128) * ((p.M + 255) / 256);
         if (t256 >= 224) R = 4;
         else if (t128 < 200) wm = 1;
+    } else {
+        const long t = (long)((p.N + 255) / 256) * ((p.M + 127) / 128);
+        if (t >= 200) wn = 8;
     }
     const int BM = 128 * wm;
     const int mt = (p.M + BM - 1) / BM;
@@ -356,7 +361,7 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
     a.M = p.M; a.N = p.N; a.K = p.K; a.r = p.r;
     a.y_f32 = p.f32out ? 1 : 0;
     a.row_bytes = p.K / 8 * p.bits;
-    a.nt = (p.N + 64 * R - 1) / (64 * R);
+    a.nt = (p.N + 16 * R * wn - 1) / (16 * R * wn);
     a.mt = mt;
     a.ntiles_k = (p.K + 127) / 128;
     const int total = a.nt * a.mt;
@@ -364,6 +369,7 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
 #define LORDS_PCASE(B_, S_)                                                                     \
     if (p.bits == B_ && ss == S_) {                                                              \
         if (S_ == 1 && wm == 2) return R == 4 ? launch_pf_t<B_, 1, 2, 4>(a, grid, st) : launch_pf_t<B_, 1, 2, 2>(a, grid, st); \
+        if (S_ > 1 && wn == 8) return launch_pf_t<B_, S_ == 1 ? 2 : S_, 1, 2, 8>(a, grid, st);    \
         return launch_pf_t<B_, S_, 1, 2>(a, grid, st);                                           \
     }
     LORDS_PCASE(2, 1) LORDS_PCASE(2, 2) LORDS_PCASE(2, 4)

@@ -36,6 +36,15 @@ block-wise scale it starts from):
               same S as the SVD factors of Alg. 1 step 1 (rank(S) <= r, Sec. 3.1)
   pack_codes  indices -> packed rows (inverse of unpack_codes)
 
+Layers that share their input (every linear layer of a block is quantised on its
+own, Sec. 4.3; Q/K/V and Gate/Up of the module list in Table 7 read one input):
+
+  matmul_batched   Y_l = X W_hat_l^T for each layer l, by the definition above
+  gate_up          H = silu(X W_hat_gate^T) (.) (X W_hat_up^T),
+                   silu(g) = g / (1 + e^-g): the gated MLP the Gate and Up
+                   modules belong to (the model's own activation, not part of
+                   the paper's method), written out from its definition
+
 Pins (see tests/test_oracle_pins.py): hand-derived byte vectors for the
 unpacker, scalar brute force on tiny inputs, the block-wise special case
 (paper Sec. 3.1), identity activations, the rank-1 closed form, the all-ones
@@ -95,6 +104,26 @@ def matmul_rows(X, codes, codebook, B, A, bits: int, rows) -> np.ndarray:
     without forming all of W_hat."""
     rows = np.asarray(rows, dtype=np.int64)
     return matmul(X, np.asarray(codes)[rows], codebook, np.asarray(B)[rows], A, bits)
+
+
+def matmul_batched(X, layers, codebook, bits: int):
+    """[Y_l] for layers = [(codes_l, B_l, A_l), ...] sharing X and the level table:
+    nothing but the single-layer definition, layer by layer."""
+    return [matmul(X, codes, codebook, B, A, bits) for (codes, B, A) in layers]
+
+
+def silu(g) -> np.ndarray:
+    """g / (1 + exp(-g)) in fp64, evaluated without overflow for large |g|."""
+    g = np.asarray(g, dtype=np.float64)
+    e = np.exp(-np.abs(g))                     # in (0, 1]
+    return np.where(g >= 0, g / (1.0 + e), g * e / (1.0 + e))
+
+
+def gate_up(X, gate, up, codebook, bits: int) -> np.ndarray:
+    """H = silu(X W_hat_gate^T) (.) (X W_hat_up^T), fp64 [M, N]; gate, up = (codes, B, A)."""
+    G = matmul(X, gate[0], codebook, gate[1], gate[2], bits)
+    U = matmul(X, up[0], codebook, up[1], up[2], bits)
+    return silu(G) * U
 
 
 def equivalent_rank(N: int, K: int, group: int) -> int:

@@ -131,6 +131,37 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook,
                     lords_dtype factor_dtype, lords_dtype y_dtype, void *stream,
                     lords_path path);
 
+/* Several quantised matrices applied to the SAME activations: Y[l] = X W_hat[l]^T for l = 0 .. L-1.
+ * Every linear layer of a transformer block carries its own codes and factors (Sec. 4.3; module
+ * list of Table 7), and the query/key/value projections (and gate/up) read one input; at one token a
+ * layer is a few microseconds of memory traffic, so the end-to-end decode rate (Sec. 4.4, Table 6)
+ * is set by per-launch overheads that one launch for all of them pays once.
+ *   codes, B, A, Y, N   in   HOST arrays of L entries: device pointers (Y[l] is written: M x N[l],
+ *                            dtype `y_dtype`) and row counts.  The arrays are read before the call
+ *                            returns.
+ *   K, r, bits, codebook, factor_dtype are shared by all L matrices.  1 <= L <= 8 (LORDS_ERR_SHAPE).
+ * With M == 1 and bf16 factors of rank <= 64 all matrices are served by one kernel launch;
+ * other cases run matrix by matrix.  Each Y[l] equals what lords_matmul gives for that matrix.
+ */
+int lords_matmul_batched(const void *X, const void *const *codes, const float *codebook,
+                         const void *const *B, const void *const *A, void *const *Y, const int *N,
+                         int L, int M, int K, int r, int bits,
+                         lords_dtype factor_dtype, lords_dtype y_dtype, void *stream);
+
+/* Gate and up projection of a gated MLP block (the Gate and Up modules of Table 7, both N x K, same
+ * input) with the block's activation applied on the way out:
+ *      H[m][n] = silu(G[m][n]) * U[m][n],   G = X W_hat_gate^T,  U = X W_hat_up^T,
+ *      silu(g) = g / (1 + exp(-g)).
+ * G and U are summed in fp32 and never rounded or written out on their own; the product is formed in
+ * fp32 and rounded once to `h_dtype`.  With M == 1 (bf16 factors, rank <= 64) this is one launch; larger
+ * M multiplies at most 1024 tokens at a time into an fp32 workspace and combines them in one pass.
+ *   H   out  M x N
+ */
+int lords_gate_up(const void *X, const void *codes_gate, const void *B_gate, const void *A_gate,
+                  const void *codes_up, const void *B_up, const void *A_up, const float *codebook,
+                  void *H, int M, int N, int K, int r, int bits,
+                  lords_dtype factor_dtype, lords_dtype h_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

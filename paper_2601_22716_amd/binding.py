@@ -15,7 +15,8 @@ STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LOR
                 4: "LORDS_ERR_ALIGN", 5: "LORDS_ERR_DTYPE", 6: "LORDS_ERR_LAUNCH", 7: "LORDS_ERR_UNSUPPORTED"}
 
 EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank",
-           "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex"]
+           "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex",
+           "lords_matmul_batched", "lords_gate_up"]
 
 
 class LordsError(RuntimeError):
@@ -61,6 +62,10 @@ def library():
         lib.lords_quantize.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
         lib.lords_block_init.restype = ci
         lib.lords_block_init.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
+        lib.lords_matmul_batched.restype = ci
+        lib.lords_matmul_batched.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+        lib.lords_gate_up.restype = ci
+        lib.lords_gate_up.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
         _lib = lib
     return _lib
 
@@ -151,3 +156,29 @@ def lords_matmul_ex(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int,
                     path: int = LORDS_PATH_AUTO, stream=None) -> None:
     _check(library().lords_matmul_ex(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
                                      _dtype_code(B), _dtype_code(Y), _stream(stream), path), "lords_matmul_ex")
+
+
+def _ptr_array(tensors):
+    """Host array of device pointers (void *[L]) from a sequence of tensors / raw ints / None."""
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def lords_matmul_batched(X, codes, codebook, B, A, Y, N, M: int, K: int, r: int, bits: int, stream=None) -> None:
+    """codes, B, A, Y: sequences of L tensors; N: sequence of L row counts."""
+    L = len(N)
+    if not (len(codes) == len(B) == len(A) == len(Y) == L):
+        raise ValueError("codes, B, A, Y and N must have the same length")
+    n_arr = (ctypes.c_int * L)(*[int(n) for n in N])
+    _check(library().lords_matmul_batched(_ptr(X), _ptr_array(codes), _ptr(codebook), _ptr_array(B), _ptr_array(A),
+                                          _ptr_array(Y), n_arr, L, M, K, r, bits, _dtype_code(B[0]), _dtype_code(Y[0]),
+                                          _stream(stream)), "lords_matmul_batched")
+
+
+def lords_gate_up(X, codes_gate, B_gate, A_gate, codes_up, B_up, A_up, codebook, H, M: int, N: int, K: int, r: int,
+                  bits: int, stream=None) -> None:
+    _check(library().lords_gate_up(_ptr(X), _ptr(codes_gate), _ptr(B_gate), _ptr(A_gate), _ptr(codes_up), _ptr(B_up),
+                                   _ptr(A_up), _ptr(codebook), _ptr(H), M, N, K, r, bits, _dtype_code(B_gate),
+                                   _dtype_code(H), _stream(stream)), "lords_gate_up")

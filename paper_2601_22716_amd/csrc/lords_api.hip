@@ -49,6 +49,68 @@ int get_workspace(size_t need, void **out)
     return LORDS_OK;
 }
 
+// Which small-M kernel takes a problem, and the workspace it asks for.
+enum DecodeKind { kOne, kFew, kFast, kGeneral };
+DecodeKind decode_kind(const lords::MatmulProblem &p)
+{
+    if (lords::decode_m1_supported(p)) return kOne;
+    if (p.M > 1 && lords::decode_mx_supported(p)) return kFew;
+    if (lords::decode_fast_supported(p)) return kFast;
+    return kGeneral;
+}
+size_t decode_need(const lords::MatmulProblem &p)
+{
+    switch (decode_kind(p)) {
+        case kOne: return lords::decode_m1_workspace_bytes(p);
+        case kFew: return lords::decode_mx_workspace_bytes(p);
+        case kFast: return lords::decode_fast_workspace_bytes(p);
+        default: return lords::kTicketBytes + lords::decode_workspace_bytes(p);
+    }
+}
+inline lords_path resolve_path(lords_path path, int M)
+{
+    return path == LORDS_PATH_AUTO ? ((M <= 32) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL) : path;   // measured cross-over
+}
+
+// Workspace for one checked problem on `path` (already resolved), plus `extra` bytes behind it that
+// are left to the caller (*extra_ptr).
+int plan_workspace(const lords::MatmulProblem &p, lords_path path, size_t extra, void **ws, void **extra_ptr)
+{
+    size_t own = path == LORDS_PATH_DECODE ? decode_need(p) : 0;
+    // the front of the buffer holds the arrival tickets of the small-M kernels and must stay zero
+    // between calls: a caller's bytes never start inside it, whatever this problem itself needs
+    if (extra && own < lords::kTicketBytes) own = lords::kTicketBytes;
+    const size_t own_al = (own + 255) & ~(size_t)255;
+    const int rc = get_workspace(own_al + extra, ws);
+    if (rc == LORDS_OK && extra_ptr) *extra_ptr = (unsigned char *)*ws + own_al;
+    return rc;
+}
+
+int launch_matmul(const lords::MatmulProblem &p, lords_path path, void *ws, void *stream)
+{
+    hipError_t e;
+    if (path == LORDS_PATH_DECODE) {
+        switch (decode_kind(p)) {
+            case kOne: e = lords::launch_decode_m1(p, ws, (hipStream_t)stream); break;
+            case kFew: e = lords::launch_decode_mx(p, ws, (hipStream_t)stream); break;
+            case kFast: e = lords::launch_decode_fast(p, ws, (hipStream_t)stream); break;
+            default: e = lords::launch_decode(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream);
+        }
+    } else {
+        e = lords::prefill_fast_supported(p) ? lords::launch_prefill_fast(p, (hipStream_t)stream)
+                                             : lords::launch_prefill(p, (hipStream_t)stream);
+    }
+    return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+}
+
+int run_matmul(const lords::MatmulProblem &p, lords_path path, void *stream)
+{
+    path = resolve_path(path, p.M);
+    void *ws = nullptr;
+    const int rc = plan_workspace(p, path, 0, &ws, nullptr);
+    return rc != LORDS_OK ? rc : launch_matmul(p, path, ws, stream);
+}
+
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline bool bad_bits(int bits) { return bits != 2 && bits != 3 && bits != 4; }
 inline bool bad_dtype(int d) { return d != LORDS_BF16 && d != LORDS_F32; }
@@ -150,28 +212,107 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook, con
     if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
 
     lords::MatmulProblem p{X, codes, codebook, B, A, Y, M, N, K, r, bits, f32fact, y_dtype == LORDS_F32};
-    if (path == LORDS_PATH_AUTO) path = (M <= 32) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL;   // measured cross-over
-    hipError_t e;
-    if (path == LORDS_PATH_DECODE) {
-        void *ws = nullptr;
-        const bool one = lords::decode_m1_supported(p);
-        const bool few = !one && M > 1 && lords::decode_mx_supported(p);
-        const bool fast = !one && !few && lords::decode_fast_supported(p);
-        const size_t need = one ? lords::decode_m1_workspace_bytes(p)
-                          : few ? lords::decode_mx_workspace_bytes(p)
-                          : fast ? lords::decode_fast_workspace_bytes(p)
-                                 : lords::kTicketBytes + lords::decode_workspace_bytes(p);
-        const int rc = get_workspace(need, &ws);
-        if (rc != LORDS_OK) return rc;
-        if (one) e = lords::launch_decode_m1(p, ws, (hipStream_t)stream);
-        else if (few) e = lords::launch_decode_mx(p, ws, (hipStream_t)stream);
-        else if (fast) e = lords::launch_decode_fast(p, ws, (hipStream_t)stream);
-        else e = lords::launch_decode(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream);
-    } else {
-        e = lords::prefill_fast_supported(p) ? lords::launch_prefill_fast(p, (hipStream_t)stream)
-                                             : lords::launch_prefill(p, (hipStream_t)stream);
+    return run_matmul(p, path, stream);
+}
+
+int lords_matmul_batched(const void *X, const void *const *codes, const float *codebook, const void *const *B,
+                         const void *const *A, void *const *Y, const int *N, int L, int M, int K, int r, int bits,
+                         lords_dtype factor_dtype, lords_dtype y_dtype, void *stream)
+{
+    if (!X || !codes || !codebook || !B || !A || !Y || !N) return LORDS_ERR_NULL;
+    if (L < 1 || L > lords::kMaxBatch) return LORDS_ERR_SHAPE;
+    for (int l = 0; l < L; ++l)
+        if (!codes[l] || !B[l] || !A[l] || !Y[l]) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (K < 32 || (K % 32) != 0 || r < 1 || M < 0) return LORDS_ERR_SHAPE;
+    for (int l = 0; l < L; ++l)
+        if (N[l] < 1) return LORDS_ERR_SHAPE;
+    if (misaligned(X) || misaligned(codebook)) return LORDS_ERR_ALIGN;
+    for (int l = 0; l < L; ++l)
+        if (misaligned(codes[l]) || misaligned(B[l]) || misaligned(A[l]) || misaligned(Y[l])) return LORDS_ERR_ALIGN;
+    if (bad_dtype((int)factor_dtype) || bad_dtype((int)y_dtype)) return LORDS_ERR_DTYPE;
+    if (M == 0) return LORDS_OK;
+    const bool f32fact = factor_dtype == LORDS_F32;
+    if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
+
+    lords::BatchedProblem bp;
+    bp.X = X; bp.codebook = codebook;
+    for (int l = 0; l < lords::kMaxBatch; ++l) {
+        const int s = l < L ? l : 0;
+        bp.codes[l] = codes[s]; bp.B[l] = B[s]; bp.A[l] = A[s]; bp.Y[l] = Y[s]; bp.N[l] = N[s];
     }
-    return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+    bp.L = L; bp.M = M; bp.K = K; bp.r = r; bp.bits = bits;
+    bp.f32fact = f32fact; bp.f32out = y_dtype == LORDS_F32; bp.act = false;
+    if (L > 1 && lords::decode_m1_batched_supported(bp)) {
+        void *ws = nullptr;
+        const int rc = get_workspace(lords::decode_m1_batched_workspace_bytes(bp), &ws);
+        if (rc != LORDS_OK) return rc;
+        return lords::launch_decode_m1_batched(bp, ws, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+    }
+    // more than one token (or a case the one-launch kernel does not take): matrix by matrix
+    for (int l = 0; l < L; ++l) {
+        lords::MatmulProblem p{X, codes[l], codebook, B[l], A[l], Y[l], M, N[l], K, r, bits, f32fact, y_dtype == LORDS_F32};
+        const int rc = run_matmul(p, LORDS_PATH_AUTO, stream);
+        if (rc != LORDS_OK) return rc;
+    }
+    return LORDS_OK;
+}
+
+int lords_gate_up(const void *X, const void *codes_gate, const void *B_gate, const void *A_gate,
+                  const void *codes_up, const void *B_up, const void *A_up, const float *codebook, void *H,
+                  int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype h_dtype, void *stream)
+{
+    if (!X || !codes_gate || !B_gate || !A_gate || !codes_up || !B_up || !A_up || !codebook || !H) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (bad_nk(N, K) || r < 1 || M < 0) return LORDS_ERR_SHAPE;
+    if (misaligned(X) || misaligned(codes_gate) || misaligned(B_gate) || misaligned(A_gate) || misaligned(codes_up) ||
+        misaligned(B_up) || misaligned(A_up) || misaligned(codebook) || misaligned(H))
+        return LORDS_ERR_ALIGN;
+    if (bad_dtype((int)factor_dtype) || bad_dtype((int)h_dtype)) return LORDS_ERR_DTYPE;
+    if (M == 0) return LORDS_OK;
+    const bool f32fact = factor_dtype == LORDS_F32, f32out = h_dtype == LORDS_F32;
+    if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
+
+    lords::BatchedProblem bp;
+    bp.X = X; bp.codebook = codebook;
+    for (int l = 0; l < lords::kMaxBatch; ++l) {
+        const bool up = l == 1;
+        bp.codes[l] = up ? codes_up : codes_gate; bp.B[l] = up ? B_up : B_gate; bp.A[l] = up ? A_up : A_gate;
+        bp.Y[l] = H; bp.N[l] = N;
+    }
+    bp.L = 2; bp.M = M; bp.K = K; bp.r = r; bp.bits = bits;
+    bp.f32fact = f32fact; bp.f32out = f32out; bp.act = true;
+    if (lords::decode_m1_batched_supported(bp)) {
+        void *ws = nullptr;
+        const int rc = get_workspace(lords::decode_m1_batched_workspace_bytes(bp), &ws);
+        if (rc != LORDS_OK) return rc;
+        return lords::launch_decode_m1_batched(bp, ws, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+    }
+    // Otherwise: both products in fp32 into the workspace, at most kChunk tokens at a time, then one
+    // element-wise pass.  The arithmetic is the same: fp32 sums, silu(gate) * up in fp32, one rounding.
+    constexpr int kChunk = 1024;
+    const size_t esz = f32out ? 4 : 2;
+    for (int m0 = 0; m0 < M; m0 += kChunk) {
+        const int mc = M - m0 < kChunk ? M - m0 : kChunk;
+        const size_t tmp_bytes = (size_t)2 * mc * N * sizeof(float);
+        const void *Xc = (const unsigned char *)X + (size_t)m0 * K * 2;
+        lords::MatmulProblem pg{Xc, codes_gate, codebook, B_gate, A_gate, nullptr, mc, N, K, r, bits, f32fact, true};
+        const lords_path path = resolve_path(LORDS_PATH_AUTO, mc);
+        void *ws = nullptr, *tmp = nullptr;
+        int rc = plan_workspace(pg, path, tmp_bytes, &ws, &tmp);
+        if (rc != LORDS_OK) return rc;
+        float *G = (float *)tmp, *U = G + (size_t)mc * N;
+        pg.Y = G;
+        lords::MatmulProblem pu{Xc, codes_up, codebook, B_up, A_up, U, mc, N, K, r, bits, f32fact, true};
+        rc = launch_matmul(pg, path, ws, stream);
+        if (rc != LORDS_OK) return rc;
+        rc = launch_matmul(pu, path, ws, stream);
+        if (rc != LORDS_OK) return rc;
+        if (lords::launch_silu_mul(G, U, (unsigned char *)H + (size_t)m0 * N * esz, (long)mc * N, f32out,
+                                   (hipStream_t)stream) != hipSuccess)
+            return LORDS_ERR_LAUNCH;
+    }
+    return LORDS_OK;
 }
 
 int lords_matmul(const void *X, const void *codes, const float *codebook, const void *B, const void *A, void *Y,

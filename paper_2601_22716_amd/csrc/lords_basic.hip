@@ -153,4 +153,44 @@ hipError_t launch_dequant(const void *codes, const float *codebook, const void *
     }
 }
 
+// h = silu(g) * u on fp32 inputs, one rounding at the store (the gate of a SwiGLU MLP when the two
+// products could not be combined inside the matmul kernel).  Four elements per thread.
+template <bool F32OUT>
+__global__ __launch_bounds__(256) void silu_mul_kernel(const float *__restrict__ G, const float *__restrict__ U,
+                                                       void *__restrict__ H, long count)
+{
+    const long i0 = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i0 >= count) return;
+    float g[4], u[4];
+    if (i0 + 4 <= count) {
+        const f32x4 gv = *reinterpret_cast<const f32x4 *>(G + i0), uv = *reinterpret_cast<const f32x4 *>(U + i0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { g[e] = gv[e]; u[e] = uv[e]; }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const long i = i0 + e < count ? i0 + e : count - 1;
+            g[e] = G[i];
+            u[e] = U[i];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (i0 + e >= count) break;
+        const float h = g[e] / (1.0f + __expf(-g[e])) * u[e];
+        if (F32OUT) reinterpret_cast<float *>(H)[i0 + e] = h;
+        else reinterpret_cast<uint16_t *>(H)[i0 + e] = bf16_bits(h);
+    }
+}
+
+hipError_t launch_silu_mul(const float *G, const float *U, void *H, long count, bool f32out, hipStream_t st)
+{
+    if (count <= 0) return hipSuccess;
+    const long threads = (count + 3) / 4;
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    if (f32out) hipLaunchKernelGGL(silu_mul_kernel<true>, dim3(blocks), dim3(256), 0, st, G, U, H, count);
+    else hipLaunchKernelGGL(silu_mul_kernel<false>, dim3(blocks), dim3(256), 0, st, G, U, H, count);
+    return hipGetLastError();
+}
+
 }  // namespace lords

@@ -11,6 +11,9 @@ hipError_t launch_unpack(const void *codes, uint8_t *idx, int N, int K, int bits
 hipError_t launch_dequant(const void *codes, const float *codebook, const void *B, const void *A, void *W,
                           int N, int K, int r, int bits, bool f32fact, bool f32out, hipStream_t st);
 
+// H = silu(G) * U, element by element, fp32 in (lords_basic.hip).
+hipError_t launch_silu_mul(const float *G, const float *U, void *H, long count, bool f32out, hipStream_t st);
+
 // Quantisation side (lords_quant.hip).
 hipError_t launch_quantize(const void *W, const float *codebook, const void *B, const void *A, void *codes,
                            int N, int K, int r, int bits, bool f32w, bool f32fact, hipStream_t st);
@@ -35,6 +38,25 @@ constexpr size_t kTicketBytes = 16384;
 bool decode_m1_supported(const MatmulProblem &p);
 size_t decode_m1_workspace_bytes(const MatmulProblem &p);
 hipError_t launch_decode_m1(const MatmulProblem &p, void *workspace, hipStream_t st);
+
+// Several matrices applied to ONE activation vector in a single launch (lords_decode_m1.hip): same K,
+// rank, code width, level table and factor type (bf16), own N.  act: matrices 0 and 1 (same N) are a
+// gate/up pair and Y[0] receives silu(gate) * up; Y[1] is not written.
+constexpr int kMaxBatch = 8;
+struct BatchedProblem {
+    const void *X;
+    const float *codebook;
+    const void *codes[kMaxBatch];
+    const void *B[kMaxBatch];
+    const void *A[kMaxBatch];
+    void *Y[kMaxBatch];
+    int N[kMaxBatch];
+    int L, M, K, r, bits;
+    bool f32fact, f32out, act;
+};
+bool decode_m1_batched_supported(const BatchedProblem &p);
+size_t decode_m1_batched_workspace_bytes(const BatchedProblem &p);
+hipError_t launch_decode_m1_batched(const BatchedProblem &p, void *workspace, hipStream_t st);
 
 // Few-token path (2..16 tokens per pass), bf16 factors, ranks up to 64 (lords_decode_mx.hip); same
 // workspace convention.

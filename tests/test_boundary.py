@@ -154,6 +154,70 @@ def test_matmul_argument_checks():
     assert f(*a) == 7
 
 
+def ptr_array(vals):
+    arr = (ctypes.c_void_p * len(vals))()
+    for i, v in enumerate(vals):
+        arr[i] = v
+    return arr
+
+
+def test_matmul_batched_argument_checks():
+    f = L.library().lords_matmul_batched
+    three = lambda: ptr_array([P, P, P])
+    ns = (ctypes.c_int * 3)(8, 16, 4)
+
+    def ok():
+        #       X  codes    cb  B        A        Y        N   L  M  K   r  bits fdt ydt stream
+        return [P, three(), P, three(), three(), three(), ns, 3, 1, 64, 4, 4, 0, 1, None]
+    for i in (0, 1, 2, 3, 4, 5, 6):
+        a = ok(); a[i] = None
+        assert f(*a) == 1
+    for i in (1, 3, 4, 5):                    # a NULL entry inside an array
+        a = ok(); a[i] = ptr_array([P, None, P])
+        assert f(*a) == 1
+    for L_ in (0, 9, -1):                     # the count is checked before the arrays are read
+        a = ok(); a[7] = L_
+        assert f(*a) == 3
+    a = ok(); a[11] = 5
+    assert f(*a) == 2
+    for i, v in ((8, -1), (9, 48), (9, 0), (10, 0)):
+        a = ok(); a[i] = v
+        assert f(*a) == 3
+    a = ok(); a[6] = (ctypes.c_int * 3)(8, 0, 4)
+    assert f(*a) == 3
+    a = ok(); a[3] = ptr_array([P, P + 4, P])
+    assert f(*a) == 4
+    a = ok(); a[0] = P + 8
+    assert f(*a) == 4
+    for i in (12, 13):
+        a = ok(); a[i] = 7
+        assert f(*a) == 5
+    a = ok(); a[8] = 0                         # no tokens: nothing to do
+    assert f(*a) == 0
+
+
+def test_gate_up_argument_checks():
+    f = L.library().lords_gate_up
+    #     X  cg Bg Ag cu Bu Au cb H  M  N  K   r  bits fdt hdt stream
+    ok = [P, P, P, P, P, P, P, P, P, 1, 8, 64, 4, 4, 0, 1, None]
+    for i in range(9):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[13] = 1
+    assert f(*a) == 2
+    for i, v in ((9, -1), (10, 0), (11, 16), (12, 0)):
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    for i in range(9):
+        a = list(ok); a[i] = P + 8
+        assert f(*a) == 4
+    for i in (14, 15):
+        a = list(ok); a[i] = 2
+        assert f(*a) == 5
+    a = list(ok); a[9] = 0
+    assert f(*a) == 0
+
+
 def test_binding_raises_with_status_name():
     with pytest.raises(L.LordsError) as e:
         L.binding._check(4, "lords_matmul")

@@ -192,9 +192,9 @@ def bench_other(args, L, li, torch):
 
 
 def bench_shared_input(args, L, li, torch):
-    """Context figures for the one-token calls that serve several matrices reading the same activations:
+    """Context figures for the decode calls that serve several matrices reading the same activations:
     query/key/value of the Llama-3-8B block in one launch, and its gate/up pair with silu(gate)*up on the
-    way out, each beside the same matrices served by separate lords_matmul calls."""
+    way out, each beside the same matrices served by separate lords_matmul calls; one token and two."""
     out = []
     bf16_tensor = L.bf16_from_bits
     # ---- q/k/v: 4096, 1024, 1024 rows of 4096 columns, 4 bits, rank 32
@@ -206,61 +206,63 @@ def bench_shared_input(args, L, li, torch):
     for s in range(nsets):
         layers = []
         for j, N in enumerate(Ns):
-            cs = li.make_case("qproj_4b", M=1, N=N, seed=3000 + 3 * s + j)
+            cs = li.make_case("qproj_4b", M=2, N=N, seed=3000 + 3 * s + j)
             cs0 = cs0 or cs
             layers.append((torch.from_numpy(cs.codes).cuda(), bf16_tensor(cs.B_bf16), bf16_tensor(cs.A_bf16)))
         sets.append(layers)
     X = bf16_tensor(cs0.X_bf16)
     codebook = torch.from_numpy(cs0.codebook.copy()).cuda()
-    Ys = [torch.zeros((1, N), dtype=torch.float32, device="cuda") for N in Ns]
+    for M in (1, 2):
+        Ys = [torch.zeros((M, N), dtype=torch.float32, device="cuda") for N in Ns]
 
-    def one_launch(i):
-        ls = sets[i % nsets]
-        L.lords_matmul_batched(X, [l[0] for l in ls], codebook, [l[1] for l in ls], [l[2] for l in ls], Ys, Ns,
-                               1, cfg.K, cfg.r, cfg.bits)
+        def one_launch(i):
+            ls = sets[i % nsets]
+            L.lords_matmul_batched(X, [l[0] for l in ls], codebook, [l[1] for l in ls], [l[2] for l in ls], Ys, Ns,
+                                   M, cfg.K, cfg.r, cfg.bits)
 
-    def separate(i):
-        for (codes, B, A), Y, N in zip(sets[i % nsets], Ys, Ns):
-            L.lords_matmul(X, codes, codebook, B, A, Y, 1, N, cfg.K, cfg.r, cfg.bits)
+        def separate(i):
+            for (codes, B, A), Y, N in zip(sets[i % nsets], Ys, Ns):
+                L.lords_matmul(X, codes, codebook, B, A, Y, M, N, cfg.K, cfg.r, cfg.bits)
 
-    ab = sum(algorithmic_bytes(1, N, cfg.K, cfg.r, cfg.bits) for N in Ns) - 2 * cfg.K * 2
-    res = {}
-    for label, fn in (("one_launch", one_launch), ("separate_calls", separate)):
-        _, ev_ms, _, _ = time_steps(fn, 100, 5, torch, use_graph=not args.no_graph)
-        res[label] = ev_ms * 1e3 / 100
-    out.append({"workload": "decode M=1, q/k/v (4096+1024+1024 x 4096, 4-bit, rank 32) sharing X",
-                "us_per_step": res["one_launch"], "us_per_step_separate_calls": res["separate_calls"],
-                "value": ab / res["one_launch"] / 1e3, "unit": "GB/s",
-                "frac_of_hbm_peak": ab / res["one_launch"] / 1e3 / HBM_PEAK_GBS})
+        ab = sum(algorithmic_bytes(M, N, cfg.K, cfg.r, cfg.bits) for N in Ns) - 2 * M * cfg.K * 2
+        res = {}
+        for label, fn in (("one_launch", one_launch), ("separate_calls", separate)):
+            _, ev_ms, _, _ = time_steps(fn, 100, 5, torch, use_graph=not args.no_graph)
+            res[label] = ev_ms * 1e3 / 100
+        out.append({"workload": f"decode M={M}, q/k/v (4096+1024+1024 x 4096, 4-bit, rank 32) sharing X",
+                    "us_per_step": res["one_launch"], "us_per_step_separate_calls": res["separate_calls"],
+                    "value": ab / res["one_launch"] / 1e3, "unit": "GB/s",
+                    "frac_of_hbm_peak": ab / res["one_launch"] / 1e3 / HBM_PEAK_GBS})
     del sets, Ys
 
     # ---- gate/up pair of the headline layer shape, H = silu(gate) * up
     cfg = li.CONFIGS["gateup_4b"]
     per_set = 2 * cfg.N * cfg.K * cfg.bits // 8
     nsets = int(-(-COLD_BYTES // per_set))
-    _, layers, X, codebook = make_sets("gateup_4b", 1, 2 * nsets, li, torch)
-    H = torch.zeros((1, cfg.N), dtype=torch.float32, device="cuda")
-    G, U = torch.zeros_like(H), torch.zeros_like(H)
+    _, layers, X, codebook = make_sets("gateup_4b", 2, 2 * nsets, li, torch)
+    for M in (1, 2):
+        H = torch.zeros((M, cfg.N), dtype=torch.float32, device="cuda")
+        G, U = torch.zeros_like(H), torch.zeros_like(H)
 
-    def fused(i):
-        (cg, Bg, Ag), (cu, Bu, Au) = layers[2 * (i % nsets)], layers[2 * (i % nsets) + 1]
-        L.lords_gate_up(X, cg, Bg, Ag, cu, Bu, Au, codebook, H, 1, cfg.N, cfg.K, cfg.r, cfg.bits)
+        def fused(i):
+            (cg, Bg, Ag), (cu, Bu, Au) = layers[2 * (i % nsets)], layers[2 * (i % nsets) + 1]
+            L.lords_gate_up(X, cg, Bg, Ag, cu, Bu, Au, codebook, H, M, cfg.N, cfg.K, cfg.r, cfg.bits)
 
-    def two_calls(i):
-        (cg, Bg, Ag), (cu, Bu, Au) = layers[2 * (i % nsets)], layers[2 * (i % nsets) + 1]
-        L.lords_matmul(X, cg, codebook, Bg, Ag, G, 1, cfg.N, cfg.K, cfg.r, cfg.bits)
-        L.lords_matmul(X, cu, codebook, Bu, Au, U, 1, cfg.N, cfg.K, cfg.r, cfg.bits)
+        def two_calls(i):
+            (cg, Bg, Ag), (cu, Bu, Au) = layers[2 * (i % nsets)], layers[2 * (i % nsets) + 1]
+            L.lords_matmul(X, cg, codebook, Bg, Ag, G, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+            L.lords_matmul(X, cu, codebook, Bu, Au, U, M, cfg.N, cfg.K, cfg.r, cfg.bits)
 
-    ab = 2 * algorithmic_bytes(1, cfg.N, cfg.K, cfg.r, cfg.bits) - cfg.K * 2 - cfg.N * 4
-    res = {}
-    for label, fn in (("one_launch", fused), ("two_products", two_calls)):
-        _, ev_ms, _, _ = time_steps(fn, 100, 5, torch, use_graph=not args.no_graph)
-        res[label] = ev_ms * 1e3 / 100
-    out.append({"workload": "decode M=1, gate/up pair (2 x 14336 x 4096, 4-bit, rank 32), H = silu(gate)*up",
-                "us_per_step": res["one_launch"],
-                "us_per_step_two_products_without_the_activation": res["two_products"],
-                "value": ab / res["one_launch"] / 1e3, "unit": "GB/s",
-                "frac_of_hbm_peak": ab / res["one_launch"] / 1e3 / HBM_PEAK_GBS})
+        ab = 2 * algorithmic_bytes(M, cfg.N, cfg.K, cfg.r, cfg.bits) - M * cfg.K * 2 - M * cfg.N * 4
+        res = {}
+        for label, fn in (("one_launch", fused), ("two_products", two_calls)):
+            _, ev_ms, _, _ = time_steps(fn, 100, 5, torch, use_graph=not args.no_graph)
+            res[label] = ev_ms * 1e3 / 100
+        out.append({"workload": f"decode M={M}, gate/up pair (2 x 14336 x 4096, 4-bit, rank 32), H = silu(gate)*up",
+                    "us_per_step": res["one_launch"],
+                    "us_per_step_two_products_without_the_activation": res["two_products"],
+                    "value": ab / res["one_launch"] / 1e3, "unit": "GB/s",
+                    "frac_of_hbm_peak": ab / res["one_launch"] / 1e3 / HBM_PEAK_GBS})
     return out
 
 

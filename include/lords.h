@@ -140,7 +140,7 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook,
  *                            dtype `y_dtype`) and row counts.  The arrays are read before the call
  *                            returns.
  *   K, r, bits, codebook, factor_dtype are shared by all L matrices.  1 <= L <= 8 (LORDS_ERR_SHAPE).
- * With M == 1 and bf16 factors of rank <= 64 all matrices are served by one kernel launch;
+ * With M <= 16 and bf16 factors of rank <= 64 all matrices are served by one kernel launch;
  * other cases run matrix by matrix.  Each Y[l] equals what lords_matmul gives for that matrix.
  */
 int lords_matmul_batched(const void *X, const void *const *codes, const float *codebook,
@@ -153,7 +153,7 @@ int lords_matmul_batched(const void *X, const void *const *codes, const float *c
  *      H[m][n] = silu(G[m][n]) * U[m][n],   G = X W_hat_gate^T,  U = X W_hat_up^T,
  *      silu(g) = g / (1 + exp(-g)).
  * G and U are summed in fp32 and never rounded or written out on their own; the product is formed in
- * fp32 and rounded once to `h_dtype`.  With M == 1 (bf16 factors, rank <= 64) this is one launch; larger
+ * fp32 and rounded once to `h_dtype`.  With M <= 16 (bf16 factors, rank <= 64) this is one launch; larger
  * M multiplies at most 1024 tokens at a time into an fp32 workspace and combines them in one pass.
  *   H   out  M x N
  */

@@ -111,6 +111,21 @@ int run_matmul(const lords::MatmulProblem &p, lords_path path, void *stream)
     return rc != LORDS_OK ? rc : launch_matmul(p, path, ws, stream);
 }
 
+// Several matrices in ONE launch, if a kernel takes the case: a status, or -1 if none does.
+int run_batched(const lords::BatchedProblem &bp, void *stream)
+{
+    const bool one = lords::decode_m1_batched_supported(bp);
+    const bool few = !one && lords::decode_mx_batched_supported(bp);
+    if (!one && !few) return -1;
+    void *ws = nullptr;
+    const int rc = get_workspace(one ? lords::decode_m1_batched_workspace_bytes(bp)
+                                     : lords::decode_mx_batched_workspace_bytes(bp), &ws);
+    if (rc != LORDS_OK) return rc;
+    const hipError_t e = one ? lords::launch_decode_m1_batched(bp, ws, (hipStream_t)stream)
+                             : lords::launch_decode_mx_batched(bp, ws, (hipStream_t)stream);
+    return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+}
+
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline bool bad_bits(int bits) { return bits != 2 && bits != 3 && bits != 4; }
 inline bool bad_dtype(int d) { return d != LORDS_BF16 && d != LORDS_F32; }
@@ -243,11 +258,9 @@ int lords_matmul_batched(const void *X, const void *const *codes, const float *c
     }
     bp.L = L; bp.M = M; bp.K = K; bp.r = r; bp.bits = bits;
     bp.f32fact = f32fact; bp.f32out = y_dtype == LORDS_F32; bp.act = false;
-    if (L > 1 && lords::decode_m1_batched_supported(bp)) {
-        void *ws = nullptr;
-        const int rc = get_workspace(lords::decode_m1_batched_workspace_bytes(bp), &ws);
-        if (rc != LORDS_OK) return rc;
-        return lords::launch_decode_m1_batched(bp, ws, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+    if (L > 1) {
+        const int rc = run_batched(bp, stream);
+        if (rc >= 0) return rc;
     }
     // more than one token (or a case the one-launch kernel does not take): matrix by matrix
     for (int l = 0; l < L; ++l) {
@@ -282,11 +295,9 @@ int lords_gate_up(const void *X, const void *codes_gate, const void *B_gate, con
     }
     bp.L = 2; bp.M = M; bp.K = K; bp.r = r; bp.bits = bits;
     bp.f32fact = f32fact; bp.f32out = f32out; bp.act = true;
-    if (lords::decode_m1_batched_supported(bp)) {
-        void *ws = nullptr;
-        const int rc = get_workspace(lords::decode_m1_batched_workspace_bytes(bp), &ws);
-        if (rc != LORDS_OK) return rc;
-        return lords::launch_decode_m1_batched(bp, ws, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+    {
+        const int rc = run_batched(bp, stream);
+        if (rc >= 0) return rc;
     }
     // Otherwise: both products in fp32 into the workspace, at most kChunk tokens at a time, then one
     // element-wise pass.  The arithmetic is the same: fp32 sums, silu(gate) * up in fp32, one rounding.

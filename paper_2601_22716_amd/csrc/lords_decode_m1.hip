@@ -108,7 +108,8 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
 
     // Loads of slab i of the current chunk, branch-free (addresses clamped into the arrays) so that
     // they can run kDepth slabs ahead: codes of columns >= K meet zero a-operands, rank entries
-    // >= r meet zero rows of the A tile (and are zeroed here), rows >= N are dropped at the store.
+    // >= r meet zero rows of the A tile (their B entries are read from the front of the row, or set to
+    // zero by the entry-wise gather), rows >= N are dropped at the store.
     int chunk = bx;
     int slab0 = (chunk * NSG + sg) * ly.ns;                           // this wave's first slab
     uint32_t cw[kNS][G][BITS];
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
                 if (F32) t = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const float *>(ly.B) + (size_t)n * r + jc);
                 else t = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(ly.B) + (size_t)n * r + jc);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) Bq[i][4 * h + e] = t[e];      // (masked at use: a select here would wait for the load)
+                for (int e = 0; e < 4; ++e) Bq[i][4 * h + e] = t[e];
             }
         }
     };
@@ -274,7 +275,8 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
                         const int q = 4 * t + e;                       // position in the lane's run
                         const uint32_t raw = F32 ? Bq[i][q % BW] : ((q & 1) ? (Bq[i][(q >> 1) % BW] & 0xFFFF0000u) : (Bq[i][(q >> 1) % BW] << 16));
                         float b = __builtin_bit_cast(float, raw);
-                        if (BVEC) b = (QW * g + (F32 ? 4 * t : 8 * (t >> 1))) < r ? b : 0.f;
+                        // (a vector-loaded run beyond the rank holds the row's first entries, finite
+                        //  values, and meets s = 0 exactly: those rows of the A tile are zero)
                         if (e & 1) y1 = __builtin_fmaf(s, b, y1);
                         else y0 = __builtin_fmaf(s, b, y0);
                     }

@@ -34,26 +34,39 @@ constexpr int kMxWaves = 8;
 constexpr int kMxThreads = 64 * kMxWaves;
 constexpr int kMxTickets = 64;        // chunks whose tickets are taken at once
 
-struct MxArgs {
-    const uint16_t *X;     // M x K bf16, M <= 16
+// One weight matrix.  A batched launch (several matrices applied to the same activations) gives
+// each matrix a contiguous range of blockIdx.x.
+struct MxLayer {
     const uint8_t *codes;
-    const float *codebook;
     const uint16_t *A;     // r x K bf16
     const uint16_t *B;     // N x r bf16
     void *Y;
-    float *partial;        // [splits][M][N] fp32, used when splits > 1
+    float *partial;        // [splits][M][N] fp32, used when the column blocks meet in the workspace
     unsigned *counters;    // one ticket per chunk, zero between calls
-    int M, N, K, r;
-    int y_f32;
-    int row_bytes;
+    int N;
     int nslabs;            // ceil(N / 16)
     int ns;                // slabs per wave per chunk, <= kNS
     int nchunks;           // chunks of 2*ns slabs
-    int splits;            // gridDim.z
+    int gx0, gxn;          // first blockIdx.x of this matrix and how many it has
 };
 
-template <int BITS, int SS, int G, bool BVEC>
-__global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_mx_kernel(MxArgs a)
+template <int NLAYERS>
+struct MxArgsT {
+    const uint16_t *X;     // M x K bf16, M <= 16
+    const float *codebook;
+    int M, K, r;
+    int y_f32;
+    int row_bytes;
+    int splits;            // gridDim.z
+    int L;                 // matrices in this launch
+    int act;               // 1: matrices 0 and 1 are a gate/up pair, Y of matrix 0 receives silu(gate) * up
+    MxLayer layer[NLAYERS];
+};
+typedef MxArgsT<1> MxArgs;
+typedef MxArgsT<kMaxBatch> MxMultiArgs;
+
+template <int BITS, int SS, int G, bool BVEC, bool MULTI = false>
+__global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_mx_kernel(MxArgsT<MULTI ? kMaxBatch : 1> a)
 {
     constexpr int KT = 128 * G, WK = 4 * KT, AST = WK + 8, NL = 1 << BITS, NE = 1 << (2 * BITS), CPR = WK / 8;
     constexpr int LUT_BYTES = NE * 256, A_BYTES = SS * 32 * AST * 2;
@@ -66,29 +79,37 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     const int cb = wave & 3, half = wave >> 2;
     const int kw = blockIdx.z * WK;                            // first column of the workgroup
     const int kb = kw + cb * KT;                               // first column of this wave's block
-    const int N = a.N, K = a.K, M = a.M, r = a.r;
+    // the matrix this workgroup works on (wave-uniform), its index among that matrix's workgroups
+    int li = 0;
+    if (MULTI)
+        while (li + 1 < a.L && (int)blockIdx.x >= a.layer[li + 1].gx0) ++li;
+    const MxLayer ly = a.layer[MULTI ? li : 0];
+    const int bx = MULTI ? (int)blockIdx.x - ly.gx0 : (int)blockIdx.x;
+    const int gxl = MULTI ? ly.gxn : (int)gridDim.x;
+    const bool meet = a.splits > 1 || (MULTI && a.act);       // column blocks (and a gate/up pair) meet in the workspace
+    const int N = ly.N, K = a.K, M = a.M, r = a.r;
     const uint32_t laneoff = (uint32_t)lane * 4u;
     const int ngroups = K >> 5;
 
     // Loads of slab i of the current chunk, branch-free (addresses clamped into the arrays) so that
     // they can run kDepth slabs ahead: codes of columns >= K meet zero scales, rank entries >= r of
     // B meet zero rows of the A tile, rows >= N are dropped at the store.
-    int chunk = blockIdx.x;
-    int slab0 = (chunk * 2 + half) * a.ns;                     // this wave's first slab
+    int chunk = bx;
+    int slab0 = (chunk * 2 + half) * ly.ns;                    // this wave's first slab
     uint32_t cw[kNS][G][BITS];
     bf16x8 Bop[kNS][SS];
-    auto issue = [&](int i) __attribute__((always_inline)) {
-        const int n = min((slab0 + i) * 16 + c, N - 1);
+    auto issue = [&](int i, int first) __attribute__((always_inline)) {
+        const int n = min((first + i) * 16 + c, N - 1);
 #pragma unroll
         for (int v = 0; v < G; ++v) {
             const int grp = min((kb >> 5) + G * g + v, ngroups - 1);
-            load_group<BITS>(a.codes + (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS), cw[i][v]);
+            load_group<BITS>(ly.codes + (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS), cw[i][v]);
         }
         if (BVEC) {
 #pragma unroll
             for (int s = 0; s < SS; ++s) {
                 const int jj0 = 32 * s + 8 * g;
-                Bop[i][s] = *reinterpret_cast<const bf16x8 *>(a.B + (size_t)n * r + (jj0 + 8 <= r ? jj0 : 0));
+                Bop[i][s] = *reinterpret_cast<const bf16x8 *>(ly.B + (size_t)n * r + (jj0 + 8 <= r ? jj0 : 0));
             }
         }
     };
@@ -102,7 +123,7 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int j = 32 * s + 8 * g + e;
-                t[e] = j < r ? (short)a.B[(size_t)n * r + j] : (short)0;
+                t[e] = j < r ? (short)ly.B[(size_t)n * r + j] : (short)0;
             }
             Bop[i][s] = __builtin_bit_cast(bf16x8, t);
         }
@@ -120,7 +141,7 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     for (int q = 0; q < NCA; ++q) {
         const int jj = (tid + kMxThreads * q) / CPR;
         ta[q] = u32x4{0u, 0u, 0u, 0u};
-        if (jj < r && k0 < K) ta[q] = *reinterpret_cast<const u32x4 *>(a.A + (size_t)jj * K + k0);
+        if (jj < r && k0 < K) ta[q] = *reinterpret_cast<const u32x4 *>(ly.A + (size_t)jj * K + k0);
     }
 #pragma unroll
     for (int q = 0; q < NCX; ++q) {
@@ -136,7 +157,7 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < kDepth; ++i) issue(i);
+    for (int i = 0; i < kDepth; ++i) issue(i, slab0);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- 2. A tile and level table into LDS; scale a-operands back, transposed -----------------
@@ -188,17 +209,13 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     f32x4 *red = reinterpret_cast<f32x4 *>(As);            // [8 waves][kNS][64 lanes]
 
     // ---- 4. the row stream, chunk by chunk ------------------------------------------------------
-    for (; chunk < a.nchunks; chunk += gridDim.x) {
-        if (chunk != (int)blockIdx.x) {
-            slab0 = (chunk * 2 + half) * a.ns;
-#pragma unroll
-            for (int i = 0; i < kDepth; ++i) issue(i);
-        }
-        const int nsw = max(0, min(a.ns, a.nslabs - slab0));
+    for (; chunk < ly.nchunks; chunk += gxl) {
+        slab0 = (chunk * 2 + half) * ly.ns;                // (its first kDepth slabs are on their way)
+        const int nsw = max(0, min(ly.ns, ly.nslabs - slab0));
 #pragma unroll
         for (int i = 0; i < kNS; ++i) {
             if (i < nsw) {
-                if (i + kDepth < kNS) issue(i + kDepth);
+                if (i + kDepth < kNS) issue(i + kDepth, slab0);
                 __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of this slab's arithmetic
                 if (!BVEC) gather_B(i);
                 f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -234,13 +251,22 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        // The first slabs of the next chunk are requested before this chunk's sums are handed over
+        // (their registers are free), so the stream does not drain in between.  Outside the slab
+        // loop on purpose: inside it every load is unconditional, which lets the compiler count
+        // exactly how many are in flight at each use.
+        if (chunk + gxl < ly.nchunks) {
+            const int next0 = ((chunk + gxl) * 2 + half) * ly.ns;
+#pragma unroll
+            for (int i = 0; i < kDepth; ++i) issue(i, next0);
+        }
         __syncthreads();
 
         // ---- 5. add the four column blocks (fixed order); lane (m, gl) of a slab holds rows 4gl..4gl+3
-        const int rows = 2 * a.ns * 16;                    // rows of the chunk
+        const int rows = 2 * ly.ns * 16;                   // rows of the chunk
         const int row0 = chunk * rows;
-        for (int q = tid; q < 2 * a.ns * 64; q += kMxThreads) {
-            const int hf = q / (a.ns * 64), rem = q - hf * (a.ns * 64), i = rem >> 6, l = rem & 63;
+        for (int q = tid; q < 2 * ly.ns * 64; q += kMxThreads) {
+            const int hf = q / (ly.ns * 64), rem = q - hf * (ly.ns * 64), i = rem >> 6, l = rem & 63;
             const int m = l & 15, gl = l >> 4;
             f32x4 s = red[((hf * 4 + 0) * kNS + i) * 64 + l];
 #pragma unroll
@@ -251,13 +277,13 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
             if (m >= M) continue;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int n = row0 + (hf * a.ns + i) * 16 + 4 * gl + e;
+                const int n = row0 + (hf * ly.ns + i) * 16 + 4 * gl + e;
                 if (n >= N) continue;
-                if (a.splits > 1)
-                    __hip_atomic_store(&a.partial[((size_t)blockIdx.z * M + m) * N + n], s[e], __ATOMIC_RELAXED,
+                if (meet)
+                    __hip_atomic_store(&ly.partial[((size_t)blockIdx.z * M + m) * N + n], s[e], __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
-                else if (a.y_f32) reinterpret_cast<float *>(a.Y)[(size_t)m * N + n] = s[e];
-                else reinterpret_cast<uint16_t *>(a.Y)[(size_t)m * N + n] = bf16_bits(s[e]);
+                else if (a.y_f32) reinterpret_cast<float *>(ly.Y)[(size_t)m * N + n] = s[e];
+                else reinterpret_cast<uint16_t *>(ly.Y)[(size_t)m * N + n] = bf16_bits(s[e]);
             }
         }
         __syncthreads();                                   // the sums are rewritten by the next chunk
@@ -268,43 +294,58 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     //         the two dependent round trips (stores acknowledged, then the ticket) are paid once.
     //         The partial sums went out as device-coherent (write-through) stores: once they have
     //         completed they are visible to every workgroup, without an L2 write-back or invalidate.
-    if (a.splits > 1) {
+    if (meet) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        const int rows = 2 * a.ns * 16;
-        const int niter = (a.nchunks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+        // a gate/up pair shares its tickets (same chunking): the last of both matrices' workgroups finishes
+        const bool pair = MULTI && a.act;
+        const unsigned arrivals = (unsigned)a.splits * (pair ? 2u : 1u);
+        const float *Pg = pair ? a.layer[0].partial : ly.partial;
+        const float *Pu = pair ? a.layer[MULTI ? 1 : 0].partial : nullptr;
+        void *Yout = pair ? a.layer[0].Y : ly.Y;
+        const int rows = 2 * ly.ns * 16;
+        const int niter = (ly.nchunks - bx + gxl - 1) / gxl;
         for (int base = 0; base < niter; base += kMxTickets) {
             const int nt = min(kMxTickets, niter - base);
             if (tid < nt) {
-                const int ch = blockIdx.x + (base + tid) * gridDim.x;
-                const unsigned old = __hip_atomic_fetch_add(&a.counters[ch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const int last = (old == (unsigned)(a.splits - 1));
+                const int ch = bx + (base + tid) * gxl;
+                const unsigned old = __hip_atomic_fetch_add(&ly.counters[ch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int last = (old == arrivals - 1u);
                 // every other workgroup of this chunk has passed: hand the ticket back at zero
-                if (last) __hip_atomic_store(&a.counters[ch], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (last) __hip_atomic_store(&ly.counters[ch], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 flag[tid] = last;
             }
             __syncthreads();
             for (int t = 0; t < nt; ++t) {
                 if (!flag[t]) continue;
-                const int row0 = (blockIdx.x + (base + t) * gridDim.x) * rows;
+                const int row0 = (bx + (base + t) * gxl) * rows;
                 for (int q = tid; q < M * rows; q += kMxThreads) {
                     const int m = q / rows, n = row0 + (q - m * rows);
                     if (n >= N) continue;
-                    float s = 0.f;
-                    for (int z0 = 0; z0 < a.splits; z0 += 8) {
-                        float t8[8];
+                    auto add_blocks = [&](const float *P) __attribute__((always_inline)) -> float {
+                        float acc = 0.f;
+                        for (int z0 = 0; z0 < a.splits; z0 += 8) {
+                            float t8[8];
 #pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const int z = min(z0 + u, a.splits - 1);
-                            t8[u] = __hip_atomic_load(&a.partial[((size_t)z * M + m) * N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            for (int u = 0; u < 8; ++u) {
+                                const int z = min(z0 + u, a.splits - 1);
+                                t8[u] = __hip_atomic_load(&P[((size_t)z * M + m) * N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            }
+#pragma unroll
+                            for (int u = 0; u < 8; ++u)
+                                if (z0 + u < a.splits) acc += t8[u];
                         }
-#pragma unroll
-                        for (int u = 0; u < 8; ++u)
-                            if (z0 + u < a.splits) s += t8[u];
+                        return acc;
+                    };
+                    float s = add_blocks(Pg);
+                    if (pair) {
+                        // SwiGLU gate: silu(gate) * up on the fp32 sums, one rounding at the store
+                        const float up = add_blocks(Pu);
+                        s = s / (1.0f + __expf(-s)) * up;
                     }
-                    if (a.y_f32) reinterpret_cast<float *>(a.Y)[(size_t)m * N + n] = s;
-                    else reinterpret_cast<uint16_t *>(a.Y)[(size_t)m * N + n] = bf16_bits(s);
+                    if (a.y_f32) reinterpret_cast<float *>(Yout)[(size_t)m * N + n] = s;
+                    else reinterpret_cast<uint16_t *>(Yout)[(size_t)m * N + n] = bf16_bits(s);
                 }
             }
             __syncthreads();                               // the flags are rewritten by the next batch
@@ -326,6 +367,16 @@ static int mx_ss(const MatmulProblem &p)
     return rp <= 1 ? 1 : rp <= 2 ? 2 : 0;
 }
 
+// Slabs per wave and chunk when `nslabs` slabs are shared by `lanes` waves (all workgroups of a
+// column range): a wave's share is cut into the fewest passes of at most kNS slabs, all equally long.
+static int mx_slabs_per_chunk(long nslabs, long lanes)
+{
+    long share = (nslabs + lanes - 1) / lanes;
+    if (share < 1) share = 1;
+    const long passes = (share + kNS - 1) / kNS;
+    return (int)((share + passes - 1) / passes);
+}
+
 static MxPlan mx_plan(const MatmulProblem &p)
 {
     MxPlan d;
@@ -336,11 +387,8 @@ static MxPlan mx_plan(const MatmulProblem &p)
     const int nslabs = (p.N + 15) / 16;
     int gx = 256 / d.splits;                           // one resident workgroup per CU
     if (gx < 1) gx = 1;
-    int ns = (nslabs + 2 * gx - 1) / (2 * gx);
-    if (ns > kNS) ns = kNS;
-    if (ns < 1) ns = 1;
-    d.ns = ns;
-    d.nchunks = (nslabs + 2 * ns - 1) / (2 * ns);
+    d.ns = mx_slabs_per_chunk(nslabs, 2 * gx);
+    d.nchunks = (nslabs + 2 * d.ns - 1) / (2 * d.ns);
     d.gx = gx < d.nchunks ? gx : d.nchunks;
     return d;
 }
@@ -360,19 +408,19 @@ size_t decode_mx_workspace_bytes(const MatmulProblem &p)
     return kTicketBytes + (size_t)d.splits * mchunk * p.N * sizeof(float);
 }
 
-template <int BITS, int SS, int G, bool BVEC>
-static hipError_t launch_mx_t(const MxArgs &a, dim3 grid, hipStream_t st)
+template <int BITS, int SS, int G, bool BVEC, bool MULTI>
+static hipError_t launch_mx_t(const MxArgsT<MULTI ? kMaxBatch : 1> &a, dim3 grid, hipStream_t st)
 {
     constexpr int WK = 4 * 128 * G, AST = WK + 8;
     const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)SS * 32 * AST * 2 + kMxTickets * sizeof(int);
     static bool attr_set = false;
     if (!attr_set && smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_mx_kernel<BITS, SS, G, BVEC>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_mx_kernel<BITS, SS, G, BVEC, MULTI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((decode_mx_kernel<BITS, SS, G, BVEC>), grid, dim3(kMxThreads), smem, st, a);
+    hipLaunchKernelGGL((decode_mx_kernel<BITS, SS, G, BVEC, MULTI>), grid, dim3(kMxThreads), smem, st, a);
     return hipGetLastError();
 }
 
@@ -385,25 +433,31 @@ hipError_t launch_decode_mx(const MatmulProblem &p, void *workspace, hipStream_t
         MxArgs a;
         a.M = (p.M - m0) < 16 ? (p.M - m0) : 16;
         a.X = (const uint16_t *)p.X + (size_t)m0 * p.K;
-        a.Y = p.f32out ? (void *)((float *)p.Y + (size_t)m0 * p.N) : (void *)((uint16_t *)p.Y + (size_t)m0 * p.N);
-        a.codes = (const uint8_t *)p.codes;
         a.codebook = p.codebook;
-        a.A = (const uint16_t *)p.A;
-        a.B = (const uint16_t *)p.B;
-        a.counters = (unsigned *)workspace;
-        a.partial = workspace ? (float *)((unsigned char *)workspace + kTicketBytes) : nullptr;
-        a.N = p.N; a.K = p.K; a.r = p.r;
+        a.K = p.K; a.r = p.r;
         a.y_f32 = p.f32out ? 1 : 0;
         a.row_bytes = p.K / 8 * p.bits;
-        a.nslabs = (p.N + 15) / 16;
-        a.ns = d.ns;
-        a.nchunks = d.nchunks;
         a.splits = d.splits;
+        a.L = 1;
+        a.act = 0;
+        MxLayer &ly = a.layer[0];
+        ly.Y = p.f32out ? (void *)((float *)p.Y + (size_t)m0 * p.N) : (void *)((uint16_t *)p.Y + (size_t)m0 * p.N);
+        ly.codes = (const uint8_t *)p.codes;
+        ly.A = (const uint16_t *)p.A;
+        ly.B = (const uint16_t *)p.B;
+        ly.counters = (unsigned *)workspace;
+        ly.partial = workspace ? (float *)((unsigned char *)workspace + kTicketBytes) : nullptr;
+        ly.N = p.N;
+        ly.nslabs = (p.N + 15) / 16;
+        ly.ns = d.ns;
+        ly.nchunks = d.nchunks;
+        ly.gx0 = 0;
+        ly.gxn = d.gx;
         const bool bvec = (p.r % 8) == 0;
         const dim3 grid(d.gx, 1, d.splits);
         hipError_t e = hipErrorInvalidValue;
 #define LORDS_MXCASE(B_, S_, G_) \
-    if (p.bits == B_ && d.ss == S_) e = bvec ? launch_mx_t<B_, S_, G_, true>(a, grid, st) : launch_mx_t<B_, S_, G_, false>(a, grid, st);
+    if (p.bits == B_ && d.ss == S_) e = bvec ? launch_mx_t<B_, S_, G_, true, false>(a, grid, st) : launch_mx_t<B_, S_, G_, false, false>(a, grid, st);
         LORDS_MXCASE(2, 1, 2) LORDS_MXCASE(2, 2, 1)
         LORDS_MXCASE(3, 1, 2) LORDS_MXCASE(3, 2, 1)
         LORDS_MXCASE(4, 1, 2) LORDS_MXCASE(4, 2, 1)
@@ -411,6 +465,119 @@ hipError_t launch_decode_mx(const MatmulProblem &p, void *workspace, hipStream_t
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------------
+// batched launch: several matrices, the same (up to 16) tokens
+// ---------------------------------------------------------------------------------------------
+struct MxBatchPlan {
+    int ss, G, splits, total_gx;
+    int ns[kMaxBatch], nchunks[kMaxBatch], gx0[kMaxBatch], gxn[kMaxBatch];
+    size_t ticket0[kMaxBatch], partial0[kMaxBatch];           // offsets in tickets / floats
+    size_t tickets, partial_floats;
+};
+
+static bool mx_batch_plan(const BatchedProblem &p, MxBatchPlan &d)
+{
+    if (p.M < 2 || p.M > 16 || p.f32fact || p.L < 1 || p.L > kMaxBatch) return false;
+    if (p.act && (p.L != 2 || p.N[0] != p.N[1])) return false;
+    const int rp = (p.r + 31) / 32;
+    d.ss = rp <= 1 ? 1 : rp <= 2 ? 2 : 0;
+    if (d.ss == 0) return false;
+    d.G = d.ss == 1 ? 2 : 1;
+    const int wk = 4 * 128 * d.G;
+    d.splits = (p.K + wk - 1) / wk;
+    if (d.splits > 65535) return false;
+    // workgroups per matrix: one resident workgroup per CU in total, shared out by row count
+    int budget = 256 / d.splits;
+    if (budget < p.L) budget = p.L;
+    long nslabs[kMaxBatch], sum = 0;
+    for (int l = 0; l < p.L; ++l) { nslabs[l] = (p.N[l] + 15) / 16; sum += nslabs[l]; }
+    int gx[kMaxBatch], used = 0;
+    for (int l = 0; l < p.L; ++l) {
+        gx[l] = p.act ? budget / 2 : (int)((long)budget * nslabs[l] / sum);
+        if (gx[l] < 1) gx[l] = 1;
+        used += gx[l];
+    }
+    // what rounding down left over goes to the matrices with the most slabs per workgroup
+    while (!p.act && used < budget) {
+        int best = 0;
+        for (int l = 1; l < p.L; ++l)
+            if (nslabs[l] * gx[best] > nslabs[best] * gx[l]) best = l;
+        ++gx[best];
+        ++used;
+    }
+    d.tickets = 0;
+    d.partial_floats = 0;
+    int x0 = 0;
+    for (int l = 0; l < p.L; ++l) {
+        d.ns[l] = mx_slabs_per_chunk(nslabs[l], 2L * gx[l]);
+        d.nchunks[l] = (int)((nslabs[l] + 2 * d.ns[l] - 1) / (2 * d.ns[l]));
+        d.gxn[l] = gx[l] < d.nchunks[l] ? gx[l] : d.nchunks[l];
+        d.gx0[l] = x0;
+        x0 += d.gxn[l];
+        d.ticket0[l] = (p.act && l == 1) ? d.ticket0[0] : d.tickets;
+        if (!(p.act && l == 1)) d.tickets += (size_t)d.nchunks[l];
+        d.partial0[l] = d.partial_floats;
+        d.partial_floats += (size_t)d.splits * p.M * p.N[l];
+    }
+    d.total_gx = x0;
+    return d.tickets * sizeof(unsigned) <= kTicketBytes;
+}
+
+bool decode_mx_batched_supported(const BatchedProblem &p)
+{
+    MxBatchPlan d;
+    return mx_batch_plan(p, d);
+}
+
+size_t decode_mx_batched_workspace_bytes(const BatchedProblem &p)
+{
+    MxBatchPlan d;
+    if (!mx_batch_plan(p, d)) return 0;
+    return kTicketBytes + d.partial_floats * sizeof(float);
+}
+
+hipError_t launch_decode_mx_batched(const BatchedProblem &p, void *workspace, hipStream_t st)
+{
+    MxBatchPlan d;
+    if (!mx_batch_plan(p, d) || !workspace) return hipErrorInvalidValue;
+    MxMultiArgs a;
+    a.X = (const uint16_t *)p.X;
+    a.codebook = p.codebook;
+    a.M = p.M; a.K = p.K; a.r = p.r;
+    a.y_f32 = p.f32out ? 1 : 0;
+    a.row_bytes = p.K / 8 * p.bits;
+    a.splits = d.splits;
+    a.L = p.L;
+    a.act = p.act ? 1 : 0;
+    for (int l = 0; l < kMaxBatch; ++l) {
+        const int s = l < p.L ? l : 0;                      // unused entries: copies of the first
+        MxLayer &ly = a.layer[l];
+        ly.codes = (const uint8_t *)p.codes[s];
+        ly.A = (const uint16_t *)p.A[s];
+        ly.B = (const uint16_t *)p.B[s];
+        ly.Y = p.Y[s];
+        ly.counters = (unsigned *)workspace + d.ticket0[s];
+        ly.partial = (float *)((unsigned char *)workspace + kTicketBytes) + d.partial0[s];
+        ly.N = p.N[s];
+        ly.nslabs = (p.N[s] + 15) / 16;
+        ly.ns = d.ns[s];
+        ly.nchunks = d.nchunks[s];
+        ly.gx0 = d.gx0[s];
+        ly.gxn = d.gxn[s];
+    }
+    const bool bvec = (p.r % 8) == 0;
+    const dim3 grid(d.total_gx, 1, d.splits);
+    hipError_t e = hipErrorInvalidValue;
+#define LORDS_MXCASE(B_, S_, G_)                                                                  \
+    if (p.bits == B_ && d.ss == S_)                                                                \
+        e = bvec ? launch_mx_t<B_, S_, G_, true, true>(a, grid, st) : launch_mx_t<B_, S_, G_, false, true>(a, grid, st);
+    LORDS_MXCASE(2, 1, 2) LORDS_MXCASE(2, 2, 1)
+    LORDS_MXCASE(3, 1, 2) LORDS_MXCASE(3, 2, 1)
+    LORDS_MXCASE(4, 1, 2) LORDS_MXCASE(4, 2, 1)
+#undef LORDS_MXCASE
+    return e;
 }
 
 }  // namespace lords

@@ -57,6 +57,10 @@ struct BatchedProblem {
 bool decode_m1_batched_supported(const BatchedProblem &p);
 size_t decode_m1_batched_workspace_bytes(const BatchedProblem &p);
 hipError_t launch_decode_m1_batched(const BatchedProblem &p, void *workspace, hipStream_t st);
+// The same for 2..16 tokens, ranks up to 64 (lords_decode_mx.hip).
+bool decode_mx_batched_supported(const BatchedProblem &p);
+size_t decode_mx_batched_workspace_bytes(const BatchedProblem &p);
+hipError_t launch_decode_mx_batched(const BatchedProblem &p, void *workspace, hipStream_t st);
 
 // Few-token path (2..16 tokens per pass), bf16 factors, ranks up to 64 (lords_decode_mx.hip); same
 // workspace convention.

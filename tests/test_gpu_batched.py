@@ -100,11 +100,31 @@ def test_batched_one_token(gpu, bits, Ns, K, r):
         np.testing.assert_array_equal(Y, single, err_msg=f"matrix {l}: batched and single-matrix calls differ")
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("M", [2, 5, 16])
+@pytest.mark.parametrize("Ns,K,r", [([300, 70, 70], 544, 32), ([100, 200, 50, 77, 33, 64, 130, 90], 2080, 20),
+                                    ([200, 120], 1056, 64), ([90, 60, 1], 288, 13), ([700, 40], 4128, 24)])
+def test_batched_few_tokens(gpu, bits, M, Ns, K, r):
+    say(f"batched M={M} bits={bits} Ns={Ns} K={K} r={r}")
+    cases = layers_sharing_x(Ns, K, r, bits, M, seed=31)
+    dev, Ys = run_batched(gpu, cases, M)
+    want = onp.matmul_batched(cases[0].X_f32, [(c.codes, c.B_f32, c.A_f32) for c in cases], cases[0].codebook, bits)
+    rms_all = float(np.sqrt(np.mean(np.concatenate([w.ravel() for w in want]) ** 2)))
+    for l, (Y, w) in enumerate(zip(Ys, want)):
+        if w.size >= 16:
+            check(Y, w, f"matrix {l}")
+        else:
+            mx = float(np.abs(Y - w).max()) / rms_all
+            assert mx <= Y_MAX_TOL, (l, mx)
+        single = dev[l].matmul(X=dev[0].X, M=M)
+        np.testing.assert_array_equal(Y, single, err_msg=f"matrix {l}: batched and single-matrix calls differ")
+
+
 @pytest.mark.parametrize("bits", [2, 4])
-@pytest.mark.parametrize("M,fdt", [(5, "bf16"), (1, "f32"), (40, "bf16")])
-def test_batched_other_cases_run_matrix_by_matrix(gpu, bits, M, fdt):
-    say(f"batched M={M} bits={bits} factors={fdt}")
-    cases = layers_sharing_x([150, 64, 33], 544, 24, bits, M, fdt=fdt, seed=4)
+@pytest.mark.parametrize("M,fdt,r", [(5, "f32", 24), (1, "f32", 24), (40, "bf16", 24), (20, "bf16", 24), (3, "bf16", 72)])
+def test_batched_other_cases_run_matrix_by_matrix(gpu, bits, M, fdt, r):
+    say(f"batched M={M} bits={bits} factors={fdt} r={r}")
+    cases = layers_sharing_x([150, 64, 33], 544, r, bits, M, fdt=fdt, seed=4)
     _, Ys = run_batched(gpu, cases, M)
     want = onp.matmul_batched(cases[0].X_f32, [(c.codes, c.B_f32, c.A_f32) for c in cases], cases[0].codebook, bits)
     for l, (Y, w) in enumerate(zip(Ys, want)):
@@ -180,7 +200,11 @@ GATE_UP = [
     (1000, 256, 8, 1),          # one column block: the pair still meets in the workspace
     (77, 2080, 64, 1),
     (130, 288, 13, 1),
-    (150, 544, 24, 6),          # few tokens: two products and one element-wise pass
+    (150, 544, 24, 6),          # few tokens, one launch
+    (300, 2080, 64, 16),
+    (90, 288, 13, 2),
+    (120, 512, 32, 3),          # one column split: the pair still meets in the workspace
+    (150, 544, 24, 20),         # more than one pass of tokens: two products and one element-wise pass
     (96, 320, 32, 40),          # the MFMA GEMM twice
     (48, 64, 4, 1100),          # more tokens than one pass of the workspace takes
     (64, 320, 72, 1),           # a rank the one-launch kernel does not take
@@ -212,25 +236,26 @@ def test_gate_up_bf16_output_and_f32_factors(gpu, fdt):
 
 
 # ------------------------------------------------------------------ full-size, sampled
-def test_full_size_qkv_one_token_sampled(gpu):
+@pytest.mark.parametrize("M", [1, 2, 16])
+def test_full_size_qkv_sampled(gpu, M):
     """Llama-3-8B-shaped query/key/value projections (4096, 1024, 1024 rows of 4096 columns, 4 bits,
-    rank 32), one token, one launch; 192 sampled rows of each against the oracle."""
+    rank 32), one launch; 192 sampled rows of each against the oracle."""
     Ns, K, r, bits = [4096, 1024, 1024], 4096, 32, 4
-    say(f"full-size q/k/v Ns={Ns}")
-    cases = layers_sharing_x(Ns, K, r, bits, 1, seed=8)
-    dev, Ys = run_batched(gpu, cases, 1)
+    say(f"full-size q/k/v Ns={Ns} M={M}")
+    cases = layers_sharing_x(Ns, K, r, bits, M, seed=8)
+    dev, Ys = run_batched(gpu, cases, M)
     rng = np.random.default_rng(80)
     for l, (c, Y) in enumerate(zip(cases, Ys)):
         rows = np.unique(np.concatenate([[0, c.N - 1], rng.integers(0, c.N, 190)]))
         want = onp.matmul_rows(cases[0].X_f32, c.codes, c.codebook, c.B_f32, c.A_f32, bits, rows)
         check(Y[:, rows], want, f"matrix {l}, {rows.size} rows")
-        np.testing.assert_array_equal(Y, dev[l].matmul(X=dev[0].X, M=1))
+        np.testing.assert_array_equal(Y, dev[l].matmul(X=dev[0].X, M=M))
 
 
-@pytest.mark.parametrize("M", [1, 2048])
+@pytest.mark.parametrize("M", [1, 2, 16, 2048])
 def test_full_size_gate_up_sampled(gpu, M):
-    """The headline layer shape as a gate/up pair (14336 x 4096, 4 bits, rank 32): one token in one
-    launch, and 2048 tokens; sampled rows against the oracle."""
+    """The headline layer shape as a gate/up pair (14336 x 4096, 4 bits, rank 32): up to 16 tokens in
+    one launch, and 2048 tokens; sampled rows against the oracle."""
     N, K, r, bits = 14336, 4096, 32, 4
     say(f"full-size gate/up M={M}")
     cg, cu = gate_up_cases(N, K, r, bits, M, seed=9)

@@ -114,8 +114,9 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
     int slab0 = (chunk * NSG + sg) * ly.ns;                           // this wave's first slab
     uint32_t cw[kNS][G][BITS];
     uint32_t Bq[kNS][BW];
-    auto issue = [&](int i, int first) __attribute__((always_inline)) {
-        const int n = min((first + i) * 16 + c, N - 1);
+    // (a request past the wave's last slab `last` repeats that slab: same cache lines, no new traffic)
+    auto issue = [&](int i, int first, int last) __attribute__((always_inline)) {
+        const int n = min(min(first + i, last) * 16 + c, N - 1);
 #pragma unroll
         for (int v = 0; v < G; ++v) {
             const int grp = min((kb >> 5) + G * g + v, ngroups - 1);
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < kDepth; ++i) issue(i, slab0);
+    for (int i = 0; i < kDepth; ++i) issue(i, slab0, max(slab0, min(slab0 + ly.ns, ly.nslabs) - 1));
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- 2. the A tile, activations folded in: A[j][k] * x[k] rounded to bf16 ------------------
@@ -240,7 +241,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
         for (int i = 0; i < kNS; ++i) {
             ysum[i] = 0.f;
             if (i < nsw) {
-                if (i + kDepth < kNS) issue(i + kDepth, slab0);
+                if (i + kDepth < kNS) issue(i + kDepth, slab0, slab0 + nsw - 1);
                 __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of this slab's arithmetic
                 if (!BVEC) gather_B(i);
                 // one accumulator per tile, first MFMA on a literal zero; the two tiles (and the
@@ -292,7 +293,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
         if (chunk + gxl < ly.nchunks) {
             const int next0 = ((chunk + gxl) * NSG + sg) * ly.ns;
 #pragma unroll
-            for (int i = 0; i < kDepth; ++i) issue(i, next0);
+            for (int i = 0; i < kDepth; ++i) issue(i, next0, max(next0, min(next0 + ly.ns, ly.nslabs) - 1));
         }
 
         // ---- 5. add the four lanes of each row (two cross-lane steps, each issued for all slabs

@@ -98,8 +98,9 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     int slab0 = (chunk * 2 + half) * ly.ns;                    // this wave's first slab
     uint32_t cw[kNS][G][BITS];
     bf16x8 Bop[kNS][SS];
-    auto issue = [&](int i, int first) __attribute__((always_inline)) {
-        const int n = min((first + i) * 16 + c, N - 1);
+    // (a request past the wave's last slab `last` repeats that slab: same cache lines, no new traffic)
+    auto issue = [&](int i, int first, int last) __attribute__((always_inline)) {
+        const int n = min(min(first + i, last) * 16 + c, N - 1);
 #pragma unroll
         for (int v = 0; v < G; ++v) {
             const int grp = min((kb >> 5) + G * g + v, ngroups - 1);
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < kDepth; ++i) issue(i, slab0);
+    for (int i = 0; i < kDepth; ++i) issue(i, slab0, max(slab0, min(slab0 + ly.ns, ly.nslabs) - 1));
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- 2. A tile and level table into LDS; scale a-operands back, transposed -----------------
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma unroll
         for (int i = 0; i < kNS; ++i) {
             if (i < nsw) {
-                if (i + kDepth < kNS) issue(i + kDepth, slab0);
+                if (i + kDepth < kNS) issue(i + kDepth, slab0, slab0 + nsw - 1);
                 __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of this slab's arithmetic
                 if (!BVEC) gather_B(i);
                 f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -258,7 +259,7 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         if (chunk + gxl < ly.nchunks) {
             const int next0 = ((chunk + gxl) * 2 + half) * ly.ns;
 #pragma unroll
-            for (int i = 0; i < kDepth; ++i) issue(i, next0);
+            for (int i = 0; i < kDepth; ++i) issue(i, next0, max(next0, min(next0 + ly.ns, ly.nslabs) - 1));
         }
         __syncthreads();
 

@@ -39,6 +39,7 @@ namespace lords {
 constexpr int kM1Waves = 8;
 constexpr int kM1Threads = 64 * kM1Waves;
 constexpr int kM1Tickets = 64;        // chunks whose tickets are taken at once
+constexpr int kM1Depth = kDepth;      // slabs whose loads are in flight ahead of the one computed (deeper measured slower)
 
 constexpr int kM1MaxLayers = kMaxBatch;   // matrices one batched launch can hold
 
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
     const int ngroups = K >> 5;
 
     // Loads of slab i of the current chunk, branch-free (addresses clamped into the arrays) so that
-    // they can run kDepth slabs ahead: codes of columns >= K meet zero a-operands, rank entries
+    // they can run kM1Depth slabs ahead: codes of columns >= K meet zero a-operands, rank entries
     // >= r meet zero rows of the A tile (their B entries are read from the front of the row, or set to
     // zero by the entry-wise gather), rows >= N are dropped at the store.
     int chunk = bx;
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < kDepth; ++i) issue(i, slab0, max(slab0, min(slab0 + ly.ns, ly.nslabs) - 1));
+    for (int i = 0; i < kM1Depth; ++i) issue(i, slab0, max(slab0, min(slab0 + ly.ns, ly.nslabs) - 1));
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- 2. the A tile, activations folded in: A[j][k] * x[k] rounded to bf16 ------------------
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
 
     // ---- 4. the row stream, chunk by chunk ------------------------------------------------------
     for (; chunk < ly.nchunks; chunk += gxl) {
-        slab0 = (chunk * NSG + sg) * ly.ns;                  // (its first kDepth slabs are on their way)
+        slab0 = (chunk * NSG + sg) * ly.ns;                  // (its first kM1Depth slabs are on their way)
         const int nsw = max(0, min(ly.ns, ly.nslabs - slab0));
 
         float ysum[kNS];
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
         for (int i = 0; i < kNS; ++i) {
             ysum[i] = 0.f;
             if (i < nsw) {
-                if (i + kDepth < kNS) issue(i + kDepth, slab0, slab0 + nsw - 1);
+                if (i + kM1Depth < kNS) issue(i + kM1Depth, slab0, slab0 + nsw - 1);
                 __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of this slab's arithmetic
                 if (!BVEC) gather_B(i);
                 // one accumulator per tile, first MFMA on a literal zero; the two tiles (and the
@@ -293,7 +294,7 @@ __global__ __launch_bounds__(kM1Threads) __attribute__((amdgpu_waves_per_eu(2, 2
         if (chunk + gxl < ly.nchunks) {
             const int next0 = ((chunk + gxl) * NSG + sg) * ly.ns;
 #pragma unroll
-            for (int i = 0; i < kDepth; ++i) issue(i, next0, max(next0, min(next0 + ly.ns, ly.nslabs) - 1));
+            for (int i = 0; i < kM1Depth; ++i) issue(i, next0, max(next0, min(next0 + ly.ns, ly.nslabs) - 1));
         }
 
         // ---- 5. add the four lanes of each row (two cross-lane steps, each issued for all slabs

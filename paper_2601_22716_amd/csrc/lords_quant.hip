@@ -144,6 +144,59 @@ __global__ __launch_bounds__(256) void block_scale_kernel(const void *__restrict
     }
 }
 
+// The same for block sizes g that divide 256 (and are multiples of 4): W is read as one flat stream of
+// 4-element vectors, kU vectors per lane in flight; a block is g/4 neighbouring lanes of one vector row,
+// its maximum taken by cross-lane steps within that group.  Blocks are consecutive in the flat order
+// (K = r g), so block b is elements b g .. b g + g - 1 and its scale is entry b of B.
+constexpr int kBsU = 8;
+template <bool F32W, bool F32FACT>
+__global__ __launch_bounds__(256) void block_scale_vec_kernel(const void *__restrict__ Wv, const float *__restrict__ codebook,
+                                                              void *__restrict__ Bv, long nvec, int g, int nl)
+{
+    const int lane = threadIdx.x & 63;
+    const long wave = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long v0 = wave * (64 * kBsU) + lane;                       // this lane's first vector
+    if (wave * (64 * kBsU) >= nvec) return;
+    float cmax = 0.f;
+    for (int i = 0; i < nl; ++i) cmax = fmaxf(cmax, fabsf(codebook[i]));
+    float m[kBsU];
+#pragma unroll
+    for (int u = 0; u < kBsU; ++u) {
+        const long v = v0 + 64 * u;
+        const long vc = v < nvec ? v : nvec - 1;                      // past the end: a copy of the last vector, never stored
+        float x0, x1, x2, x3;
+        if (F32W) {
+            const f32x4 t = reinterpret_cast<const f32x4 *>(Wv)[vc];
+            x0 = t[0]; x1 = t[1]; x2 = t[2]; x3 = t[3];
+        } else {
+            typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+            const u32x2 t = reinterpret_cast<const u32x2 *>(Wv)[vc];
+            x0 = __builtin_bit_cast(float, t[0] << 16); x1 = __builtin_bit_cast(float, t[0] & 0xFFFF0000u);
+            x2 = __builtin_bit_cast(float, t[1] << 16); x3 = __builtin_bit_cast(float, t[1] & 0xFFFF0000u);
+        }
+        m[u] = fmaxf(fmaxf(fabsf(x0), fabsf(x1)), fmaxf(fabsf(x2), fabsf(x3)));
+    }
+    const int lpb = g >> 2;                                           // lanes per block: 1, 2, 4, ... 64
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        if (off < lpb) {
+#pragma unroll
+            for (int u = 0; u < kBsU; ++u) m[u] = fmaxf(m[u], __shfl_xor(m[u], off));
+        }
+    }
+    if ((lane & (lpb - 1)) == 0) {
+#pragma unroll
+        for (int u = 0; u < kBsU; ++u) {
+            const long v = v0 + 64 * u;
+            if (v >= nvec) continue;
+            const long blk = v / lpb;
+            const float sc = m[u] / cmax;
+            if (F32FACT) reinterpret_cast<float *>(Bv)[blk] = sc;
+            else reinterpret_cast<uint16_t *>(Bv)[blk] = bf16_bits(sc);
+        }
+    }
+}
+
 template <bool F32FACT>
 __global__ __launch_bounds__(256) void block_indicator_kernel(void *__restrict__ Av, int K, int r)
 {
@@ -184,7 +237,16 @@ hipError_t launch_block_init(const void *W, const float *codebook, void *B, void
     const long nblk = (long)N * r;
     const dim3 g1((unsigned)((nblk + 3) / 4)), g2((unsigned)(((long)r * K + 255) / 256));
     const int nl = 1 << bits;
-    if (f32w) {
+    const int g = K / r;
+    if ((g % 4) == 0 && (256 % g) == 0) {
+        const long nvec = (long)N * K / 4;
+        const dim3 gv((unsigned)((nvec + 4 * 64 * kBsU - 1) / (4 * 64 * kBsU)));
+#define LORDS_BCASE(FW_, FF_) \
+    hipLaunchKernelGGL((block_scale_vec_kernel<FW_, FF_>), gv, dim3(256), 0, st, W, codebook, B, nvec, g, nl)
+        if (f32w) { if (f32fact) LORDS_BCASE(true, true); else LORDS_BCASE(true, false); }
+        else { if (f32fact) LORDS_BCASE(false, true); else LORDS_BCASE(false, false); }
+#undef LORDS_BCASE
+    } else if (f32w) {
         if (f32fact) hipLaunchKernelGGL((block_scale_kernel<true, true>), g1, dim3(256), 0, st, W, codebook, B, N, K, r, nl);
         else hipLaunchKernelGGL((block_scale_kernel<true, false>), g1, dim3(256), 0, st, W, codebook, B, N, K, r, nl);
     } else {

@@ -98,7 +98,10 @@ def test_quantize_inverts_dequant(gpu, bits):
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("wdt", ["f32", "bf16"])
 @pytest.mark.parametrize("fdt", ["bf16", "f32"])
-@pytest.mark.parametrize("N,K,r", [(3, 32, 1), (65, 640, 5), (128, 4096, 32), (40, 96, 96)])
+@pytest.mark.parametrize("N,K,r", [(3, 32, 1), (65, 640, 5), (128, 4096, 32), (40, 96, 96),
+                                   # block sizes 4, 8 and 256 (one to sixty-four lanes per block), a ragged last wave;
+                                   # 448 does not divide 256: the one-wave-per-block kernel
+                                   (17, 64, 16), (5, 64, 8), (33, 1024, 4), (9, 1344, 3), (1000, 2048, 64)])
 def test_block_init_bit_exact(gpu, bits, wdt, fdt, N, K, r):
     say(f"block_init bits={bits} W={wdt} factors={fdt} N={N} K={K} r={r}")
     t = gpu.torch

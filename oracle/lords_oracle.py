@@ -45,6 +45,16 @@ own, Sec. 4.3; Q/K/V and Gate/Up of the module list in Table 7 read one input):
                    modules belong to (the model's own activation, not part of
                    the paper's method), written out from its definition
 
+Backward of the layer for fine-tuning the scale factors (Sec. 3.4: B and A are the trainable
+parameters, Q stays fixed, the update of the weight is Q (.) (B'A' - BA)).  With
+Y = X W_hat^T, W_hat = C[q] (.) (B A) and dY the gradient of a scalar loss with respect to Y,
+the chain rule gives
+
+  backward_input    dX = dY W_hat                                   [M, K]
+  backward_factors  G  = dY^T X         (gradient w.r.t. W_hat)     [N, K]
+                    P  = C[q] (.) G     (gradient w.r.t. S = B A)
+                    dB = P A^T   [N, r],        dA = B^T P   [r, K]
+
 Pins (see tests/test_oracle_pins.py): hand-derived byte vectors for the
 unpacker, scalar brute force on tiny inputs, the block-wise special case
 (paper Sec. 3.1), identity activations, the rank-1 closed form, the all-ones
@@ -124,6 +134,24 @@ def gate_up(X, gate, up, codebook, bits: int) -> np.ndarray:
     G = matmul(X, gate[0], codebook, gate[1], gate[2], bits)
     U = matmul(X, up[0], codebook, up[1], up[2], bits)
     return silu(G) * U
+
+
+def backward_input(dY, codes, codebook, B, A, bits: int) -> np.ndarray:
+    """dX = dY W_hat, fp64 [M, K]: gradient of a loss with respect to X given dY = dLoss/dY."""
+    W = dequant(codes, codebook, B, A, bits)
+    return np.asarray(dY, dtype=np.float64) @ W
+
+
+def backward_factors(dY, X, codes, codebook, B, A, bits: int):
+    """(dB, dA), fp64 [N, r] and [r, K]: gradients with respect to the scale factors (Sec. 3.4)."""
+    A64 = np.asarray(A, dtype=np.float64)
+    B64 = np.asarray(B, dtype=np.float64)
+    K = A64.shape[1]
+    q = unpack_codes(codes, K, bits)
+    C = np.asarray(codebook, dtype=np.float64)
+    G = np.asarray(dY, dtype=np.float64).T @ np.asarray(X, dtype=np.float64)     # dLoss/dW_hat
+    P = C[q] * G                                                                  # dLoss/dS
+    return P @ A64.T, B64.T @ P
 
 
 def equivalent_rank(N: int, K: int, group: int) -> int:

@@ -162,6 +162,43 @@ int lords_gate_up(const void *X, const void *codes_gate, const void *B_gate, con
                   void *H, int M, int N, int K, int r, int bits,
                   lords_dtype factor_dtype, lords_dtype h_dtype, void *stream);
 
+/* ---- Backward of the layer, for fine-tuning the scale factors (Sec. 3.4: B and A are trained, the
+ * codes stay fixed).  With Y = X W_hat^T and dY the gradient of a scalar loss with respect to Y:
+ *      dX = dY W_hat,     G = dY^T X,   P = C[q] (.) G,     dB = P A^T,     dA = B^T P.
+ * G and P (N x K) are never written to device memory. ---- */
+
+/* The packed codes with rows and columns swapped: codes_t has K rows of N codes, code n of row k
+ * being code k of row n of `codes`.  Made once per layer (the codes do not change during this kind of
+ * fine-tuning) and handed to lords_backward_input.  N must be a multiple of 32 (LORDS_ERR_SHAPE).
+ *   codes    in   N x K*bits/8 bytes
+ *   codes_t  out  K x N*bits/8 bytes
+ */
+int lords_transpose_codes(const void *codes, void *codes_t, int N, int K, int bits, void *stream);
+
+/* dX[m][k] = sum_n dY[m][n] W_hat[n][k]: the forward product of the transposed layer
+ * W_hat^T = C[Q^T] (.) (A^T B^T), run by the kernels of lords_matmul (same arithmetic, same accuracy).
+ *   dY       in   M x N bf16
+ *   codes_t  in   from lords_transpose_codes
+ *   B, A     in   N x r and r x K (NOT transposed: the library transposes them into its workspace)
+ *   dX       out  M x K, dtype `dx_dtype`
+ * N must be a multiple of 32.
+ */
+int lords_backward_input(const void *dY, const void *codes_t, const float *codebook, const void *B, const void *A,
+                         void *dX, int M, int N, int K, int r, int bits,
+                         lords_dtype factor_dtype, lords_dtype dx_dtype, void *stream);
+
+/* dB[n][j] = sum_k C[q[n][k]] G[n][k] A[j][k],  dA[j][k] = sum_n B[n][j] C[q[n][k]] G[n][k],
+ * G = dY^T X accumulated in fp32 over the tokens.  P = C[q] (.) G is rounded once to bf16 and fp32
+ * factors are rounded to bf16 as MFMA operands; the sums are fp32 and run-to-run identical.
+ *   dY, X    in   M x N and M x K, bf16
+ *   dB, dA   out  N x r and r x K, fp32 (overwritten, not accumulated into)
+ * Needs N % 8 == 0 and r <= 64 (LORDS_ERR_UNSUPPORTED otherwise); M == 0 gives zeros.
+ * Uses the per-device workspace: (ceil(K/128) N r + ceil(N/256) r K) * 4 bytes of partial results.
+ */
+int lords_backward_factors(const void *dY, const void *X, const void *codes, const float *codebook,
+                           const void *B, const void *A, float *dB, float *dA,
+                           int M, int N, int K, int r, int bits, lords_dtype factor_dtype, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

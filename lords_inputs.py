@@ -24,7 +24,7 @@ import numpy as np
 
 __all__ = [
     "LayerConfig", "CONFIGS", "nf_codebook", "int_codebook", "to_bf16",
-    "bf16_bits_to_f32", "row_bytes", "make_case", "make_blockwise_case",
+    "bf16_bits_to_f32", "row_bytes", "make_case", "make_blockwise_case", "make_output_grad",
 ]
 
 
@@ -219,3 +219,10 @@ def make_blockwise_case(N: int, K: int, bits: int, group: int, M: int = 1,
         B_f32, A_f32 = s, A
     return Case(cfg, M, codes, nf_codebook(bits), B_f32, A_f32, X_f32, X_bits,
                 B_bits, A_bits, extra={"block_scales": B_f32, "group": group})
+
+
+def make_output_grad(M: int, N: int, seed: int = 0) -> tuple[np.ndarray, np.ndarray]:
+    """A stand-in for dLoss/dY of a layer: M x N values ~ N(0,1) rounded to bf16.
+    Returns (uint16 bits, fp32 values)."""
+    g = np.random.default_rng([seed, 777, M, N]).standard_normal((M, N)).astype(np.float32)
+    return to_bf16(g)

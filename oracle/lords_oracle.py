@@ -154,6 +154,34 @@ def backward_factors(dY, X, codes, codebook, B, A, bits: int):
     return P @ A64.T, B64.T @ P
 
 
+def backward_input_cols(dY, codes, codebook, B, A, bits: int, cols) -> np.ndarray:
+    """Columns `cols` of dX (dX[:, cols]): the definition restricted to chosen in-features, for
+    checking full-size runs on sampled outputs without forming all of W_hat."""
+    cols = np.asarray(cols, dtype=np.int64)
+    A64 = np.asarray(A, dtype=np.float64)
+    q = unpack_codes(codes, A64.shape[1], bits)[:, cols]
+    W = np.asarray(codebook, dtype=np.float64)[q] * (np.asarray(B, dtype=np.float64) @ A64[:, cols])
+    return np.asarray(dY, dtype=np.float64) @ W
+
+
+def backward_factors_rows(dY, X, codes, codebook, B, A, bits: int, rows) -> np.ndarray:
+    """Rows `rows` of dB: needs only those rows of G = dY^T X."""
+    rows = np.asarray(rows, dtype=np.int64)
+    A64 = np.asarray(A, dtype=np.float64)
+    q = unpack_codes(np.asarray(codes)[rows], A64.shape[1], bits)
+    G = np.asarray(dY, dtype=np.float64)[:, rows].T @ np.asarray(X, dtype=np.float64)
+    return (np.asarray(codebook, dtype=np.float64)[q] * G) @ A64.T
+
+
+def backward_factors_cols(dY, X, codes, codebook, B, A, bits: int, cols) -> np.ndarray:
+    """Columns `cols` of dA: needs only those columns of G = dY^T X."""
+    cols = np.asarray(cols, dtype=np.int64)
+    K = np.asarray(A).shape[1]
+    q = unpack_codes(codes, K, bits)[:, cols]
+    G = np.asarray(dY, dtype=np.float64).T @ np.asarray(X, dtype=np.float64)[:, cols]
+    return np.asarray(B, dtype=np.float64).T @ (np.asarray(codebook, dtype=np.float64)[q] * G)
+
+
 def equivalent_rank(N: int, K: int, group: int) -> int:
     """Rank whose factor budget r (N + K) matches the block-wise scale budget
     N K / group: r = floor(N K / (group (N + K)))  (Sec. 3.2; Appendix A)."""

@@ -9,4 +9,5 @@ from .binding import (  # noqa: F401
     STATUS_NAMES, library, library_path, lords_version, lords_status_string, lords_row_bytes,
     lords_equivalent_rank, lords_unpack, bf16_from_bits, lords_dequant, lords_matmul, lords_matmul_ex,
     lords_quantize, lords_block_init, lords_matmul_batched, lords_gate_up,
+    lords_transpose_codes, lords_backward_input, lords_backward_factors,
 )

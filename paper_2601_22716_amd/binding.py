@@ -16,7 +16,7 @@ STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LOR
 
 EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank",
            "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex",
-           "lords_matmul_batched", "lords_gate_up"]
+           "lords_matmul_batched", "lords_gate_up", "lords_transpose_codes", "lords_backward_input", "lords_backward_factors"]
 
 
 class LordsError(RuntimeError):
@@ -66,6 +66,12 @@ def library():
         lib.lords_matmul_batched.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
         lib.lords_gate_up.restype = ci
         lib.lords_gate_up.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+        lib.lords_transpose_codes.restype = ci
+        lib.lords_transpose_codes.argtypes = [vp, vp, ci, ci, ci, vp]
+        lib.lords_backward_input.restype = ci
+        lib.lords_backward_input.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
+        lib.lords_backward_factors.restype = ci
+        lib.lords_backward_factors.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
         _lib = lib
     return _lib
 
@@ -182,3 +188,19 @@ def lords_gate_up(X, codes_gate, B_gate, A_gate, codes_up, B_up, A_up, codebook,
     _check(library().lords_gate_up(_ptr(X), _ptr(codes_gate), _ptr(B_gate), _ptr(A_gate), _ptr(codes_up), _ptr(B_up),
                                    _ptr(A_up), _ptr(codebook), _ptr(H), M, N, K, r, bits, _dtype_code(B_gate),
                                    _dtype_code(H), _stream(stream)), "lords_gate_up")
+
+
+def lords_transpose_codes(codes, codes_t, N: int, K: int, bits: int, stream=None) -> None:
+    _check(library().lords_transpose_codes(_ptr(codes), _ptr(codes_t), N, K, bits, _stream(stream)), "lords_transpose_codes")
+
+
+def lords_backward_input(dY, codes_t, codebook, B, A, dX, M: int, N: int, K: int, r: int, bits: int, stream=None) -> None:
+    _check(library().lords_backward_input(_ptr(dY), _ptr(codes_t), _ptr(codebook), _ptr(B), _ptr(A), _ptr(dX), M, N, K, r,
+                                          bits, _dtype_code(B), _dtype_code(dX), _stream(stream)), "lords_backward_input")
+
+
+def lords_backward_factors(dY, X, codes, codebook, B, A, dB, dA, M: int, N: int, K: int, r: int, bits: int,
+                           stream=None) -> None:
+    _check(library().lords_backward_factors(_ptr(dY), _ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(dB),
+                                            _ptr(dA), M, N, K, r, bits, _dtype_code(B), _stream(stream)),
+           "lords_backward_factors")

@@ -326,6 +326,64 @@ int lords_gate_up(const void *X, const void *codes_gate, const void *B_gate, con
     return LORDS_OK;
 }
 
+int lords_transpose_codes(const void *codes, void *codes_t, int N, int K, int bits, void *stream)
+{
+    if (!codes || !codes_t) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (bad_nk(N, K) || (N % 32) != 0) return LORDS_ERR_SHAPE;
+    if (misaligned(codes) || misaligned(codes_t)) return LORDS_ERR_ALIGN;
+    return lords::launch_transpose_codes(codes, codes_t, N, K, bits, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+}
+
+int lords_backward_input(const void *dY, const void *codes_t, const float *codebook, const void *B, const void *A, void *dX,
+                         int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype dx_dtype, void *stream)
+{
+    if (!dY || !codes_t || !codebook || !B || !A || !dX) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (bad_nk(N, K) || (N % 32) != 0 || r < 1 || M < 0) return LORDS_ERR_SHAPE;
+    if (misaligned(dY) || misaligned(codes_t) || misaligned(codebook) || misaligned(B) || misaligned(A) || misaligned(dX))
+        return LORDS_ERR_ALIGN;
+    if (bad_dtype((int)factor_dtype) || bad_dtype((int)dx_dtype)) return LORDS_ERR_DTYPE;
+    if (M == 0) return LORDS_OK;
+    const bool f32fact = factor_dtype == LORDS_F32;
+    if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
+    // The transposed layer: rows = the K in-features, columns = the N out-features, factors A^T (K x r)
+    // and B^T (r x N); its forward product applied to dY is dX.
+    const size_t esz = f32fact ? 4 : 2;
+    const size_t at_bytes = ((size_t)K * r * esz + 255) & ~(size_t)255, bt_bytes = ((size_t)r * N * esz + 255) & ~(size_t)255;
+    lords::MatmulProblem p{dY, codes_t, codebook, nullptr, nullptr, dX, M, K, N, r, bits, f32fact, dx_dtype == LORDS_F32};
+    const lords_path path = resolve_path(LORDS_PATH_AUTO, M);
+    void *ws = nullptr, *extra = nullptr;
+    const int rc = plan_workspace(p, path, at_bytes + bt_bytes, &ws, &extra);
+    if (rc != LORDS_OK) return rc;
+    void *At = extra, *Bt = (unsigned char *)extra + at_bytes;
+    if (lords::launch_transpose_factor(A, At, r, K, f32fact, (hipStream_t)stream) != hipSuccess) return LORDS_ERR_LAUNCH;
+    if (lords::launch_transpose_factor(B, Bt, N, r, f32fact, (hipStream_t)stream) != hipSuccess) return LORDS_ERR_LAUNCH;
+    p.B = At;
+    p.A = Bt;
+    return launch_matmul(p, path, ws, stream);
+}
+
+int lords_backward_factors(const void *dY, const void *X, const void *codes, const float *codebook, const void *B,
+                           const void *A, float *dB, float *dA, int M, int N, int K, int r, int bits,
+                           lords_dtype factor_dtype, void *stream)
+{
+    if (!dY || !X || !codes || !codebook || !B || !A || !dB || !dA) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (bad_nk(N, K) || r < 1 || M < 0) return LORDS_ERR_SHAPE;
+    if (misaligned(dY) || misaligned(X) || misaligned(codes) || misaligned(codebook) || misaligned(B) || misaligned(A) ||
+        misaligned(dB) || misaligned(dA))
+        return LORDS_ERR_ALIGN;
+    if (bad_dtype((int)factor_dtype)) return LORDS_ERR_DTYPE;
+    if (!lords::factor_grad_supported(N, K, r)) return LORDS_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    const int rc = get_workspace(lords::kTicketBytes + lords::factor_grad_workspace_bytes(N, K, r), &ws);
+    if (rc != LORDS_OK) return rc;
+    return lords::launch_factor_grad(dY, X, codes, codebook, B, A, dB, dA, M, N, K, r, bits, factor_dtype == LORDS_F32,
+                                     (unsigned char *)ws + lords::kTicketBytes, (hipStream_t)stream) == hipSuccess
+               ? LORDS_OK : LORDS_ERR_LAUNCH;
+}
+
 int lords_matmul(const void *X, const void *codes, const float *codebook, const void *B, const void *A, void *Y,
                  int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype y_dtype, void *stream)
 {

@@ -1,0 +1,402 @@
+// Backward of the LoRDS linear layer for fine-tuning the scale factors (Sec. 3.4: B and A are the
+// trainable parameters, the codes stay fixed).  With Y = X W_hat^T, W_hat = C[Q] (.) (B A):
+//
+//   dX = dY W_hat                      gradient with respect to the activations
+//   G  = dY^T X,  P = C[Q] (.) G       gradient with respect to W_hat and to the scale S = B A
+//   dB = P A^T,   dA = B^T P           gradients with respect to the factors
+//
+// dX.  The codes of a row run along K, but dX contracts over N.  Since Q is frozen during this kind
+// of fine-tuning, a second packed copy of it with the codes running along N (transpose_codes_kernel,
+// made once per layer, bits/8 bytes per weight) turns dX = dY W_hat into the forward product of the
+// transposed layer: W_hat^T = C[Q^T] (.) (A^T B^T), i.e. the ordinary kernels with (codes^T, A^T, B^T)
+// in the places of (codes, B, A).  Only the small factor transposes are done per call.
+//
+// dB, dA.  factor_grad_kernel: a workgroup of eight waves owns a 256-row x 128-column tile of G.
+// It walks M in chunks of 64 tokens; the dY tile (64 x 256) and the X tile (64 x 128) go from
+// global memory straight into LDS (global_load_lds_dwordx4), double-buffered, 16-byte chunks
+// XOR-swizzled by the row number.  Both are row-major along the token axis, which is the
+// contraction axis here, so both MFMA operands come out of LDS through the transposing read
+// (ds_read_b64_tr_b16).  Wave w owns rows 32w .. 32w+31 and all 128 columns: accumulator block
+// (kb, nb) holds G[k = 16kb + 4g + e][n = 32w + 16nb + c] in lane (c, g), element e -- four
+// consecutive columns of one row, which is (i) how the packed codes of that row are laid out, and
+// (ii) after the multiplication by the level, exactly the a-operand layout of
+// v_mfma_f32_16x16x16_bf16 for the contraction over k: dB needs no data movement at all.
+// For dA (contraction over n) the same P values go to LDS as a row-major bf16 tile and come back
+// through the transposing read, with the B tile as the other operand.
+// G and P never reach HBM.  The sums over the other tiles (column tiles for dB, row tiles for dA)
+// are written as fp32 partial results and added in a fixed order by reduce_partials_kernel:
+// results are run-to-run identical.
+#include "lords_decode_common.h"
+
+namespace lords {
+
+// ---------------------------------------------------------------------------------------------
+// packed codes, transposed: codes_t row k holds the codes of column k, code n at bits [bits*n, ..)
+// ---------------------------------------------------------------------------------------------
+// One thread per (column k, group of 32 rows): gathers 32 codes, one from each of 32 rows, and
+// writes the BITS dwords of the group.  A workgroup takes 32 consecutive columns of the same 32 rows
+// so that the 32 row segments it reads are contiguous.
+template <int BITS>
+__global__ __launch_bounds__(256) void transpose_codes_kernel(const uint8_t *__restrict__ codes, uint8_t *__restrict__ codes_t,
+                                                              int N, int K)
+{
+    __shared__ uint32_t tile[32][BITS * 8 + 1];             // 32 rows x 256 columns of codes
+    const int n0 = blockIdx.y * 32, k0 = blockIdx.x * 256;
+    const int row_bytes = K / 8 * BITS, rowt_bytes = N / 8 * BITS;
+    // the 32 x (256 codes = BITS*8 dwords) source block, coalesced
+    for (int id = threadIdx.x; id < 32 * BITS * 8; id += 256) {
+        const int rr = id / (BITS * 8), d = id % (BITS * 8);
+        const int kd = (k0 >> 5) * BITS + d;                 // dword within the row
+        uint32_t v = 0;
+        if (n0 + rr < N && kd < row_bytes / 4)
+            v = reinterpret_cast<const uint32_t *>(codes + (size_t)(n0 + rr) * row_bytes)[kd];
+        tile[rr][d] = v;
+    }
+    __syncthreads();
+    const int kk = threadIdx.x;                              // column within the block
+    if (k0 + kk >= K) return;
+    const int grp = kk >> 5, e = kk & 31;                    // its 32-code group and place in it
+    uint32_t out[BITS];
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) out[i] = 0;
+#pragma unroll
+    for (int rr = 0; rr < 32; ++rr) {
+        // code e of group grp of source row rr
+        const int o = BITS * e, d = o >> 5, s = o & 31;
+        uint32_t v = tile[rr][grp * BITS + d] >> s;
+        if (s + BITS > 32) v |= tile[rr][grp * BITS + d + 1] << (32 - s);
+        v &= (1u << BITS) - 1u;
+        // becomes code rr of the destination group
+        const int o2 = BITS * rr, d2 = o2 >> 5, s2 = o2 & 31;
+        out[d2] |= v << s2;
+        if (s2 + BITS > 32) out[d2 + 1 < BITS ? d2 + 1 : d2] |= v >> (32 - s2);
+    }
+    uint32_t *dst = reinterpret_cast<uint32_t *>(codes_t + (size_t)(k0 + kk) * rowt_bytes) + (n0 >> 5) * BITS;
+#pragma unroll
+    for (int i = 0; i < BITS; ++i) dst[i] = out[i];
+}
+
+hipError_t launch_transpose_codes(const void *codes, void *codes_t, int N, int K, int bits, hipStream_t st)
+{
+    const dim3 grid((unsigned)((K + 255) / 256), (unsigned)(N / 32)), block(256);
+    switch (bits) {
+        case 2: hipLaunchKernelGGL(transpose_codes_kernel<2>, grid, block, 0, st, (const uint8_t *)codes, (uint8_t *)codes_t, N, K); break;
+        case 3: hipLaunchKernelGGL(transpose_codes_kernel<3>, grid, block, 0, st, (const uint8_t *)codes, (uint8_t *)codes_t, N, K); break;
+        default: hipLaunchKernelGGL(transpose_codes_kernel<4>, grid, block, 0, st, (const uint8_t *)codes, (uint8_t *)codes_t, N, K); break;
+    }
+    return hipGetLastError();
+}
+
+// out[c][r] = in[r][c] for a small rows x cols factor (bf16 or fp32 elements), through a 32 x 32 tile
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_factor_kernel(const T *__restrict__ in, T *__restrict__ out, int rows, int cols)
+{
+    __shared__ T tile[32][33];
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    for (int id = threadIdx.x; id < 1024; id += 256) {
+        const int rr = id >> 5, cc = id & 31;
+        if (r0 + rr < rows && c0 + cc < cols) tile[rr][cc] = in[(size_t)(r0 + rr) * cols + c0 + cc];
+    }
+    __syncthreads();
+    for (int id = threadIdx.x; id < 1024; id += 256) {
+        const int cc = id >> 5, rr = id & 31;
+        if (r0 + rr < rows && c0 + cc < cols) out[(size_t)(c0 + cc) * rows + r0 + rr] = tile[rr][cc];
+    }
+}
+
+hipError_t launch_transpose_factor(const void *in, void *out, int rows, int cols, bool f32, hipStream_t st)
+{
+    const dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32)), block(256);
+    if (f32) hipLaunchKernelGGL(transpose_factor_kernel<float>, grid, block, 0, st, (const float *)in, (float *)out, rows, cols);
+    else hipLaunchKernelGGL(transpose_factor_kernel<uint16_t>, grid, block, 0, st, (const uint16_t *)in, (uint16_t *)out, rows, cols);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// factor gradients
+// ---------------------------------------------------------------------------------------------
+struct FgArgs {
+    const uint16_t *dY;    // M x N bf16
+    const uint16_t *X;     // M x K bf16
+    const uint8_t *codes;
+    const float *codebook;
+    const void *B;         // N x r
+    const void *A;         // r x K
+    float *partB;          // [ktiles][N][r]
+    float *partA;          // [ntiles][r][K]
+    int M, N, K, r;
+    int f32fact;
+    int row_bytes;
+    int ntiles, ktiles;
+};
+
+constexpr int kFgThreads = 512;
+constexpr int kFgBN = 256, kFgBK = 128, kFgMC = 64;
+constexpr int kFgDYB = kFgMC * kFgBN * 2, kFgXB = kFgMC * kFgBK * 2;     // bytes of one dY / X tile
+constexpr int kFgStage = 2 * (kFgDYB + kFgXB);
+constexpr int kFgAST = 264;                                               // bytes per row of the A tile (128 columns + pad)
+
+__device__ __forceinline__ void fg_lds_direct_16(const void *gsrc, void *lds_wave_base)
+{
+    // Every active lane fetches 16 bytes from its own address; they land at lds_wave_base + 16*lane
+    // (M0 holds the wave's LDS base).  Written as assembly so that the compiler does not make later
+    // LDS reads wait for these loads; the kernel waits for them itself before a buffer is read.
+    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(base), "v"(gsrc) : "memory", "m0");
+}
+
+// Transposing read of 8 consecutive rows of one column block out of a row-major, chunk-swizzled
+// tile (rows of ROWB bytes; the 16-byte chunk ch of row m sits in slot ch ^ (m & 15)): lane (c, g)
+// passes row0 = first row + 8g and col0 = first column of the 16-column block and receives
+// tile[row0 + e][col0 + c], e = 0..7.
+template <int ROWB>
+__device__ __forceinline__ bf16x8 fg_tr_read(const unsigned char *tile, int row0, int col0, int c)
+{
+    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+    const int col = col0 + 4 * (c & 3);
+    const int ra = row0 + (c >> 2), rb = ra + 4;
+    const unsigned char *p0 = tile + ra * ROWB + (((col >> 3) ^ (ra & 15)) << 4) + ((col & 7) << 1);
+    const unsigned char *p1 = tile + rb * ROWB + (((col >> 3) ^ (rb & 15)) << 4) + ((col & 7) << 1);
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p0);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p1);
+    return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// BITS: code width.  SS: the rank padded to 32*SS (1 or 2).
+template <int BITS, int SS>
+__global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void factor_grad_kernel(FgArgs a)
+{
+    constexpr int RP = 32 * SS, JB = 2 * SS;                  // padded rank, 16-entry rank blocks
+    constexpr int BST = (RP + 4) * 2;                         // bytes per row of the B tile
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char *As = smem + kFgStage;                      // [RP][kFgAST]  bf16
+    unsigned char *Bs = As + RP * kFgAST;                     // [256][BST]    bf16
+    float *cb = reinterpret_cast<float *>(Bs + kFgBN * BST);  // [2^BITS]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int M = a.M, N = a.N, K = a.K, r = a.r;
+    const int nt = blockIdx.x / a.ktiles, kt = blockIdx.x % a.ktiles;
+    const int n0 = nt * kFgBN, k0 = kt * kFgBK;
+
+    // ---- staging of one chunk of 64 tokens into buffer p -------------------------------------------
+    auto stage = [&](int ch, int p) {
+        unsigned char *dYs = smem + p * (kFgDYB + kFgXB), *Xs = dYs + kFgDYB;
+#pragma nounroll
+        for (int q = 0; q < 4; ++q) {                        // dY: a wave-level load covers two rows of 512 bytes
+            const int row = 16 * q + 2 * wave + (lane >> 5), slot = lane & 31;
+            const int n = min(n0 + 8 * (slot ^ (row & 15)), N - 8);       // (columns >= N: finite filler, masked later)
+            const int m = ch * kFgMC + row;
+            unsigned char *dst = dYs + (16 * q + 2 * wave) * 512;
+            if (m < M) fg_lds_direct_16(a.dY + (size_t)m * N + n, dst);
+            else *reinterpret_cast<u32x4 *>(dst + 16 * lane) = u32x4{0u, 0u, 0u, 0u};   // tokens >= M add nothing
+        }
+#pragma nounroll
+        for (int q = 0; q < 2; ++q) {                        // X: four rows of 256 bytes
+            const int row = 32 * q + 4 * wave + (lane >> 4), slot = lane & 15;
+            const int k = min(k0 + 8 * (slot ^ (row & 15)), K - 8);
+            const int m = ch * kFgMC + row;
+            unsigned char *dst = Xs + (32 * q + 4 * wave) * 256;
+            if (m < M) fg_lds_direct_16(a.X + (size_t)m * K + k, dst);
+            else *reinterpret_cast<u32x4 *>(dst + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    stage(0, 0);
+
+    // ---- A tile (rank x 128 columns), B tile (256 rows x rank), level table: once per workgroup ------
+    for (int id = tid; id < RP * kFgBK; id += kFgThreads) {
+        const int j = id / kFgBK, kk = id % kFgBK;
+        uint16_t v = 0;
+        if (j < r && k0 + kk < K)
+            v = a.f32fact ? bf16_bits(reinterpret_cast<const float *>(a.A)[(size_t)j * K + k0 + kk])
+                          : reinterpret_cast<const uint16_t *>(a.A)[(size_t)j * K + k0 + kk];
+        *reinterpret_cast<uint16_t *>(As + j * kFgAST + kk * 2) = v;
+    }
+    for (int id = tid; id < kFgBN * RP; id += kFgThreads) {
+        const int nn = id / RP, j = id % RP;
+        uint16_t v = 0;
+        if (j < r && n0 + nn < N)
+            v = a.f32fact ? bf16_bits(reinterpret_cast<const float *>(a.B)[(size_t)(n0 + nn) * r + j])
+                          : reinterpret_cast<const uint16_t *>(a.B)[(size_t)(n0 + nn) * r + j];
+        *reinterpret_cast<uint16_t *>(Bs + nn * BST + j * 2) = v;
+    }
+    if (tid < (1 << BITS)) cb[tid] = a.codebook[tid];
+
+    // ---- G = dY^T X over the tokens -----------------------------------------------------------------
+    f32x4 acc[8][2];
+#pragma unroll
+    for (int kb = 0; kb < 8; ++kb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) acc[kb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nchunks = (M + kFgMC - 1) / kFgMC;
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const int p = ch & 1;
+        if (ch + 1 < nchunks) stage(ch + 1, p ^ 1);
+        const unsigned char *dYs = smem + p * (kFgDYB + kFgXB), *Xs = dYs + kFgDYB;
+#pragma unroll
+        for (int ms = 0; ms < 2; ++ms) {
+            bf16x8 Yop[2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) Yop[nb] = fg_tr_read<512>(dYs, 32 * ms + 8 * g, 32 * wave + 16 * nb, c);
+#pragma unroll
+            for (int kb = 0; kb < 8; ++kb) {
+                const bf16x8 Xop = fg_tr_read<256>(Xs, 32 * ms + 8 * g, 16 * kb, c);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[kb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Xop, Yop[nb], acc[kb][nb], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);          // the next chunk has landed
+        __syncthreads();
+    }
+
+    // ---- P = level (.) G; dB = P A^T straight from the registers; P to LDS for dA ----------------------
+    // (the staging buffers are free: every wave has passed the barrier that ended the last chunk)
+    unsigned char *Ps = smem;                                 // [256][256 bytes], chunk-swizzled like the X tile
+    f32x4 dBacc[2][JB];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) dBacc[nb][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int row_dwords = a.row_bytes >> 2;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int nl = 32 * wave + 16 * nb + c, n = n0 + nl;  // the row whose four values this lane holds
+        const uint32_t *row32 = reinterpret_cast<const uint32_t *>(a.codes + (size_t)min(n, N - 1) * a.row_bytes);
+#pragma unroll
+        for (int kb = 0; kb < 8; ++kb) {
+            const int kl = 16 * kb + 4 * g, kk = k0 + kl;     // its four columns kk .. kk+3
+            const int kc = min(kk, K - 4);
+            const int off = BITS * kc, d = off >> 5, sh = off & 31;
+            const uint64_t w = (uint64_t)row32[d] | ((uint64_t)row32[min(d + 1, row_dwords - 1)] << 32);
+            const uint32_t v = (uint32_t)(w >> sh);
+            const bool ok = n < N && kk < K;
+            typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4v;
+            s16x4v pb;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lvl = cb[(v >> (BITS * e)) & ((1u << BITS) - 1u)];
+                const float pv = ok ? lvl * acc[kb][nb][e] : 0.f;
+                pb[e] = (short)bf16_bits(pv);
+            }
+            // dB[n][j] += sum over these four columns of P[n][k] A[j][k]
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) {
+                const s16x4v aop = *reinterpret_cast<const s16x4v *>(As + (16 * jb + c) * kFgAST + kl * 2);
+                dBacc[nb][jb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, aop, dBacc[nb][jb], 0, 0, 0);
+            }
+            *reinterpret_cast<s16x4v *>(Ps + nl * 256 + (((kl >> 3) ^ (nl & 15)) << 4) + ((kl & 7) << 1)) = pb;
+        }
+    }
+    // dB partial of this column tile: lane (c, g) holds rows 4g+e of rank entry 16 jb + c
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+            const int j = 16 * jb + c;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int n = n0 + 32 * wave + 16 * nb + 4 * g + e;
+                if (n < N && j < r) a.partB[((size_t)kt * N + n) * r + j] = dBacc[nb][jb][e];
+            }
+        }
+    __syncthreads();
+
+    // ---- dA = B^T P over the 256 rows: wave w takes columns 16w .. 16w+15, all rank blocks ------------
+    f32x4 dAacc[JB];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) dAacc[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ns = 0; ns < 8; ++ns) {
+        const bf16x8 Pop = fg_tr_read<256>(Ps, 32 * ns + 8 * g, 16 * wave, c);
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+            typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+            const int ra = 32 * ns + 8 * g + (c >> 2), col = 16 * jb + 4 * (c & 3);
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(Bs + ra * BST + col * 2));
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(Bs + (ra + 4) * BST + col * 2));
+            const bf16x8 Bop = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            dAacc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Bop, Pop, dAacc[jb], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb) {
+        const int k = k0 + 16 * wave + c;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = 16 * jb + 4 * g + e;
+            if (j < r && k < K) a.partA[((size_t)nt * r + j) * K + k] = dAacc[jb][e];
+        }
+    }
+}
+
+// out[i] = sum over p of part[p][i], p increasing
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ part, float *__restrict__ out,
+                                                              long count, int nparts)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    float s = 0.f;
+    for (int p = 0; p < nparts; ++p) s += part[(size_t)p * count + i];
+    out[i] = s;
+}
+
+bool factor_grad_supported(int N, int K, int r) { return r >= 1 && r <= 64 && (N % 8) == 0 && N >= 8 && K >= 32; }
+
+size_t factor_grad_workspace_bytes(int N, int K, int r)
+{
+    const size_t ntiles = (N + kFgBN - 1) / kFgBN, ktiles = (K + kFgBK - 1) / kFgBK;
+    return (ktiles * (size_t)N * r + ntiles * (size_t)r * K) * sizeof(float);
+}
+
+template <int BITS, int SS>
+static hipError_t launch_fg_t(const FgArgs &a, hipStream_t st)
+{
+    constexpr int RP = 32 * SS;
+    const size_t smem = (size_t)kFgStage + (size_t)RP * kFgAST + (size_t)kFgBN * (RP + 4) * 2 + (size_t)(1 << BITS) * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&factor_grad_kernel<BITS, SS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((factor_grad_kernel<BITS, SS>), dim3(a.ntiles * a.ktiles), dim3(kFgThreads), smem, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_factor_grad(const void *dY, const void *X, const void *codes, const float *codebook, const void *B,
+                              const void *A, float *dB, float *dA, int M, int N, int K, int r, int bits, bool f32fact,
+                              void *workspace, hipStream_t st)
+{
+    FgArgs a;
+    a.dY = (const uint16_t *)dY;
+    a.X = (const uint16_t *)X;
+    a.codes = (const uint8_t *)codes;
+    a.codebook = codebook;
+    a.B = B;
+    a.A = A;
+    a.M = M; a.N = N; a.K = K; a.r = r;
+    a.f32fact = f32fact ? 1 : 0;
+    a.row_bytes = K / 8 * bits;
+    a.ntiles = (N + kFgBN - 1) / kFgBN;
+    a.ktiles = (K + kFgBK - 1) / kFgBK;
+    a.partB = (float *)workspace;
+    a.partA = a.partB + (size_t)a.ktiles * N * r;
+    const int ss = r <= 32 ? 1 : 2;
+    hipError_t e = hipErrorInvalidValue;
+#define LORDS_FGCASE(B_, S_) if (bits == B_ && ss == S_) e = launch_fg_t<B_, S_>(a, st);
+    LORDS_FGCASE(2, 1) LORDS_FGCASE(2, 2) LORDS_FGCASE(3, 1) LORDS_FGCASE(3, 2) LORDS_FGCASE(4, 1) LORDS_FGCASE(4, 2)
+#undef LORDS_FGCASE
+    if (e != hipSuccess) return e;
+    const long cb = (long)N * r, ca = (long)r * K;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((cb + 255) / 256)), dim3(256), 0, st, a.partB, dB, cb, a.ktiles);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((ca + 255) / 256)), dim3(256), 0, st, a.partA, dA, ca, a.ntiles);
+    return hipGetLastError();
+}
+
+}  // namespace lords

@@ -20,6 +20,18 @@ hipError_t launch_quantize(const void *W, const float *codebook, const void *B, 
 hipError_t launch_block_init(const void *W, const float *codebook, void *B, void *A,
                              int N, int K, int r, int bits, bool f32w, bool f32fact, hipStream_t st);
 
+// Backward side (lords_backward.hip).  codes_t: the packed codes with the roles of rows and columns
+// swapped (K rows of N codes); N must be a multiple of 32.
+hipError_t launch_transpose_codes(const void *codes, void *codes_t, int N, int K, int bits, hipStream_t st);
+hipError_t launch_transpose_factor(const void *in, void *out, int rows, int cols, bool f32, hipStream_t st);
+// dB (N x r) and dA (r x K), fp32, from dY (M x N) and X (M x K), both bf16.  `workspace` must hold
+// factor_grad_workspace_bytes(N, K, r) bytes (fp32 partial results per tile, added in a fixed order).
+bool factor_grad_supported(int N, int K, int r);
+size_t factor_grad_workspace_bytes(int N, int K, int r);
+hipError_t launch_factor_grad(const void *dY, const void *X, const void *codes, const float *codebook, const void *B,
+                              const void *A, float *dB, float *dA, int M, int N, int K, int r, int bits, bool f32fact,
+                              void *workspace, hipStream_t st);
+
 struct MatmulProblem {
     const void *X;          // M x K bf16
     const void *codes;      // N x K*bits/8

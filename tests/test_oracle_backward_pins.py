@@ -101,3 +101,16 @@ def test_planted_mistakes_are_caught():
     assert not np.allclose(wrong_no_level, fd_B, rtol=1e-3, atol=1e-3)
     assert not np.allclose(wrong_role, fd_B, rtol=1e-3, atol=1e-3)
     assert np.allclose(dB, fd_B, rtol=1e-7, atol=1e-7)
+
+
+def test_restricted_forms_match_the_full_ones():
+    c = case(3, N=12, K=64, r=3, M=5, seed=5)
+    dX = onp.backward_input(c["dY"], c["codes"], c["C"], c["B"], c["A"], 3)
+    dB, dA = onp.backward_factors(c["dY"], c["X"], c["codes"], c["C"], c["B"], c["A"], 3)
+    cols, rows = [0, 7, 63, 31], [11, 0, 5]
+    np.testing.assert_allclose(onp.backward_input_cols(c["dY"], c["codes"], c["C"], c["B"], c["A"], 3, cols), dX[:, cols],
+                               rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(onp.backward_factors_rows(c["dY"], c["X"], c["codes"], c["C"], c["B"], c["A"], 3, rows),
+                               dB[rows], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(onp.backward_factors_cols(c["dY"], c["X"], c["codes"], c["C"], c["B"], c["A"], 3, cols),
+                               dA[:, cols], rtol=1e-12, atol=1e-12)

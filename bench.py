@@ -188,7 +188,40 @@ def bench_other(args, L, li, torch):
                         "frac_of_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS})
         del sets, X, Y
     out.extend(bench_shared_input(args, L, li, torch))
+    out.extend(bench_backward(args, L, li, torch))
     return out
+
+
+def bench_backward(args, L, li, torch):
+    """Context figures for one fine-tuning step of the scale factors on the headline layer, 2048 tokens:
+    forward, gradient with respect to the activations (through the transposed codes), gradients with
+    respect to B and A."""
+    name, M = "gateup_4b", 2048
+    cfg = li.CONFIGS[name]
+    cs, sets, X, codebook = make_sets(name, M, 1, li, torch)
+    codes, B, A = sets[0]
+    dY = L.bf16_from_bits(li.make_output_grad(M, cfg.N, 4000)[0])
+    codes_t = torch.empty((cfg.K, cfg.N * cfg.bits // 8), dtype=torch.uint8, device="cuda")
+    L.lords_transpose_codes(codes, codes_t, cfg.N, cfg.K, cfg.bits)
+    Y = torch.zeros((M, cfg.N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.zeros((M, cfg.K), dtype=torch.bfloat16, device="cuda")
+    dB = torch.zeros((cfg.N, cfg.r), dtype=torch.float32, device="cuda")
+    dA = torch.zeros((cfg.r, cfg.K), dtype=torch.float32, device="cuda")
+    legs = {
+        "forward": lambda i: L.lords_matmul(X, codes, codebook, B, A, Y, M, cfg.N, cfg.K, cfg.r, cfg.bits),
+        "backward_input": lambda i: L.lords_backward_input(dY, codes_t, codebook, B, A, dX, M, cfg.N, cfg.K, cfg.r, cfg.bits),
+        "backward_factors": lambda i: L.lords_backward_factors(dY, X, codes, codebook, B, A, dB, dA, M, cfg.N, cfg.K, cfg.r,
+                                                               cfg.bits),
+    }
+    fl = 2.0 * M * cfg.N * cfg.K
+    res = {}
+    for label, fn in legs.items():
+        _, ev_ms, _, _ = time_steps(fn, 10, 3, torch, use_graph=False)
+        res[label] = ev_ms * 1e3 / 10
+    total = sum(res.values())
+    return [{"workload": f"fine-tuning step of the scale factors, M={M} on the headline layer: forward + dX + (dB, dA)",
+             "us_per_step": total, "us_by_leg": res, "value": 3 * fl / total / 1e6, "unit": "TFLOP/s",
+             "frac_of_mfma_peak": 3 * fl / total / 1e6 / MFMA_BF16_PEAK_TFLOPS}]
 
 
 def bench_shared_input(args, L, li, torch):

@@ -218,6 +218,63 @@ def test_gate_up_argument_checks():
     assert f(*a) == 0
 
 
+def test_transpose_codes_argument_checks():
+    f = L.library().lords_transpose_codes
+    ok = [P, P, 64, 64, 4, None]
+    for i in (0, 1):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[4] = 8
+    assert f(*a) == 2
+    for i, v in ((2, 0), (2, 40), (3, 16), (3, 48)):        # N must be a multiple of 32, K too
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    a = list(ok); a[1] = P + 4
+    assert f(*a) == 4
+
+
+def test_backward_input_argument_checks():
+    f = L.library().lords_backward_input
+    #     dY codes_t cb B  A  dX M  N   K   r  bits fdt xdt stream
+    ok = [P, P,      P, P, P, P, 2, 64, 64, 4, 4,   0,  1,  None]
+    for i in range(6):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[10] = 0
+    assert f(*a) == 2
+    for i, v in ((6, -1), (7, 48), (7, 0), (8, 40), (9, 0)):
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    a = list(ok); a[5] = P + 8
+    assert f(*a) == 4
+    for i in (11, 12):
+        a = list(ok); a[i] = 4
+        assert f(*a) == 5
+    a = list(ok); a[6] = 0
+    assert f(*a) == 0
+
+
+def test_backward_factors_argument_checks():
+    f = L.library().lords_backward_factors
+    #     dY X  codes cb B  A  dB dA M  N   K   r  bits fdt stream
+    ok = [P, P, P,    P, P, P, P, P, 2, 64, 64, 4, 4,   0,  None]
+    for i in range(8):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[12] = 5
+    assert f(*a) == 2
+    for i, v in ((8, -1), (9, 0), (10, 16), (11, 0)):
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    a = list(ok); a[6] = P + 4
+    assert f(*a) == 4
+    a = list(ok); a[13] = 2
+    assert f(*a) == 5
+    for i, v in ((9, 36), (11, 65)):                         # rows not a multiple of 8; rank above 64
+        a = list(ok); a[i] = v
+        assert f(*a) == 7
+
+
 def test_binding_raises_with_status_name():
     with pytest.raises(L.LordsError) as e:
         L.binding._check(4, "lords_matmul")

@@ -57,7 +57,7 @@ typedef enum { LORDS_BF16 = 0, LORDS_F32 = 1 } lords_dtype;
 /* Which kernel family lords_matmul_ex runs.  AUTO picks by M. */
 typedef enum {
     LORDS_PATH_AUTO = 0,
-    LORDS_PATH_DECODE = 1,   /* memory-bound small-M path (16 tokens per pass) */
+    LORDS_PATH_DECODE = 1,   /* memory-bound small-M path (16 tokens per pass over the codes) */
     LORDS_PATH_PREFILL = 2   /* bf16 MFMA GEMM with the dequantised tile as operand */
 } lords_path;
 
@@ -115,9 +115,10 @@ int lords_block_init(const void *W, const float *codebook, void *B, void *A,
  * (the linear layer the paper's inference kernel replaces, Sec. 4.4; Fig. 1b).
  *   X   in   M x K bf16
  *   Y   out  M x N, dtype `y_dtype`; accumulation is fp32.
- * M == 0 returns LORDS_OK without launching.  M <= 32 takes the memory-bound
- * decode kernels (16 tokens per pass), larger M the MFMA GEMM; results are
- * run-to-run deterministic.
+ * M == 0 returns LORDS_OK without launching.  M <= 16 takes the memory-bound
+ * decode kernels (one pass over the codes for all tokens), larger M the MFMA GEMM
+ * (which cuts K into up to four ranges, added in a fixed order, when there are too
+ * few tiles to fill the chip); results are run-to-run deterministic.
  */
 int lords_matmul(const void *X, const void *codes, const float *codebook,
                  const void *B, const void *A, void *Y,

@@ -69,14 +69,17 @@ size_t decode_need(const lords::MatmulProblem &p)
 }
 inline lords_path resolve_path(lords_path path, int M)
 {
-    return path == LORDS_PATH_AUTO ? ((M <= 32) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL) : path;   // measured cross-over
+    return path == LORDS_PATH_AUTO ? ((M <= 16) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL) : path;   // measured cross-over
 }
 
 // Workspace for one checked problem on `path` (already resolved), plus `extra` bytes behind it that
 // are left to the caller (*extra_ptr).
 int plan_workspace(const lords::MatmulProblem &p, lords_path path, size_t extra, void **ws, void **extra_ptr)
 {
-    size_t own = path == LORDS_PATH_DECODE ? decode_need(p) : 0;
+    // (prefill: the tickets at the front are not used, but stay reserved)
+    size_t own = path == LORDS_PATH_DECODE ? decode_need(p)
+               : (lords::prefill_fast_supported(p) && lords::prefill_fast_workspace_bytes(p))
+                     ? lords::kTicketBytes + lords::prefill_fast_workspace_bytes(p) : 0;
     // the front of the buffer holds the arrival tickets of the small-M kernels and must stay zero
     // between calls: a caller's bytes never start inside it, whatever this problem itself needs
     if (extra && own < lords::kTicketBytes) own = lords::kTicketBytes;
@@ -97,8 +100,9 @@ int launch_matmul(const lords::MatmulProblem &p, lords_path path, void *ws, void
             default: e = lords::launch_decode(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream);
         }
     } else {
-        e = lords::prefill_fast_supported(p) ? lords::launch_prefill_fast(p, (hipStream_t)stream)
-                                             : lords::launch_prefill(p, (hipStream_t)stream);
+        e = lords::prefill_fast_supported(p)
+                ? lords::launch_prefill_fast(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream)
+                : lords::launch_prefill(p, (hipStream_t)stream);
     }
     return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
 }

@@ -14,7 +14,7 @@
 // dB, dA.  factor_grad_kernel: a workgroup of eight waves owns a 256-row x 128-column tile of G.
 // It walks M in chunks of 64 tokens; the dY tile (64 x 256) and the X tile (64 x 128) go from
 // global memory straight into LDS (global_load_lds_dwordx4), double-buffered, 16-byte chunks
-// XOR-swizzled by the row number.  Both are row-major along the token axis, which is the
+// XOR-swizzled by the row number (slot = chunk ^ 2(row & 7)).  Both are row-major along the token axis, which is the
 // contraction axis here, so both MFMA operands come out of LDS through the transposing read
 // (ds_read_b64_tr_b16).  Wave w owns rows 32w .. 32w+31 and all 128 columns: accumulator block
 // (kb, nb) holds G[k = 16kb + 4g + e][n = 32w + 16nb + c] in lane (c, g), element e -- four
@@ -147,7 +147,8 @@ __device__ __forceinline__ void fg_lds_direct_16(const void *gsrc, void *lds_wav
 }
 
 // Transposing read of 8 consecutive rows of one column block out of a row-major, chunk-swizzled
-// tile (rows of ROWB bytes; the 16-byte chunk ch of row m sits in slot ch ^ (m & 15)): lane (c, g)
+// tile (rows of ROWB bytes; the 16-byte chunk ch of row m sits in slot ch ^ 2(m & 7), so that the four
+// rows a group of 16 lanes reads, 32 bytes each, fall into different banks): lane (c, g)
 // passes row0 = first row + 8g and col0 = first column of the 16-column block and receives
 // tile[row0 + e][col0 + c], e = 0..7.
 template <int ROWB>
@@ -156,8 +157,8 @@ __device__ __forceinline__ bf16x8 fg_tr_read(const unsigned char *tile, int row0
     typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
     const int col = col0 + 4 * (c & 3);
     const int ra = row0 + (c >> 2), rb = ra + 4;
-    const unsigned char *p0 = tile + ra * ROWB + (((col >> 3) ^ (ra & 15)) << 4) + ((col & 7) << 1);
-    const unsigned char *p1 = tile + rb * ROWB + (((col >> 3) ^ (rb & 15)) << 4) + ((col & 7) << 1);
+    const unsigned char *p0 = tile + ra * ROWB + (((col >> 3) ^ ((ra & 7) << 1)) << 4) + ((col & 7) << 1);
+    const unsigned char *p1 = tile + rb * ROWB + (((col >> 3) ^ ((rb & 7) << 1)) << 4) + ((col & 7) << 1);
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p0);
     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p1);
     return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma nounroll
         for (int q = 0; q < 4; ++q) {                        // dY: a wave-level load covers two rows of 512 bytes
             const int row = 16 * q + 2 * wave + (lane >> 5), slot = lane & 31;
-            const int n = min(n0 + 8 * (slot ^ (row & 15)), N - 8);       // (columns >= N: finite filler, masked later)
+            const int n = min(n0 + 8 * (slot ^ ((row & 7) << 1)), N - 8);       // (columns >= N: finite filler, masked later)
             const int m = ch * kFgMC + row;
             unsigned char *dst = dYs + (16 * q + 2 * wave) * 512;
             if (m < M) fg_lds_direct_16(a.dY + (size_t)m * N + n, dst);
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma nounroll
         for (int q = 0; q < 2; ++q) {                        // X: four rows of 256 bytes
             const int row = 32 * q + 4 * wave + (lane >> 4), slot = lane & 15;
-            const int k = min(k0 + 8 * (slot ^ (row & 15)), K - 8);
+            const int k = min(k0 + 8 * (slot ^ ((row & 7) << 1)), K - 8);
             const int m = ch * kFgMC + row;
             unsigned char *dst = Xs + (32 * q + 4 * wave) * 256;
             if (m < M) fg_lds_direct_16(a.X + (size_t)m * K + k, dst);
@@ -205,21 +206,57 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     stage(0, 0);
 
     // ---- A tile (rank x 128 columns), B tile (256 rows x rank), level table: once per workgroup ------
-    for (int id = tid; id < RP * kFgBK; id += kFgThreads) {
-        const int j = id / kFgBK, kk = id % kFgBK;
-        uint16_t v = 0;
-        if (j < r && k0 + kk < K)
-            v = a.f32fact ? bf16_bits(reinterpret_cast<const float *>(a.A)[(size_t)j * K + k0 + kk])
-                          : reinterpret_cast<const uint16_t *>(a.A)[(size_t)j * K + k0 + kk];
-        *reinterpret_cast<uint16_t *>(As + j * kFgAST + kk * 2) = v;
-    }
-    for (int id = tid; id < kFgBN * RP; id += kFgThreads) {
-        const int nn = id / RP, j = id % RP;
-        uint16_t v = 0;
-        if (j < r && n0 + nn < N)
-            v = a.f32fact ? bf16_bits(reinterpret_cast<const float *>(a.B)[(size_t)(n0 + nn) * r + j])
-                          : reinterpret_cast<const uint16_t *>(a.B)[(size_t)(n0 + nn) * r + j];
-        *reinterpret_cast<uint16_t *>(Bs + nn * BST + j * 2) = v;
+    typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+    if (!a.f32fact && (r & 7) == 0) {
+        // 16-byte pieces, all loads of a thread in flight together (rows of the LDS tiles are only
+        // 8-byte aligned: two stores per piece)
+        u32x4 va[RP * 16 / kFgThreads], vb[kFgBN * (RP / 8) / kFgThreads];
+#pragma unroll
+        for (int q = 0; q < RP * 16 / kFgThreads; ++q) {
+            const int id = tid + kFgThreads * q, j = id >> 4, kk = 8 * (id & 15);
+            va[q] = u32x4{0u, 0u, 0u, 0u};
+            if (j < r && k0 + kk < K) va[q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.A) + (size_t)j * K + k0 + kk);
+        }
+#pragma unroll
+        for (int q = 0; q < kFgBN * (RP / 8) / kFgThreads; ++q) {
+            const int id = tid + kFgThreads * q, nn = id / (RP / 8), j = 8 * (id % (RP / 8));
+            vb[q] = u32x4{0u, 0u, 0u, 0u};
+            if (j < r && n0 + nn < N) vb[q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.B) + (size_t)(n0 + nn) * r + j);
+        }
+#pragma unroll
+        for (int q = 0; q < RP * 16 / kFgThreads; ++q) {
+            const int id = tid + kFgThreads * q, j = id >> 4, kk = 8 * (id & 15);
+            u32x2 *dst = reinterpret_cast<u32x2 *>(As + j * kFgAST + kk * 2);
+            dst[0] = u32x2{va[q][0], va[q][1]};
+            dst[1] = u32x2{va[q][2], va[q][3]};
+        }
+#pragma unroll
+        for (int q = 0; q < kFgBN * (RP / 8) / kFgThreads; ++q) {
+            const int id = tid + kFgThreads * q, nn = id / (RP / 8), j = 8 * (id % (RP / 8));
+            u32x2 *dst = reinterpret_cast<u32x2 *>(Bs + nn * BST + j * 2);
+            dst[0] = u32x2{vb[q][0], vb[q][1]};
+            dst[1] = u32x2{vb[q][2], vb[q][3]};
+        }
+    } else {
+        // fp32 factors (rounded to bf16 here) or a rank that is not a multiple of 8: entry by entry
+#pragma unroll 8
+        for (int id = tid; id < RP * kFgBK; id += kFgThreads) {
+            const int j = id / kFgBK, kk = id % kFgBK;
+            uint16_t v = 0;
+            if (j < r && k0 + kk < K)
+                v = a.f32fact ? bf16_bits(reinterpret_cast<const float *>(a.A)[(size_t)j * K + k0 + kk])
+                              : reinterpret_cast<const uint16_t *>(a.A)[(size_t)j * K + k0 + kk];
+            *reinterpret_cast<uint16_t *>(As + j * kFgAST + kk * 2) = v;
+        }
+#pragma unroll 8
+        for (int id = tid; id < kFgBN * RP; id += kFgThreads) {
+            const int nn = id / RP, j = id % RP;
+            uint16_t v = 0;
+            if (j < r && n0 + nn < N)
+                v = a.f32fact ? bf16_bits(reinterpret_cast<const float *>(a.B)[(size_t)(n0 + nn) * r + j])
+                              : reinterpret_cast<const uint16_t *>(a.B)[(size_t)(n0 + nn) * r + j];
+            *reinterpret_cast<uint16_t *>(Bs + nn * BST + j * 2) = v;
+        }
     }
     if (tid < (1 << BITS)) cb[tid] = a.codebook[tid];
 
@@ -237,19 +274,22 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         const int p = ch & 1;
         if (ch + 1 < nchunks) stage(ch + 1, p ^ 1);
         const unsigned char *dYs = smem + p * (kFgDYB + kFgXB), *Xs = dYs + kFgDYB;
+        // all operand reads of the chunk are issued before the first MFMA: the LDS round trip is paid once
+        bf16x8 Yop[2][2], Xop[2][8];
 #pragma unroll
         for (int ms = 0; ms < 2; ++ms) {
-            bf16x8 Yop[2];
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) Yop[nb] = fg_tr_read<512>(dYs, 32 * ms + 8 * g, 32 * wave + 16 * nb, c);
+            for (int nb = 0; nb < 2; ++nb) Yop[ms][nb] = fg_tr_read<512>(dYs, 32 * ms + 8 * g, 32 * wave + 16 * nb, c);
 #pragma unroll
-            for (int kb = 0; kb < 8; ++kb) {
-                const bf16x8 Xop = fg_tr_read<256>(Xs, 32 * ms + 8 * g, 16 * kb, c);
+            for (int kb = 0; kb < 8; ++kb) Xop[ms][kb] = fg_tr_read<256>(Xs, 32 * ms + 8 * g, 16 * kb, c);
+        }
+#pragma unroll
+        for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+            for (int kb = 0; kb < 8; ++kb)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    acc[kb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Xop, Yop[nb], acc[kb][nb], 0, 0, 0);
-            }
-        }
+                    acc[kb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Xop[ms][kb], Yop[ms][nb], acc[kb][nb], 0, 0, 0);
         __builtin_amdgcn_s_waitcnt(0);          // the next chunk has landed
         __syncthreads();
     }
@@ -289,7 +329,7 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 const s16x4v aop = *reinterpret_cast<const s16x4v *>(As + (16 * jb + c) * kFgAST + kl * 2);
                 dBacc[nb][jb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, aop, dBacc[nb][jb], 0, 0, 0);
             }
-            *reinterpret_cast<s16x4v *>(Ps + nl * 256 + (((kl >> 3) ^ (nl & 15)) << 4) + ((kl & 7) << 1)) = pb;
+            *reinterpret_cast<s16x4v *>(Ps + nl * 256 + (((kl >> 3) ^ ((nl & 7) << 1)) << 4) + ((kl & 7) << 1)) = pb;
         }
     }
     // dB partial of this column tile: lane (c, g) holds rows 4g+e of rank entry 16 jb + c

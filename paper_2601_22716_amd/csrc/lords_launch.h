@@ -92,7 +92,8 @@ size_t decode_workspace_bytes(const MatmulProblem &p);
 hipError_t launch_decode(const MatmulProblem &p, void *workspace, hipStream_t st);
 // MFMA GEMM path for large M: bf16 factors up to 128 rank columns (lords_prefill.hip) ...
 bool prefill_fast_supported(const MatmulProblem &p);
-hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st);
+size_t prefill_fast_workspace_bytes(const MatmulProblem &p);      // fp32 partial results when K is split
+hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStream_t st);
 // ... and the general variant (fp32 factors, any rank; lords_fused.hip).
 hipError_t launch_prefill(const MatmulProblem &p, hipStream_t st);
 

@@ -42,6 +42,7 @@ struct PrefillArgs {
     int row_bytes;
     int nt, mt;            // tiles along N and M
     int ntiles_k;          // ceil(K / 128)
+    int tiles_per_split;   // K tiles one workgroup walks; gridDim.y such ranges, each with its own M x N fp32 output
 };
 
 constexpr int kPfCopies = 8;
@@ -180,9 +181,11 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(2,
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[rho][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // this workgroup's range of K tiles (all of them unless K is split over gridDim.y)
+    const int kt0 = blockIdx.y * a.tiles_per_split, kt1 = min(kt0 + a.tiles_per_split, a.ntiles_k);
     uint32_t cw[R][BITS], cwn[R][BITS];
-    stage(0, 0);
-    load_codes(0, cw);
+    stage(kt0, 0);
+    load_codes(kt0, cw);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
 
@@ -192,9 +195,9 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(2,
     for (int u = 0; u < 4; ++u) xoff[u] = (uint32_t)(c * 256 + (((4 * g + u) ^ c) * 16));
     const uint32_t lutoff = (uint32_t)(2 * XBUF + 2 * ABUF) + (uint32_t)(lane & 7) * 4u;
 
-    for (int kt = 0; kt < a.ntiles_k; ++kt) {
-        const int p = kt & 1;
-        if (kt + 1 < a.ntiles_k) {
+    for (int kt = kt0; kt < kt1; ++kt) {
+        const int p = (kt - kt0) & 1;
+        if (kt + 1 < kt1) {
             stage(kt + 1, p ^ 1);
             load_codes(kt + 1, cwn);
         }
@@ -277,6 +280,8 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(2,
     }
 
     // ---- epilogue: lane (c,g) holds token 16 mb + c, rows 16 rho + 4 g + {0..3} ------------------------
+    // (with K split, a.Y is the fp32 buffer of partial results and this range writes its own M x N part)
+    void *Yp = gridDim.y > 1 ? (void *)(reinterpret_cast<float *>(a.Y) + (size_t)blockIdx.y * M * N) : a.Y;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m_wave + 16 * mb + c;
@@ -286,20 +291,20 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(2,
             const int n = n_wave + 16 * rho + 4 * g;
             if (n + 3 < N && (N & 3) == 0) {
                 if (a.y_f32) {
-                    *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(a.Y) + (size_t)m * N + n) = acc[rho][mb];
+                    *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(Yp) + (size_t)m * N + n) = acc[rho][mb];
                 } else {
                     typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
                     u32x2 o;
                     o[0] = (uint32_t)bf16_bits(acc[rho][mb][0]) | ((uint32_t)bf16_bits(acc[rho][mb][1]) << 16);
                     o[1] = (uint32_t)bf16_bits(acc[rho][mb][2]) | ((uint32_t)bf16_bits(acc[rho][mb][3]) << 16);
-                    *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(a.Y) + (size_t)m * N + n) = o;
+                    *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(Yp) + (size_t)m * N + n) = o;
                 }
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (n + e >= N) continue;
-                    if (a.y_f32) reinterpret_cast<float *>(a.Y)[(size_t)m * N + n + e] = acc[rho][mb][e];
-                    else reinterpret_cast<uint16_t *>(a.Y)[(size_t)m * N + n + e] = bf16_bits(acc[rho][mb][e]);
+                    if (a.y_f32) reinterpret_cast<float *>(Yp)[(size_t)m * N + n + e] = acc[rho][mb][e];
+                    else reinterpret_cast<uint16_t *>(Yp)[(size_t)m * N + n + e] = bf16_bits(acc[rho][mb][e]);
                 }
             }
         }
@@ -317,8 +322,76 @@ static int pf_ss(int r)
 
 bool prefill_fast_supported(const MatmulProblem &p) { return !p.f32fact && pf_ss(p.r) != 0; }
 
+// out[i] = sum over the K ranges of part[s][i], s increasing; four values per thread
+template <bool F32OUT>
+__global__ __launch_bounds__(256) void reduce_split_kernel(const float *__restrict__ part, void *__restrict__ Y, long count, int nparts)
+{
+    const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i0 >= count) return;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    if (i0 + 4 <= count) {
+        for (int p = 0; p < nparts; ++p) {
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(part + (size_t)p * count + i0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] += t[e];
+        }
+    } else {
+        for (int p = 0; p < nparts; ++p)
+            for (int e = 0; e < 4; ++e)
+                if (i0 + e < count) s[e] += part[(size_t)p * count + i0 + e];
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (i0 + e >= count) break;
+        if (F32OUT) reinterpret_cast<float *>(Y)[i0 + e] = s[e];
+        else reinterpret_cast<uint16_t *>(Y)[i0 + e] = bf16_bits(s[e]);
+    }
+}
+
+// Tile shape and K split of a problem.  Tile shapes, largest first: 256 tokens x 256 rows (8 waves,
+// 4 slabs each), 256 x 128, 128 x 128 (4 waves) for at most 128 tokens.  Padded ranks above 32 take
+// 128-token tiles only (their B operands need the registers, their A tile the LDS): 8 waves side by
+// side along N (256 rows) when that still gives every CU a tile, else 4 waves (128 rows).  Where the
+// tiles would leave most CUs idle, K is cut into up to 4 ranges, each range a workgroup of its own
+// writing fp32 partial results that a second kernel adds in range order (deterministic).
+struct PfPlan {
+    int ss, wm, R, wn, splits, tiles_per_split, nt, mt;
+};
+
+static PfPlan pf_plan(const MatmulProblem &p)
+{
+    PfPlan d;
+    d.ss = pf_ss(p.r);
+    d.wm = 1; d.R = 2; d.wn = 4;
+    if (d.ss == 1) {
+        const long t256 = (long)((p.N + 255) / 256) * ((p.M + 255) / 256);
+        if (t256 >= 224) { d.wm = 2; d.R = 4; }
+        else if (p.M > 128) d.wm = 2;
+    } else {
+        const long t = (long)((p.N + 255) / 256) * ((p.M + 127) / 128);
+        if (t >= 200) d.wn = 8;
+    }
+    d.nt = (p.N + 16 * d.R * d.wn - 1) / (16 * d.R * d.wn);
+    d.mt = (p.M + 128 * d.wm - 1) / (128 * d.wm);
+    const int ntiles_k = (p.K + 127) / 128;
+    const long tiles = (long)d.nt * d.mt;
+    long s = 256 / tiles;
+    if (s > 4) s = 4;
+    if (s > ntiles_k / 4) s = ntiles_k / 4;              // at least four K tiles per range
+    if (s < 1) s = 1;
+    d.tiles_per_split = (int)((ntiles_k + s - 1) / s);
+    d.splits = (ntiles_k + d.tiles_per_split - 1) / d.tiles_per_split;
+    return d;
+}
+
+size_t prefill_fast_workspace_bytes(const MatmulProblem &p)
+{
+    const PfPlan d = pf_plan(p);
+    return d.splits > 1 ? (size_t)d.splits * p.M * p.N * sizeof(float) : 0;
+}
+
 template <int BITS, int SS, int WM, int R, int WN = 4>
-static hipError_t launch_pf_t(const PrefillArgs &a, int grid, hipStream_t st)
+static hipError_t launch_pf_t(const PrefillArgs &a, dim3 grid, hipStream_t st)
 {
     const size_t smem = (size_t)2 * (128 * WM) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
     static bool attr_set = false;
@@ -328,55 +401,49 @@ static hipError_t launch_pf_t(const PrefillArgs &a, int grid, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM, R, WN>), dim3(grid), dim3(64 * WN * WM), smem, st, a);
+    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM, R, WN>), grid, dim3(64 * WN * WM), smem, st, a);
     return hipGetLastError();
 }
 
-hipError_t launch_prefill_fast(const MatmulProblem &p, hipStream_t st)
+// `workspace`: prefill_fast_workspace_bytes(p) bytes (only used when K is split).
+hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStream_t st)
 {
-    const int ss = pf_ss(p.r);
-    // Tile shapes, largest first: 256 tokens x 256 rows (8 waves, 4 slabs each), 256 x 128, and for
-    // shapes that would leave CUs idle 128 tokens x 128 rows (4 waves).  Padded ranks above 32 take
-    // 128-token tiles only (their B operands need the registers, their A tile the LDS): 8 waves side
-    // by side along N (256 rows) when that still gives every CU a tile, else 4 waves (128 rows).
-    int wm = ss == 1 ? 2 : 1, R = 2, wn = 4;
-    if (ss == 1) {
-        const long t256 = (long)((p.N + 255) / 256) * ((p.M + 255) / 256);
-        const long t128 = (long)((p.N + 127) / 128) * ((p.M + 255) / 256);
-        if (t256 >= 224) R = 4;
-        else if (t128 < 200) wm = 1;
-    } else {
-        const long t = (long)((p.N + 255) / 256) * ((p.M + 127) / 128);
-        if (t >= 200) wn = 8;
-    }
-    const int BM = 128 * wm;
-    const int mt = (p.M + BM - 1) / BM;
+    const PfPlan d = pf_plan(p);
+    if (d.splits > 1 && !workspace) return hipErrorInvalidValue;
+    const int ss = d.ss, wm = d.wm, R = d.R, wn = d.wn;
     PrefillArgs a;
     a.X = (const uint16_t *)p.X;
     a.codes = (const uint8_t *)p.codes;
     a.codebook = p.codebook;
     a.B = (const uint16_t *)p.B;
     a.A = (const uint16_t *)p.A;
-    a.Y = p.Y;
+    a.Y = d.splits > 1 ? workspace : p.Y;
     a.M = p.M; a.N = p.N; a.K = p.K; a.r = p.r;
-    a.y_f32 = p.f32out ? 1 : 0;
+    a.y_f32 = (p.f32out || d.splits > 1) ? 1 : 0;
     a.row_bytes = p.K / 8 * p.bits;
-    a.nt = (p.N + 16 * R * wn - 1) / (16 * R * wn);
-    a.mt = mt;
+    a.nt = d.nt;
+    a.mt = d.mt;
     a.ntiles_k = (p.K + 127) / 128;
+    a.tiles_per_split = d.tiles_per_split;
     const int total = a.nt * a.mt;
-    const int grid = ((total + 7) / 8) * 8;
+    const dim3 grid(((total + 7) / 8) * 8, d.splits);
+    hipError_t e = hipErrorInvalidValue;
 #define LORDS_PCASE(B_, S_)                                                                     \
     if (p.bits == B_ && ss == S_) {                                                              \
-        if (S_ == 1 && wm == 2) return R == 4 ? launch_pf_t<B_, 1, 2, 4>(a, grid, st) : launch_pf_t<B_, 1, 2, 2>(a, grid, st); \
-        if (S_ > 1 && wn == 8) return launch_pf_t<B_, S_ == 1 ? 2 : S_, 1, 2, 8>(a, grid, st);    \
-        return launch_pf_t<B_, S_, 1, 2>(a, grid, st);                                           \
+        if (S_ == 1 && wm == 2) e = R == 4 ? launch_pf_t<B_, 1, 2, 4>(a, grid, st) : launch_pf_t<B_, 1, 2, 2>(a, grid, st); \
+        else if (S_ > 1 && wn == 8) e = launch_pf_t<B_, S_ == 1 ? 2 : S_, 1, 2, 8>(a, grid, st); \
+        else e = launch_pf_t<B_, S_, 1, 2>(a, grid, st);                                         \
     }
     LORDS_PCASE(2, 1) LORDS_PCASE(2, 2) LORDS_PCASE(2, 4)
     LORDS_PCASE(3, 1) LORDS_PCASE(3, 2) LORDS_PCASE(3, 4)
     LORDS_PCASE(4, 1) LORDS_PCASE(4, 2) LORDS_PCASE(4, 4)
 #undef LORDS_PCASE
-    return hipErrorInvalidValue;
+    if (e != hipSuccess || d.splits == 1) return e;
+    const long count = (long)p.M * p.N;
+    const unsigned blocks = (unsigned)(((count + 3) / 4 + 255) / 256);
+    if (p.f32out) hipLaunchKernelGGL(reduce_split_kernel<true>, dim3(blocks), dim3(256), 0, st, (const float *)workspace, p.Y, count, d.splits);
+    else hipLaunchKernelGGL(reduce_split_kernel<false>, dim3(blocks), dim3(256), 0, st, (const float *)workspace, p.Y, count, d.splits);
+    return hipGetLastError();
 }
 
 }  // namespace lords

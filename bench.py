@@ -323,7 +323,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", choices=["decode", "prefill", "all"], default="all")
+    ap.add_argument("--workload", choices=["decode", "prefill", "shared_input", "backward", "all"], default="all",
+                    help="decode / prefill: the headline workloads; shared_input, backward: context figures only "
+                         "(profiling runs); all: everything")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -358,6 +360,10 @@ def main():
             line["prefill"] = p
     if args.workload == "all" and not args.calibrate_copy:
         line["other_workloads"] = bench_other(args, L, li, torch)
+    if args.workload == "shared_input":
+        line["other_workloads"] = bench_shared_input(args, L, li, torch)
+    if args.workload == "backward":
+        line["other_workloads"] = bench_backward(args, L, li, torch)
     if args.calibrate_copy:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

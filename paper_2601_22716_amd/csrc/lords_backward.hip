@@ -12,8 +12,9 @@
 // in the places of (codes, B, A).  Only the small factor transposes are done per call.
 //
 // dB, dA.  factor_grad_kernel: a workgroup of eight waves owns a 256-row x 128-column tile of G.
-// It walks M in chunks of 64 tokens; the dY tile (64 x 256) and the X tile (64 x 128) go from
-// global memory straight into LDS (global_load_lds_dwordx4), double-buffered, 16-byte chunks
+// It walks M in chunks of 32 tokens; the dY tile (32 x 256) and the X tile (32 x 128) go from
+// global memory straight into LDS (global_load_lds_dwordx4), four buffers with three chunks in
+// flight (a chunk is used about a microsecond after it was requested), 16-byte chunks
 // XOR-swizzled by the row number (slot = chunk ^ 2(row & 7)).  Both are row-major along the token axis, which is the
 // contraction axis here, so both MFMA operands come out of LDS through the transposing read
 // (ds_read_b64_tr_b16).  Wave w owns rows 32w .. 32w+31 and all 128 columns: accumulator block
@@ -131,9 +132,11 @@ struct FgArgs {
 };
 
 constexpr int kFgThreads = 512;
-constexpr int kFgBN = 256, kFgBK = 128, kFgMC = 64;
+constexpr int kFgBN = 256, kFgBK = 128, kFgMC = 32;
+constexpr int kFgNB = 4;                                                  // staging buffers: three chunks in flight
 constexpr int kFgDYB = kFgMC * kFgBN * 2, kFgXB = kFgMC * kFgBK * 2;     // bytes of one dY / X tile
-constexpr int kFgStage = 2 * (kFgDYB + kFgXB);
+constexpr int kFgStage = kFgNB * (kFgDYB + kFgXB);
+constexpr int kFgLoads = 3;                                               // direct-to-LDS loads per wave and chunk
 constexpr int kFgAST = 264;                                               // bytes per row of the A tile (128 columns + pad)
 
 __device__ __forceinline__ void fg_lds_direct_16(const void *gsrc, void *lds_wave_base)
@@ -181,29 +184,28 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     const int nt = blockIdx.x / a.ktiles, kt = blockIdx.x % a.ktiles;
     const int n0 = nt * kFgBN, k0 = kt * kFgBK;
 
-    // ---- staging of one chunk of 64 tokens into buffer p -------------------------------------------
+    // ---- staging of one chunk of 32 tokens into buffer p: always kFgLoads loads per wave, so that the
+    //      loop can wait for "all but the loads of the chunks behind this one" -----------------------------
     auto stage = [&](int ch, int p) {
         unsigned char *dYs = smem + p * (kFgDYB + kFgXB), *Xs = dYs + kFgDYB;
-#pragma nounroll
-        for (int q = 0; q < 4; ++q) {                        // dY: a wave-level load covers two rows of 512 bytes
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {                        // dY: a wave-level load covers two rows of 512 bytes
             const int row = 16 * q + 2 * wave + (lane >> 5), slot = lane & 31;
             const int n = min(n0 + 8 * (slot ^ ((row & 7) << 1)), N - 8);       // (columns >= N: finite filler, masked later)
-            const int m = ch * kFgMC + row;
-            unsigned char *dst = dYs + (16 * q + 2 * wave) * 512;
-            if (m < M) fg_lds_direct_16(a.dY + (size_t)m * N + n, dst);
-            else *reinterpret_cast<u32x4 *>(dst + 16 * lane) = u32x4{0u, 0u, 0u, 0u};   // tokens >= M add nothing
+            const int m = min(ch * kFgMC + row, M - 1);      // (tokens >= M: a copy of the last token; its X row is zeroed before use)
+            fg_lds_direct_16(a.dY + (size_t)m * N + n, dYs + (16 * q + 2 * wave) * 512);
         }
-#pragma nounroll
-        for (int q = 0; q < 2; ++q) {                        // X: four rows of 256 bytes
-            const int row = 32 * q + 4 * wave + (lane >> 4), slot = lane & 15;
+        {                                                    // X: four rows of 256 bytes
+            const int row = 4 * wave + (lane >> 4), slot = lane & 15;
             const int k = min(k0 + 8 * (slot ^ ((row & 7) << 1)), K - 8);
-            const int m = ch * kFgMC + row;
-            unsigned char *dst = Xs + (32 * q + 4 * wave) * 256;
-            if (m < M) fg_lds_direct_16(a.X + (size_t)m * K + k, dst);
-            else *reinterpret_cast<u32x4 *>(dst + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
+            const int m = min(ch * kFgMC + row, M - 1);
+            fg_lds_direct_16(a.X + (size_t)m * K + k, Xs + (4 * wave) * 256);
         }
     };
-    stage(0, 0);
+    const int nchunks = (M + kFgMC - 1) / kFgMC;
+#pragma unroll
+    for (int d = 0; d < kFgNB - 1; ++d)
+        if (d < nchunks) stage(d, d);
 
     // ---- A tile (rank x 128 columns), B tile (256 rows x rank), level table: once per workgroup ------
     typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
@@ -267,35 +269,38 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) acc[kb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int nchunks = (M + kFgMC - 1) / kFgMC;
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+    __syncthreads();                                       // A and B tiles, level table
     for (int ch = 0; ch < nchunks; ++ch) {
-        const int p = ch & 1;
-        if (ch + 1 < nchunks) stage(ch + 1, p ^ 1);
-        const unsigned char *dYs = smem + p * (kFgDYB + kFgXB), *Xs = dYs + kFgDYB;
-        // all operand reads of the chunk are issued before the first MFMA: the LDS round trip is paid once
-        bf16x8 Yop[2][2], Xop[2][8];
-#pragma unroll
-        for (int ms = 0; ms < 2; ++ms) {
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) Yop[ms][nb] = fg_tr_read<512>(dYs, 32 * ms + 8 * g, 32 * wave + 16 * nb, c);
-#pragma unroll
-            for (int kb = 0; kb < 8; ++kb) Xop[ms][kb] = fg_tr_read<256>(Xs, 32 * ms + 8 * g, 16 * kb, c);
+        const int p = ch & (kFgNB - 1);
+        // chunk ch has landed once at most the loads of the chunks requested after it are outstanding
+        const int behind = min(kFgNB - 2, nchunks - 1 - ch);
+        if (behind >= 2) __builtin_amdgcn_s_waitcnt(0x0070 | (2 * kFgLoads));
+        else if (behind == 1) __builtin_amdgcn_s_waitcnt(0x0070 | kFgLoads);
+        else __builtin_amdgcn_s_waitcnt(0x0070);
+        __builtin_amdgcn_s_barrier();                      // ... for every wave; and every wave has left chunk ch-1
+        asm volatile("" ::: "memory");
+        unsigned char *dYs = smem + p * (kFgDYB + kFgXB), *Xs = dYs + kFgDYB;
+        if ((ch + 1) * kFgMC > M) {
+            // ragged last chunk: tokens >= M must add nothing: their X rows become zero
+            const int row = tid >> 4;
+            if (ch * kFgMC + row >= M) *reinterpret_cast<u32x4 *>(Xs + row * 256 + 16 * (tid & 15)) = u32x4{0u, 0u, 0u, 0u};
+            __syncthreads();
         }
+        if (ch + kFgNB - 1 < nchunks) stage(ch + kFgNB - 1, (ch + kFgNB - 1) & (kFgNB - 1));   // into the buffer of chunk ch-1
+        bf16x8 Yop[2], Xop[8];
 #pragma unroll
-        for (int ms = 0; ms < 2; ++ms)
+        for (int nb = 0; nb < 2; ++nb) Yop[nb] = fg_tr_read<512>(dYs, 8 * g, 32 * wave + 16 * nb, c);
 #pragma unroll
-            for (int kb = 0; kb < 8; ++kb)
+        for (int kb = 0; kb < 8; ++kb) Xop[kb] = fg_tr_read<256>(Xs, 8 * g, 16 * kb, c);
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    acc[kb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Xop[ms][kb], Yop[ms][nb], acc[kb][nb], 0, 0, 0);
-        __builtin_amdgcn_s_waitcnt(0);          // the next chunk has landed
-        __syncthreads();
+        for (int kb = 0; kb < 8; ++kb)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+                acc[kb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Xop[kb], Yop[nb], acc[kb][nb], 0, 0, 0);
     }
+    __syncthreads();                                       // every wave has left the last chunk: the buffers are free
 
     // ---- P = level (.) G; dB = P A^T straight from the registers; P to LDS for dA ----------------------
-    // (the staging buffers are free: every wave has passed the barrier that ended the last chunk)
     unsigned char *Ps = smem;                                 // [256][256 bytes], chunk-swizzled like the X tile
     f32x4 dBacc[2][JB];
 #pragma unroll

@@ -202,6 +202,19 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
             fg_lds_direct_16(a.X + (size_t)m * K + k, Xs + (4 * wave) * 256);
         }
     };
+    // ---- the packed codes of the tile (256 rows x 4*BITS dwords), requested now with coalesced loads and
+    //      parked in registers over the token loop; they go to LDS once the staging buffers are free ----
+    constexpr int CW = 4 * BITS, CST = CW + 1;                // dwords of a row's 128 codes; padded LDS row
+    const int row_dwords = a.row_bytes >> 2;
+    uint32_t ctile[2 * BITS];
+#pragma unroll
+    for (int q = 0; q < 2 * BITS; ++q) {
+        const int id = tid + kFgThreads * q, row = id / CW, dd = id % CW;
+        const int gd = (k0 >> 5) * BITS + dd;
+        ctile[q] = 0;
+        if (n0 + row < N && gd < row_dwords)
+            ctile[q] = reinterpret_cast<const uint32_t *>(a.codes + (size_t)(n0 + row) * a.row_bytes)[gd];
+    }
     const int nchunks = (M + kFgMC - 1) / kFgMC;
 #pragma unroll
     for (int d = 0; d < kFgNB - 1; ++d)
@@ -307,25 +320,46 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) dBacc[nb][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int row_dwords = a.row_bytes >> 2;
+    uint32_t *ct = reinterpret_cast<uint32_t *>(smem + 65536);       // [256][CST], behind the P tile
+#pragma unroll
+    for (int q = 0; q < 2 * BITS; ++q) {
+        const int id = tid + kFgThreads * q;
+        ct[(id / CW) * CST + id % CW] = ctile[q];
+    }
+    __syncthreads();
+    // Three passes over the lane's 16 blocks, each pass issuing all of its LDS reads before any is used:
+    // code words, then levels, then the arithmetic (one pass with everything in program order pays two
+    // LDS round trips per block).
+    typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4v;
+    uint32_t cv[2][8];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-        const int nl = 32 * wave + 16 * nb + c, n = n0 + nl;  // the row whose four values this lane holds
-        const uint32_t *row32 = reinterpret_cast<const uint32_t *>(a.codes + (size_t)min(n, N - 1) * a.row_bytes);
+        const int nl = 32 * wave + 16 * nb + c;               // the row whose four values this lane holds
+#pragma unroll
+        for (int kb = 0; kb < 8; ++kb) {
+            const int off = BITS * (16 * kb + 4 * g), d = off >> 5, sh = off & 31;   // within the row's 128 codes of this tile
+            const uint64_t w = (uint64_t)ct[nl * CST + d] | ((uint64_t)ct[nl * CST + min(d + 1, CW - 1)] << 32);
+            cv[nb][kb] = (uint32_t)(w >> sh);
+        }
+    }
+    float lv[2][8][4];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int kb = 0; kb < 8; ++kb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) lv[nb][kb][e] = cb[(cv[nb][kb] >> (BITS * e)) & ((1u << BITS) - 1u)];
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int nl = 32 * wave + 16 * nb + c, n = n0 + nl;
 #pragma unroll
         for (int kb = 0; kb < 8; ++kb) {
             const int kl = 16 * kb + 4 * g, kk = k0 + kl;     // its four columns kk .. kk+3
-            const int kc = min(kk, K - 4);
-            const int off = BITS * kc, d = off >> 5, sh = off & 31;
-            const uint64_t w = (uint64_t)row32[d] | ((uint64_t)row32[min(d + 1, row_dwords - 1)] << 32);
-            const uint32_t v = (uint32_t)(w >> sh);
             const bool ok = n < N && kk < K;
-            typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4v;
             s16x4v pb;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float lvl = cb[(v >> (BITS * e)) & ((1u << BITS) - 1u)];
-                const float pv = ok ? lvl * acc[kb][nb][e] : 0.f;
+                const float pv = ok ? lv[nb][kb][e] * acc[kb][nb][e] : 0.f;
                 pb[e] = (short)bf16_bits(pv);
             }
             // dB[n][j] += sum over these four columns of P[n][k] A[j][k]

@@ -11,14 +11,14 @@
 // transposed layer: W_hat^T = C[Q^T] (.) (A^T B^T), i.e. the ordinary kernels with (codes^T, A^T, B^T)
 // in the places of (codes, B, A).  Only the small factor transposes are done per call.
 //
-// dB, dA.  factor_grad_kernel: a workgroup of eight waves owns a 256-row x 128-column tile of G.
-// It walks M in chunks of 32 tokens; the dY tile (32 x 256) and the X tile (32 x 128) go from
-// global memory straight into LDS (global_load_lds_dwordx4), four buffers with three chunks in
-// flight (a chunk is used about a microsecond after it was requested), 16-byte chunks
-// XOR-swizzled by the row number (slot = chunk ^ 2(row & 7)).  Both are row-major along the token axis, which is the
+// dB, dA.  factor_grad_kernel: a workgroup of eight waves owns a 256-row x 256-column tile of G.
+// It walks M in chunks of 32 tokens; the dY tile (32 x 256) and the X tile (32 x 256) go from
+// global memory straight into LDS (global_load_lds_dwordx4), three buffers with two chunks in
+// flight (two buffers for ranks above 32), 16-byte chunks XOR-swizzled by the row number
+// (slot = chunk ^ 2(row & 7)).  Both are row-major along the token axis, which is the
 // contraction axis here, so both MFMA operands come out of LDS through the transposing read
-// (ds_read_b64_tr_b16).  Wave w owns rows 32w .. 32w+31 and all 128 columns: accumulator block
-// (kb, nb) holds G[k = 16kb + 4g + e][n = 32w + 16nb + c] in lane (c, g), element e -- four
+// (ds_read_b64_tr_b16).  Wave (wn, wk) owns rows 64wn .. 64wn+63 and columns 128wk .. 128wk+127:
+// accumulator block (kb, nb) holds G[k = 128wk + 16kb + 4g + e][n = 64wn + 16nb + c] in lane (c, g), element e -- four
 // consecutive columns of one row, which is (i) how the packed codes of that row are laid out, and
 // (ii) after the multiplication by the level, exactly the a-operand layout of
 // v_mfma_f32_16x16x16_bf16 for the contraction over k: dB needs no data movement at all.
@@ -123,7 +123,7 @@ struct FgArgs {
     const float *codebook;
     const void *B;         // N x r
     const void *A;         // r x K
-    float *partB;          // [ktiles][N][r]
+    float *partB;          // [2*ktiles][N][r]: one part per half tile (128 columns)
     float *partA;          // [ntiles][r][K]
     int M, N, K, r;
     int f32fact;
@@ -132,12 +132,10 @@ struct FgArgs {
 };
 
 constexpr int kFgThreads = 512;
-constexpr int kFgBN = 256, kFgBK = 128, kFgMC = 32;
-constexpr int kFgNB = 4;                                                  // staging buffers: three chunks in flight
-constexpr int kFgDYB = kFgMC * kFgBN * 2, kFgXB = kFgMC * kFgBK * 2;     // bytes of one dY / X tile
-constexpr int kFgStage = kFgNB * (kFgDYB + kFgXB);
-constexpr int kFgLoads = 3;                                               // direct-to-LDS loads per wave and chunk
-constexpr int kFgAST = 264;                                               // bytes per row of the A tile (128 columns + pad)
+constexpr int kFgBN = 256, kFgBK = 256, kFgMC = 32;
+constexpr int kFgTile = kFgMC * 512;                                      // bytes of one dY or X tile (32 tokens x 256 columns)
+constexpr int kFgLoads = 4;                                               // direct-to-LDS loads per wave and chunk
+constexpr int kFgAST = 520;                                               // bytes per row of the A tile (256 columns + pad)
 
 __device__ __forceinline__ void fg_lds_direct_16(const void *gsrc, void *lds_wave_base)
 {
@@ -173,43 +171,46 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 {
     constexpr int RP = 32 * SS, JB = 2 * SS;                  // padded rank, 16-entry rank blocks
     constexpr int BST = (RP + 4) * 2;                         // bytes per row of the B tile
+    constexpr int NB = SS == 1 ? 3 : 2;                       // staging buffers (what LDS leaves room for)
+    constexpr int STAGE = NB * 2 * kFgTile;
+    constexpr int CW = 4 * BITS, CST = CW + 1;                // dwords of 128 codes of a row; padded LDS row
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *As = smem + kFgStage;                      // [RP][kFgAST]  bf16
+    unsigned char *As = smem + STAGE;                         // [RP][kFgAST]  bf16
     unsigned char *Bs = As + RP * kFgAST;                     // [256][BST]    bf16
     float *cb = reinterpret_cast<float *>(Bs + kFgBN * BST);  // [2^BITS]
+    // codes of one half of the tile (256 rows x 128 columns): behind the P tile where the staging
+    // region is large enough, else in a region of its own
+    uint32_t *ct = SS == 1 ? reinterpret_cast<uint32_t *>(smem + 65536) : reinterpret_cast<uint32_t *>(cb + (1 << BITS));
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
+    const int wn = wave & 3, wk = wave >> 2;                  // this wave's 64 rows and 128 columns of the tile
     const int M = a.M, N = a.N, K = a.K, r = a.r;
     const int nt = blockIdx.x / a.ktiles, kt = blockIdx.x % a.ktiles;
     const int n0 = nt * kFgBN, k0 = kt * kFgBK;
 
     // ---- staging of one chunk of 32 tokens into buffer p: always kFgLoads loads per wave, so that the
-    //      loop can wait for "all but the loads of the chunks behind this one" -----------------------------
+    //      loop can wait for "all but the loads of the chunk behind this one" ------------------------------
     auto stage = [&](int ch, int p) {
-        unsigned char *dYs = smem + p * (kFgDYB + kFgXB), *Xs = dYs + kFgDYB;
+        unsigned char *dYs = smem + p * (2 * kFgTile), *Xs = dYs + kFgTile;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {                        // dY: a wave-level load covers two rows of 512 bytes
+        for (int q = 0; q < 2; ++q) {                        // a wave-level load covers two rows of 512 bytes
             const int row = 16 * q + 2 * wave + (lane >> 5), slot = lane & 31;
-            const int n = min(n0 + 8 * (slot ^ ((row & 7) << 1)), N - 8);       // (columns >= N: finite filler, masked later)
+            const int ch16 = slot ^ ((row & 7) << 1);                            // the 16-byte chunk that sits in this slot
+            const int n = min(n0 + 8 * ch16, N - 8);         // (columns >= N or K: finite filler, masked later)
+            const int k = min(k0 + 8 * ch16, K - 8);
             const int m = min(ch * kFgMC + row, M - 1);      // (tokens >= M: a copy of the last token; its X row is zeroed before use)
             fg_lds_direct_16(a.dY + (size_t)m * N + n, dYs + (16 * q + 2 * wave) * 512);
-        }
-        {                                                    // X: four rows of 256 bytes
-            const int row = 4 * wave + (lane >> 4), slot = lane & 15;
-            const int k = min(k0 + 8 * (slot ^ ((row & 7) << 1)), K - 8);
-            const int m = min(ch * kFgMC + row, M - 1);
-            fg_lds_direct_16(a.X + (size_t)m * K + k, Xs + (4 * wave) * 256);
+            fg_lds_direct_16(a.X + (size_t)m * K + k, Xs + (16 * q + 2 * wave) * 512);
         }
     };
-    // ---- the packed codes of the tile (256 rows x 4*BITS dwords), requested now with coalesced loads and
-    //      parked in registers over the token loop; they go to LDS once the staging buffers are free ----
-    constexpr int CW = 4 * BITS, CST = CW + 1;                // dwords of a row's 128 codes; padded LDS row
+    // ---- the packed codes of the tile (256 rows x 8*BITS dwords), requested now with coalesced loads and
+    //      parked in registers over the token loop; they go to LDS, half a tile at a time, afterwards ------
     const int row_dwords = a.row_bytes >> 2;
-    uint32_t ctile[2 * BITS];
+    uint32_t ctile[4 * BITS];
 #pragma unroll
-    for (int q = 0; q < 2 * BITS; ++q) {
-        const int id = tid + kFgThreads * q, row = id / CW, dd = id % CW;
+    for (int q = 0; q < 4 * BITS; ++q) {
+        const int id = tid + kFgThreads * q, row = id / (2 * CW), dd = id % (2 * CW);
         const int gd = (k0 >> 5) * BITS + dd;
         ctile[q] = 0;
         if (n0 + row < N && gd < row_dwords)
@@ -217,18 +218,18 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
     const int nchunks = (M + kFgMC - 1) / kFgMC;
 #pragma unroll
-    for (int d = 0; d < kFgNB - 1; ++d)
+    for (int d = 0; d < NB - 1; ++d)
         if (d < nchunks) stage(d, d);
 
-    // ---- A tile (rank x 128 columns), B tile (256 rows x rank), level table: once per workgroup ------
+    // ---- A tile (rank x 256 columns), B tile (256 rows x rank), level table: once per workgroup ------
     typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
     if (!a.f32fact && (r & 7) == 0) {
         // 16-byte pieces, all loads of a thread in flight together (rows of the LDS tiles are only
         // 8-byte aligned: two stores per piece)
-        u32x4 va[RP * 16 / kFgThreads], vb[kFgBN * (RP / 8) / kFgThreads];
+        u32x4 va[RP * 32 / kFgThreads], vb[kFgBN * (RP / 8) / kFgThreads];
 #pragma unroll
-        for (int q = 0; q < RP * 16 / kFgThreads; ++q) {
-            const int id = tid + kFgThreads * q, j = id >> 4, kk = 8 * (id & 15);
+        for (int q = 0; q < RP * 32 / kFgThreads; ++q) {
+            const int id = tid + kFgThreads * q, j = id >> 5, kk = 8 * (id & 31);
             va[q] = u32x4{0u, 0u, 0u, 0u};
             if (j < r && k0 + kk < K) va[q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.A) + (size_t)j * K + k0 + kk);
         }
@@ -239,8 +240,8 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
             if (j < r && n0 + nn < N) vb[q] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint16_t *>(a.B) + (size_t)(n0 + nn) * r + j);
         }
 #pragma unroll
-        for (int q = 0; q < RP * 16 / kFgThreads; ++q) {
-            const int id = tid + kFgThreads * q, j = id >> 4, kk = 8 * (id & 15);
+        for (int q = 0; q < RP * 32 / kFgThreads; ++q) {
+            const int id = tid + kFgThreads * q, j = id >> 5, kk = 8 * (id & 31);
             u32x2 *dst = reinterpret_cast<u32x2 *>(As + j * kFgAST + kk * 2);
             dst[0] = u32x2{va[q][0], va[q][1]};
             dst[1] = u32x2{va[q][2], va[q][3]};
@@ -276,140 +277,137 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     if (tid < (1 << BITS)) cb[tid] = a.codebook[tid];
 
     // ---- G = dY^T X over the tokens -----------------------------------------------------------------
-    f32x4 acc[8][2];
+    f32x4 acc[8][4];
 #pragma unroll
     for (int kb = 0; kb < 8; ++kb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) acc[kb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int nb = 0; nb < 4; ++nb) acc[kb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     __syncthreads();                                       // A and B tiles, level table
+    int p = 0;                                             // buffer of chunk ch
     for (int ch = 0; ch < nchunks; ++ch) {
-        const int p = ch & (kFgNB - 1);
-        // chunk ch has landed once at most the loads of the chunks requested after it are outstanding
-        const int behind = min(kFgNB - 2, nchunks - 1 - ch);
-        if (behind >= 2) __builtin_amdgcn_s_waitcnt(0x0070 | (2 * kFgLoads));
-        else if (behind == 1) __builtin_amdgcn_s_waitcnt(0x0070 | kFgLoads);
+        // chunk ch has landed once at most the loads of the chunk requested after it are outstanding
+        if (NB == 3 && ch + 1 < nchunks) __builtin_amdgcn_s_waitcnt(0x0070 | kFgLoads);
         else __builtin_amdgcn_s_waitcnt(0x0070);
         __builtin_amdgcn_s_barrier();                      // ... for every wave; and every wave has left chunk ch-1
         asm volatile("" ::: "memory");
-        unsigned char *dYs = smem + p * (kFgDYB + kFgXB), *Xs = dYs + kFgDYB;
+        unsigned char *dYs = smem + p * (2 * kFgTile), *Xs = dYs + kFgTile;
         if ((ch + 1) * kFgMC > M) {
             // ragged last chunk: tokens >= M must add nothing: their X rows become zero
-            const int row = tid >> 4;
-            if (ch * kFgMC + row >= M) *reinterpret_cast<u32x4 *>(Xs + row * 256 + 16 * (tid & 15)) = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int id = tid + kFgThreads * q, row = id >> 5;
+                if (ch * kFgMC + row >= M) *reinterpret_cast<u32x4 *>(Xs + row * 512 + 16 * (id & 31)) = u32x4{0u, 0u, 0u, 0u};
+            }
             __syncthreads();
         }
-        if (ch + kFgNB - 1 < nchunks) stage(ch + kFgNB - 1, (ch + kFgNB - 1) & (kFgNB - 1));   // into the buffer of chunk ch-1
-        bf16x8 Yop[2], Xop[8];
+        const int pprev = p == 0 ? NB - 1 : p - 1;         // the buffer of chunk ch-1, free now
+        if (ch + NB - 1 < nchunks) stage(ch + NB - 1, pprev);
+        bf16x8 Yop[4], Xop[8];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) Yop[nb] = fg_tr_read<512>(dYs, 8 * g, 32 * wave + 16 * nb, c);
+        for (int nb = 0; nb < 4; ++nb) Yop[nb] = fg_tr_read<512>(dYs, 8 * g, 64 * wn + 16 * nb, c);
 #pragma unroll
-        for (int kb = 0; kb < 8; ++kb) Xop[kb] = fg_tr_read<256>(Xs, 8 * g, 16 * kb, c);
+        for (int kb = 0; kb < 8; ++kb) Xop[kb] = fg_tr_read<512>(Xs, 8 * g, 128 * wk + 16 * kb, c);
 #pragma unroll
         for (int kb = 0; kb < 8; ++kb)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+            for (int nb = 0; nb < 4; ++nb)
                 acc[kb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Xop[kb], Yop[nb], acc[kb][nb], 0, 0, 0);
+        p = p + 1 == NB ? 0 : p + 1;
     }
     __syncthreads();                                       // every wave has left the last chunk: the buffers are free
 
-    // ---- P = level (.) G; dB = P A^T straight from the registers; P to LDS for dA ----------------------
-    unsigned char *Ps = smem;                                 // [256][256 bytes], chunk-swizzled like the X tile
-    f32x4 dBacc[2][JB];
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb) dBacc[nb][jb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    uint32_t *ct = reinterpret_cast<uint32_t *>(smem + 65536);       // [256][CST], behind the P tile
-#pragma unroll
-    for (int q = 0; q < 2 * BITS; ++q) {
-        const int id = tid + kFgThreads * q;
-        ct[(id / CW) * CST + id % CW] = ctile[q];
-    }
-    __syncthreads();
-    // Three passes over the lane's 16 blocks, each pass issuing all of its LDS reads before any is used:
-    // code words, then levels, then the arithmetic (one pass with everything in program order pays two
-    // LDS round trips per block).
+    // ---- per half of the tile's columns (h = 0: the waves with wk = 0 hold it, then h = 1):
+    //      P = level (.) G; dB = P A^T straight from the registers; P to LDS; dA = B^T P from there ------
+    unsigned char *Ps = smem;                                 // [256][256 bytes], chunk-swizzled
     typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4v;
-    uint32_t cv[2][8];
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const int nl = 32 * wave + 16 * nb + c;               // the row whose four values this lane holds
+    for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int kb = 0; kb < 8; ++kb) {
-            const int off = BITS * (16 * kb + 4 * g), d = off >> 5, sh = off & 31;   // within the row's 128 codes of this tile
-            const uint64_t w = (uint64_t)ct[nl * CST + d] | ((uint64_t)ct[nl * CST + min(d + 1, CW - 1)] << 32);
-            cv[nb][kb] = (uint32_t)(w >> sh);
+        for (int q = 0; q < 4 * BITS; ++q) {
+            const int id = tid + kFgThreads * q, row = id / (2 * CW), dd = id % (2 * CW);
+            if (dd / CW == h) ct[row * CST + dd % CW] = ctile[q];
         }
-    }
-    float lv[2][8][4];
+        __syncthreads();
+        if (wk == h) {
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+            for (int nb = 0; nb < 4; ++nb) {
+                const int nl = 64 * wn + 16 * nb + c, n = n0 + nl;    // the row whose four values this lane holds
+                // all LDS reads of a pass are issued before any is used: code words, then levels
+                uint32_t cv[8];
 #pragma unroll
-        for (int kb = 0; kb < 8; ++kb)
+                for (int kb = 0; kb < 8; ++kb) {
+                    const int off = BITS * (16 * kb + 4 * g), d = off >> 5, sh = off & 31;   // within the row's 128 codes of this half
+                    const uint64_t w = (uint64_t)ct[nl * CST + d] | ((uint64_t)ct[nl * CST + min(d + 1, CW - 1)] << 32);
+                    cv[kb] = (uint32_t)(w >> sh);
+                }
+                float lv[8][4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) lv[nb][kb][e] = cb[(cv[nb][kb] >> (BITS * e)) & ((1u << BITS) - 1u)];
+                for (int kb = 0; kb < 8; ++kb)
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-        const int nl = 32 * wave + 16 * nb + c, n = n0 + nl;
+                    for (int e = 0; e < 4; ++e) lv[kb][e] = cb[(cv[kb] >> (BITS * e)) & ((1u << BITS) - 1u)];
+                f32x4 dBacc[JB];
 #pragma unroll
-        for (int kb = 0; kb < 8; ++kb) {
-            const int kl = 16 * kb + 4 * g, kk = k0 + kl;     // its four columns kk .. kk+3
-            const bool ok = n < N && kk < K;
-            s16x4v pb;
+                for (int jb = 0; jb < JB; ++jb) dBacc[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float pv = ok ? lv[nb][kb][e] * acc[kb][nb][e] : 0.f;
-                pb[e] = (short)bf16_bits(pv);
+                for (int kb = 0; kb < 8; ++kb) {
+                    const int kl = 16 * kb + 4 * g, kk = k0 + 128 * h + kl;      // its four columns kk .. kk+3
+                    const bool ok = n < N && kk < K;
+                    s16x4v pb;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float pv = ok ? lv[kb][e] * acc[kb][nb][e] : 0.f;
+                        pb[e] = (short)bf16_bits(pv);
+                    }
+                    // dB[n][j] += sum over these four columns of P[n][k] A[j][k]
+#pragma unroll
+                    for (int jb = 0; jb < JB; ++jb) {
+                        const s16x4v aop = *reinterpret_cast<const s16x4v *>(As + (16 * jb + c) * kFgAST + (128 * h + kl) * 2);
+                        dBacc[jb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, aop, dBacc[jb], 0, 0, 0);
+                    }
+                    *reinterpret_cast<s16x4v *>(Ps + nl * 256 + (((kl >> 3) ^ ((nl & 7) << 1)) << 4) + ((kl & 7) << 1)) = pb;
+                }
+                // dB partial of this half tile: lane (c, g) holds rows 4g+e of rank entry 16 jb + c
+#pragma unroll
+                for (int jb = 0; jb < JB; ++jb) {
+                    const int j = 16 * jb + c;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int nn = n0 + 64 * wn + 16 * nb + 4 * g + e;
+                        if (nn < N && j < r) a.partB[((size_t)(2 * kt + h) * N + nn) * r + j] = dBacc[jb][e];
+                    }
+                }
             }
-            // dB[n][j] += sum over these four columns of P[n][k] A[j][k]
+        }
+        __syncthreads();
+
+        // dA = B^T P over the 256 rows: wave w takes columns 16w .. 16w+15 of the half, all rank blocks
+        f32x4 dAacc[JB];
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) dAacc[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ns = 0; ns < 8; ++ns) {
+            const bf16x8 Pop = fg_tr_read<256>(Ps, 32 * ns + 8 * g, 16 * wave, c);
 #pragma unroll
             for (int jb = 0; jb < JB; ++jb) {
-                const s16x4v aop = *reinterpret_cast<const s16x4v *>(As + (16 * jb + c) * kFgAST + kl * 2);
-                dBacc[nb][jb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, aop, dBacc[nb][jb], 0, 0, 0);
+                typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
+                const int ra = 32 * ns + 8 * g + (c >> 2), col = 16 * jb + 4 * (c & 3);
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(Bs + ra * BST + col * 2));
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(Bs + (ra + 4) * BST + col * 2));
+                const bf16x8 Bop = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                dAacc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Bop, Pop, dAacc[jb], 0, 0, 0);
             }
-            *reinterpret_cast<s16x4v *>(Ps + nl * 256 + (((kl >> 3) ^ ((nl & 7) << 1)) << 4) + ((kl & 7) << 1)) = pb;
         }
-    }
-    // dB partial of this column tile: lane (c, g) holds rows 4g+e of rank entry 16 jb + c
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) {
-            const int j = 16 * jb + c;
+            const int k = k0 + 128 * h + 16 * wave + c;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int n = n0 + 32 * wave + 16 * nb + 4 * g + e;
-                if (n < N && j < r) a.partB[((size_t)kt * N + n) * r + j] = dBacc[nb][jb][e];
+                const int j = 16 * jb + 4 * g + e;
+                if (j < r && k < K) a.partA[((size_t)nt * r + j) * K + k] = dAacc[jb][e];
             }
         }
-    __syncthreads();
-
-    // ---- dA = B^T P over the 256 rows: wave w takes columns 16w .. 16w+15, all rank blocks ------------
-    f32x4 dAacc[JB];
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb) dAacc[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ns = 0; ns < 8; ++ns) {
-        const bf16x8 Pop = fg_tr_read<256>(Ps, 32 * ns + 8 * g, 16 * wave, c);
-#pragma unroll
-        for (int jb = 0; jb < JB; ++jb) {
-            typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
-            const int ra = 32 * ns + 8 * g + (c >> 2), col = 16 * jb + 4 * (c & 3);
-            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(Bs + ra * BST + col * 2));
-            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(Bs + (ra + 4) * BST + col * 2));
-            const bf16x8 Bop = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            dAacc[jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Bop, Pop, dAacc[jb], 0, 0, 0);
-        }
-    }
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb) {
-        const int k = k0 + 16 * wave + c;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int j = 16 * jb + 4 * g + e;
-            if (j < r && k < K) a.partA[((size_t)nt * r + j) * K + k] = dAacc[jb][e];
-        }
+        if (h == 0) __syncthreads();                       // the P tile and the codes are rewritten by the other half
     }
 }
 
@@ -429,14 +427,15 @@ bool factor_grad_supported(int N, int K, int r) { return r >= 1 && r <= 64 && (N
 size_t factor_grad_workspace_bytes(int N, int K, int r)
 {
     const size_t ntiles = (N + kFgBN - 1) / kFgBN, ktiles = (K + kFgBK - 1) / kFgBK;
-    return (ktiles * (size_t)N * r + ntiles * (size_t)r * K) * sizeof(float);
+    return (2 * ktiles * (size_t)N * r + ntiles * (size_t)r * K) * sizeof(float);    // dB: one part per half tile of columns
 }
 
 template <int BITS, int SS>
 static hipError_t launch_fg_t(const FgArgs &a, hipStream_t st)
 {
     constexpr int RP = 32 * SS;
-    const size_t smem = (size_t)kFgStage + (size_t)RP * kFgAST + (size_t)kFgBN * (RP + 4) * 2 + (size_t)(1 << BITS) * 4;
+    const size_t smem = (size_t)(SS == 1 ? 3 : 2) * 2 * kFgTile + (size_t)RP * kFgAST + (size_t)kFgBN * (RP + 4) * 2 +
+                        (size_t)(1 << BITS) * 4 + (SS == 1 ? 0 : (size_t)kFgBN * (4 * BITS + 1) * 4);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&factor_grad_kernel<BITS, SS>),
@@ -465,7 +464,7 @@ hipError_t launch_factor_grad(const void *dY, const void *X, const void *codes, 
     a.ntiles = (N + kFgBN - 1) / kFgBN;
     a.ktiles = (K + kFgBK - 1) / kFgBK;
     a.partB = (float *)workspace;
-    a.partA = a.partB + (size_t)a.ktiles * N * r;
+    a.partA = a.partB + (size_t)2 * a.ktiles * N * r;
     const int ss = r <= 32 ? 1 : 2;
     hipError_t e = hipErrorInvalidValue;
 #define LORDS_FGCASE(B_, S_) if (bits == B_ && ss == S_) e = launch_fg_t<B_, S_>(a, st);
@@ -473,7 +472,7 @@ hipError_t launch_factor_grad(const void *dY, const void *X, const void *codes, 
 #undef LORDS_FGCASE
     if (e != hipSuccess) return e;
     const long cb = (long)N * r, ca = (long)r * K;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((cb + 255) / 256)), dim3(256), 0, st, a.partB, dB, cb, a.ktiles);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((cb + 255) / 256)), dim3(256), 0, st, a.partB, dB, cb, 2 * a.ktiles);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((ca + 255) / 256)), dim3(256), 0, st, a.partA, dA, ca, a.ntiles);
     return hipGetLastError();
 }

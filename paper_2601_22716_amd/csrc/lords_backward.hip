@@ -436,12 +436,10 @@ static hipError_t launch_fg_t(const FgArgs &a, hipStream_t st)
     constexpr int RP = 32 * SS;
     const size_t smem = (size_t)(SS == 1 ? 3 : 2) * 2 * kFgTile + (size_t)RP * kFgAST + (size_t)kFgBN * (RP + 4) * 2 +
                         (size_t)(1 << BITS) * 4 + (SS == 1 ? 0 : (size_t)kFgBN * (4 * BITS + 1) * 4);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&factor_grad_kernel<BITS, SS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsOptIn lds_opt_in;
+    {
+        const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&factor_grad_kernel<BITS, SS>), smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     hipLaunchKernelGGL((factor_grad_kernel<BITS, SS>), dim3(a.ntiles * a.ktiles), dim3(kFgThreads), smem, st, a);
     return hipGetLastError();

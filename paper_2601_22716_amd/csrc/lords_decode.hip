@@ -386,12 +386,10 @@ static hipError_t launch_decode_t(const DecodeArgs &a, dim3 grid, hipStream_t st
     constexpr size_t R0 = A_BYTES > LUT_BYTES ? (A_BYTES > RED_BYTES ? A_BYTES : RED_BYTES)
                                               : (LUT_BYTES > RED_BYTES ? LUT_BYTES : RED_BYTES);
     const size_t smem = R0 + 128;
-    static bool attr_set = false;
-    if (!attr_set && smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<BITS, SS, G, BVEC, M1>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsOptIn lds_opt_in;
+    if (smem > 48 * 1024) {
+        const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&decode_kernel<BITS, SS, G, BVEC, M1>), smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     hipLaunchKernelGGL((decode_kernel<BITS, SS, G, BVEC, M1>), grid, dim3(256), smem, st, a);
     return hipGetLastError();

@@ -478,12 +478,10 @@ static hipError_t launch_m1_t(const M1ArgsT<MULTI ? kM1MaxLayers : 1> &a, dim3 g
 {
     constexpr int KT = 128 * G, AST = (G == 1 ? 4 : 1) * KT + 8;
     const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)JT * 16 * AST * 2 + kM1Tickets * sizeof(int);
-    static bool attr_set = false;
-    if (!attr_set && smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_m1_kernel<BITS, JT, G, BVEC, F32, MULTI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsOptIn lds_opt_in;
+    if (smem > 48 * 1024) {
+        const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&decode_m1_kernel<BITS, JT, G, BVEC, F32, MULTI>), smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     hipLaunchKernelGGL((decode_m1_kernel<BITS, JT, G, BVEC, F32, MULTI>), grid, dim3(kM1Threads), smem, st, a);
     return hipGetLastError();

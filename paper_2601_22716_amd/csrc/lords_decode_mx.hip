@@ -414,12 +414,10 @@ static hipError_t launch_mx_t(const MxArgsT<MULTI ? kMaxBatch : 1> &a, dim3 grid
 {
     constexpr int WK = 4 * 128 * G, AST = WK + 8;
     const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)SS * 32 * AST * 2 + kMxTickets * sizeof(int);
-    static bool attr_set = false;
-    if (!attr_set && smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_mx_kernel<BITS, SS, G, BVEC, MULTI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsOptIn lds_opt_in;
+    if (smem > 48 * 1024) {
+        const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&decode_mx_kernel<BITS, SS, G, BVEC, MULTI>), smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     hipLaunchKernelGGL((decode_mx_kernel<BITS, SS, G, BVEC, MULTI>), grid, dim3(kMxThreads), smem, st, a);
     return hipGetLastError();

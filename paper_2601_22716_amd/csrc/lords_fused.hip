@@ -323,12 +323,10 @@ template <int BITS, int SS, int R, int MB, bool XLDS, bool MULTI>
 static hipError_t launch_fused(const FusedArgs &a, dim3 grid, hipStream_t st)
 {
     const size_t smem = (size_t)(32 * SS) * kAST * 2 + (XLDS ? (size_t)16 * MB * kAST * 2 : 0) + 16 * sizeof(float);
-    static bool attr_set = false;          // per instantiation
-    if (!attr_set && smem > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&fused_kernel<BITS, SS, R, MB, XLDS, MULTI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsOptIn lds_opt_in;
+    if (smem > 48 * 1024) {
+        const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&fused_kernel<BITS, SS, R, MB, XLDS, MULTI>), smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     hipLaunchKernelGGL((fused_kernel<BITS, SS, R, MB, XLDS, MULTI>), grid, dim3(256), smem, st, a);
     return hipGetLastError();

@@ -6,6 +6,26 @@
 
 namespace lords {
 
+// A kernel that asks for more dynamic LDS than the default limit must be told so once PER DEVICE
+// (the attribute belongs to the function on the device that is current).  One of these, static,
+// per kernel instantiation; a repeated call from two threads does the same thing twice.
+struct LdsOptIn {
+    bool done[16] = {};
+};
+inline hipError_t allow_dynamic_lds(LdsOptIn &state, const void *func, size_t bytes)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 16) return hipErrorInvalidDevice;
+    if (!state.done[dev]) {
+        e = hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        state.done[dev] = true;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_unpack(const void *codes, uint8_t *idx, int N, int K, int bits, hipStream_t st);
 
 hipError_t launch_dequant(const void *codes, const float *codebook, const void *B, const void *A, void *W,

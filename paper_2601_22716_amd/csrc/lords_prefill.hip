@@ -394,12 +394,10 @@ template <int BITS, int SS, int WM, int R, int WN = 4>
 static hipError_t launch_pf_t(const PrefillArgs &a, dim3 grid, hipStream_t st)
 {
     const size_t smem = (size_t)2 * (128 * WM) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM, R, WN>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsOptIn lds_opt_in;
+    {
+        const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM, R, WN>), smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM, R, WN>), grid, dim3(64 * WN * WM), smem, st, a);
     return hipGetLastError();

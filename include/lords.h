@@ -27,9 +27,11 @@
  *    NULL -> BITS -> SHAPE -> ALIGN -> DTYPE before anything is launched, so a bad
  *    call touches no memory.  A launch failure reported by the runtime gives
  *    LORDS_ERR_LAUNCH.
- *  - lords_matmul may use a per-device workspace that the library allocates on
- *    first need and keeps until the process ends; calls that overlap in time on
- *    one device must therefore not be issued from different streams.
+ *  - The multiplying entry points (lords_matmul*, lords_gate_up, lords_backward_*)
+ *    use a per-device workspace that the library allocates on first need, grows
+ *    when a call needs more (it then waits for the device to go idle first) and
+ *    keeps until the process ends; calls that overlap in time on one device must
+ *    therefore not be issued from different streams.
  */
 #ifndef LORDS_H
 #define LORDS_H

@@ -75,6 +75,8 @@ BATCHES = [
     ([200, 120], 1056, 64),                         # rank above 32: four column blocks per workgroup
     ([90, 60, 1], 288, 13),                         # rank not a multiple of 8, a one-row matrix
     ([2000, 40], 4128, 32),                         # very unequal row counts, K not a multiple of a column block
+    ([50, 30, 70], 256, 16),                        # one column block: every workgroup writes its rows itself
+    ([40, 20], 128, 40),
 ]
 
 

@@ -149,6 +149,29 @@ def test_matmul_parity_ragged_tokens(gpu, M):
     check_y(d.matmul(path=L.LORDS_PATH_PREFILL), want, "prefill")
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K,r,M,dt", [
+    # few tiles and a long K: the GEMM cuts K into ranges and a second kernel adds them
+    (130, 4128, 32, 40, "bf16"),       # bf16 output written by the adding kernel
+    (77, 2080, 48, 19, "f32"),         # M*N not a multiple of 4: ragged tail of the adding kernel
+    (300, 1056, 64, 130, "bf16"),
+    (64, 512, 8, 33, "bf16"),          # exactly four K tiles: one range, no second kernel
+])
+def test_matmul_prefill_with_k_ranges(gpu, bits, N, K, r, M, dt):
+    import torch
+    import paper_2601_22716_amd as L
+    say(f"prefill K ranges bits={bits} N={N} K={K} r={r} M={M} out={dt}")
+    cs = li.make_case("tiny", M=M, N=N, K=K, bits=bits, r=r, factor_dtype="bf16", seed=61, signed_factors=True)
+    d = gpu.DeviceCase(cs)
+    want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, bits)
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+    Y1 = d.matmul(path=L.LORDS_PATH_PREFILL, dtype=tdt)
+    check_y(Y1, want, "Y")
+    # the ranges are added in a fixed order: run-to-run identical; other calls in between
+    d.matmul(path=L.LORDS_PATH_DECODE, M=min(M, 3), X=d.X[:min(M, 3)].contiguous())
+    np.testing.assert_array_equal(d.matmul(path=L.LORDS_PATH_PREFILL, dtype=tdt), Y1)
+
+
 def test_matmul_tiny_config(gpu):
     import torch
     cs = li.make_case("tiny")

@@ -358,28 +358,48 @@ struct PfPlan {
     int ss, wm, R, wn, splits, tiles_per_split, nt, mt;
 };
 
+// K ranges for `tiles` output tiles: as many as fill the chip, at most 4, at least four K tiles each
+static int pf_ranges(long tiles, int ntiles_k)
+{
+    long s = 256 / tiles;
+    if (s > 4) s = 4;
+    if (s > ntiles_k / 4) s = ntiles_k / 4;
+    return s < 1 ? 1 : (int)s;
+}
+
 static PfPlan pf_plan(const MatmulProblem &p)
 {
     PfPlan d;
     d.ss = pf_ss(p.r);
     d.wm = 1; d.R = 2; d.wn = 4;
+    const int ntiles_k = (p.K + 127) / 128;
+    int s = 1;
     if (d.ss == 1) {
-        const long t256 = (long)((p.N + 255) / 256) * ((p.M + 255) / 256);
-        if (t256 >= 224) { d.wm = 2; d.R = 4; }
-        else if (p.M > 128) d.wm = 2;
+        // Candidates (tokens x rows of a tile, measured time of one K tile of one workgroup): 256 x 256
+        // at 5.1 us, 256 x 128 at 3.0 us, 128 x 128 at 2.3 us (only where no more than 128 tokens are there
+        // anyway).  Cost of a candidate: rounds of workgroups over 256 CUs x K tiles per range x that time,
+        // plus, with more than one range, the second kernel's traffic at 4 TB/s and 3 us.
+        struct Cand { int wm, R; double t; };
+        const Cand cands[3] = {{2, 4, 5.1}, {2, 2, 3.0}, {1, 2, 2.3}};
+        double best = 1e30;
+        for (int i = 0; i < 3; ++i) {
+            const Cand &c = cands[i];
+            if (c.wm == 1 && p.M > 128) continue;
+            const long tiles = (long)((p.N + 64 * c.R - 1) / (64 * c.R)) * ((p.M + 128 * c.wm - 1) / (128 * c.wm));
+            const int sc = pf_ranges(tiles, ntiles_k);
+            const long rounds = (tiles * sc + 255) / 256;
+            double cost = (double)rounds * ((ntiles_k + sc - 1) / sc) * c.t;
+            if (sc > 1) cost += 3.0 + ((double)sc * 4.0 + 2.0) * p.M * p.N / 4.0e6;
+            if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; s = sc; }
+        }
     } else {
         const long t = (long)((p.N + 255) / 256) * ((p.M + 127) / 128);
         if (t >= 200) d.wn = 8;
+        s = pf_ranges((long)((p.N + 16 * d.R * d.wn - 1) / (16 * d.R * d.wn)) * ((p.M + 127) / 128), ntiles_k);
     }
     d.nt = (p.N + 16 * d.R * d.wn - 1) / (16 * d.R * d.wn);
     d.mt = (p.M + 128 * d.wm - 1) / (128 * d.wm);
-    const int ntiles_k = (p.K + 127) / 128;
-    const long tiles = (long)d.nt * d.mt;
-    long s = 256 / tiles;
-    if (s > 4) s = 4;
-    if (s > ntiles_k / 4) s = ntiles_k / 4;              // at least four K tiles per range
-    if (s < 1) s = 1;
-    d.tiles_per_split = (int)((ntiles_k + s - 1) / s);
+    d.tiles_per_split = (ntiles_k + s - 1) / s;
     d.splits = (ntiles_k + d.tiles_per_split - 1) / d.tiles_per_split;
     return d;
 }

@@ -188,7 +188,57 @@ def bench_other(args, L, li, torch):
                         "frac_of_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS})
         del sets, X, Y
     out.extend(bench_shared_input(args, L, li, torch))
+    out.extend(bench_block(args, L, li, torch))
     out.extend(bench_backward(args, L, li, torch))
+    return out
+
+
+def bench_block(args, L, li, torch):
+    """Context figure: the seven linear layers of one Llama-3-8B-shaped block at one token and at two, as four
+    calls (q/k/v in one launch, o, gate/up with its activation, down), 4-bit codes of rank 32, rotating
+    through enough blocks that no launch finds its weights in the last-level cache."""
+    K0, I = 4096, 14336
+    bits, r = 4, 32
+    shapes = {"q": (4096, K0), "k": (1024, K0), "v": (1024, K0), "o": (4096, 4096), "gate": (I, K0), "up": (I, K0),
+              "down": (K0, I)}
+    per_block = sum(n * k for n, k in shapes.values()) * bits // 8
+    nblocks = int(-(-COLD_BYTES // per_block))
+    bf16_tensor = L.bf16_from_bits
+    blocks, xs = [], {}
+    for b in range(nblocks):
+        layers = {}
+        for j, (name, (n, k)) in enumerate(shapes.items()):
+            cs = li.make_case("qproj_4b", M=2, N=n, K=k, seed=5000 + 7 * b + j)
+            xs.setdefault(k, bf16_tensor(cs.X_bf16))
+            layers[name] = (torch.from_numpy(cs.codes).cuda(), bf16_tensor(cs.B_bf16), bf16_tensor(cs.A_bf16))
+            codebook = torch.from_numpy(cs.codebook.copy()).cuda()
+        blocks.append(layers)
+    out = []
+    for M in (1, 2):
+        f32 = dict(dtype=torch.float32, device="cuda")
+        Yq, Yk, Yv = torch.zeros((M, 4096), **f32), torch.zeros((M, 1024), **f32), torch.zeros((M, 1024), **f32)
+        Yo, H, Yd = torch.zeros((M, 4096), **f32), torch.zeros((M, I), **f32), torch.zeros((M, K0), **f32)
+        X4, X14 = xs[K0], xs[I]          # stand-ins for the activations that feed each layer (shapes only)
+
+        def step(i):
+            ly = blocks[i % nblocks]
+            q, k, v = ly["q"], ly["k"], ly["v"]
+            L.lords_matmul_batched(X4, [q[0], k[0], v[0]], codebook, [q[1], k[1], v[1]], [q[2], k[2], v[2]],
+                                   [Yq, Yk, Yv], [4096, 1024, 1024], M, K0, r, bits)
+            o = ly["o"]
+            L.lords_matmul(X4, o[0], codebook, o[1], o[2], Yo, M, 4096, K0, r, bits)
+            g, u = ly["gate"], ly["up"]
+            L.lords_gate_up(X4, g[0], g[1], g[2], u[0], u[1], u[2], codebook, H, M, I, K0, r, bits)
+            d = ly["down"]
+            L.lords_matmul(X14, d[0], codebook, d[1], d[2], Yd, M, K0, I, r, bits)
+
+        _, ev_ms, mode, _ = time_steps(step, 60, 6, torch, use_graph=not args.no_graph)
+        us = ev_ms * 1e3 / 60
+        out.append({"workload": f"decode M={M}, the seven linear layers of one Llama-3-8B-shaped block in four calls "
+                                f"(4-bit, rank 32; {nblocks} rotating blocks)",
+                    "us_per_step": us, "launch_mode": mode, "value": per_block / us / 1e3, "unit": "GB/s (codes only)",
+                    "frac_of_hbm_peak": per_block / us / 1e3 / HBM_PEAK_GBS,
+                    "ms_for_32_blocks": us * 32 / 1e3})
     return out
 
 
@@ -361,7 +411,7 @@ def main():
     if args.workload == "all" and not args.calibrate_copy:
         line["other_workloads"] = bench_other(args, L, li, torch)
     if args.workload == "shared_input":
-        line["other_workloads"] = bench_shared_input(args, L, li, torch)
+        line["other_workloads"] = bench_shared_input(args, L, li, torch) + bench_block(args, L, li, torch)
     if args.workload == "backward":
         line["other_workloads"] = bench_backward(args, L, li, torch)
     if args.calibrate_copy:

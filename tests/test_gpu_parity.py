@@ -230,3 +230,38 @@ def test_matmul_full_size_sampled(gpu, name, M):
     if M == cs.cfg.Ms[0]:
         got = d.unpack()
         np.testing.assert_array_equal(got[rows], oc.unpack_codes(cs.codes[rows], cs.K, cs.bits))
+
+
+@pytest.mark.parametrize("name,M", [("gateup_4b", 1), ("qproj_4b", 4), ("qproj_4b", 64)])
+def test_matmul_in_a_hip_graph_replays_identically(gpu, name, M):
+    """bench.py times the calls as HIP-graph replays: a captured call must give, on every replay, with
+    the program's own eager calls and synchronisations in between, exactly what the eager call gives
+    (the kernels keep their tickets in a workspace that both kinds of launch share)."""
+    import torch
+    import paper_2601_22716_amd as L
+    cfg = li.CONFIGS[name]
+    cs = li.make_case(name, M=M, seed=71)
+    d = gpu.DeviceCase(cs)
+    args = (d.codes, d.codebook, d.B, d.A)
+    Y_eager = torch.zeros((M, cfg.N), dtype=torch.float32, device="cuda")
+    L.lords_matmul(d.X, *args, Y_eager, M, cfg.N, cfg.K, cfg.r, cfg.bits)      # also allocates the workspace
+    torch.cuda.synchronize()
+    Y_graph = torch.zeros_like(Y_eager)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        L.lords_matmul(d.X, *args, Y_graph, M, cfg.N, cfg.K, cfg.r, cfg.bits)  # warm, on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            L.lords_matmul(d.X, *args, Y_graph, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+    for rep in range(3):
+        Y_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y_graph, Y_eager), f"replay {rep}"
+        # eager work of the same kind between the replays
+        Y2 = torch.zeros_like(Y_eager)
+        L.lords_matmul(d.X, *args, Y2, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+        torch.cuda.synchronize()
+        assert torch.equal(Y2, Y_eager)

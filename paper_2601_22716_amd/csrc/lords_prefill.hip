@@ -70,7 +70,7 @@ __device__ __forceinline__ uint32_t pair_index(const uint32_t (&w)[BITS], int p)
 }
 
 template <int BITS, int SS, int WM, int R, int WN = 4>
-__global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(PrefillArgs a)
+__global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN * WM / 4, WN * WM / 4))) void prefill_kernel(PrefillArgs a)
 {
     constexpr int MB = 8, BN = 16 * R * WN, BM = 128 * WM, NT = 64 * WN * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
     constexpr int RPP = 4 * WN * WM;                           // tile rows one staging pass of the workgroup covers
@@ -145,7 +145,8 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(2,
             const int k = min(kb + 8 * xkc, K - 8);            // ragged last tile: any finite data will do
             unsigned char *dst = Xs + p * XBUF + wave * 1024;
 #pragma nounroll
-            for (int q = 0; q < BM / RPP; ++q) {
+            for (int q = 0; q < (BM + RPP - 1) / RPP; ++q) {
+                if (BM % RPP != 0 && xm0 + RPP * q >= BM) break;    // (whole waves: a wave's four rows lie on one side)
                 const int m = min(m_blk + xm0 + RPP * q, M - 1);   // rows >= M: a copy of the last row, never stored
                 lds_direct_16(a.X + (size_t)m * K + k, dst + q * (RPP * 256));
             }
@@ -377,20 +378,25 @@ static PfPlan pf_plan(const MatmulProblem &p)
     if (d.ss == 1) {
         // Candidates (tokens x rows of a tile, measured time of one K tile of one workgroup): 256 x 256
         // at 5.1 us, 256 x 128 at 3.0 us, 128 x 128 at 2.3 us (only where no more than 128 tokens are there
-        // anyway).  Cost of a candidate: rounds of workgroups over 256 CUs x K tiles per range x that time,
-        // plus, with more than one range, the second kernel's traffic at 4 TB/s and 3 us.
-        struct Cand { int wm, R; double t; };
-        const Cand cands[3] = {{2, 4, 5.1}, {2, 2, 3.0}, {1, 2, 2.3}};
+        // anyway), and 256 x 192 with twelve waves (three per SIMD) at 3.9 us: no faster per weight than
+        // 256 x 256, but a row count that divides some layers into whole rounds where 256 does not; it
+        // has to win by 7 % to be taken.  Cost of a candidate: rounds of workgroups over 256 CUs x K tiles
+        // per range x that time, plus, with more than one range, the second kernel's traffic at 4 TB/s
+        // and 3 us.
+        struct Cand { int wm, R, wn; double t, handicap; };
+        const Cand cands[4] = {{2, 4, 4, 5.1, 1.0}, {2, 2, 4, 3.0, 1.0}, {1, 2, 4, 2.3, 1.0}, {2, 2, 6, 3.9, 1.0 / 0.93}};
         double best = 1e30;
-        for (int i = 0; i < 3; ++i) {
+        for (int i = 0; i < 4; ++i) {
             const Cand &c = cands[i];
             if (c.wm == 1 && p.M > 128) continue;
-            const long tiles = (long)((p.N + 64 * c.R - 1) / (64 * c.R)) * ((p.M + 128 * c.wm - 1) / (128 * c.wm));
+            if (c.wn == 6 && p.M <= 128) continue;
+            const long tiles = (long)((p.N + 16 * c.R * c.wn - 1) / (16 * c.R * c.wn)) * ((p.M + 128 * c.wm - 1) / (128 * c.wm));
             const int sc = pf_ranges(tiles, ntiles_k);
             const long rounds = (tiles * sc + 255) / 256;
             double cost = (double)rounds * ((ntiles_k + sc - 1) / sc) * c.t;
             if (sc > 1) cost += 3.0 + ((double)sc * 4.0 + 2.0) * p.M * p.N / 4.0e6;
-            if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; s = sc; }
+            cost *= c.handicap;
+            if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; d.wn = c.wn; s = sc; }
         }
     } else {
         const long t = (long)((p.N + 255) / 256) * ((p.M + 127) / 128);
@@ -448,7 +454,8 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStrea
     hipError_t e = hipErrorInvalidValue;
 #define LORDS_PCASE(B_, S_)                                                                     \
     if (p.bits == B_ && ss == S_) {                                                              \
-        if (S_ == 1 && wm == 2) e = R == 4 ? launch_pf_t<B_, 1, 2, 4>(a, grid, st) : launch_pf_t<B_, 1, 2, 2>(a, grid, st); \
+        if (S_ == 1 && wm == 2 && wn == 6) e = launch_pf_t<B_, 1, 2, 2, 6>(a, grid, st);          \
+        else if (S_ == 1 && wm == 2) e = R == 4 ? launch_pf_t<B_, 1, 2, 4>(a, grid, st) : launch_pf_t<B_, 1, 2, 2>(a, grid, st); \
         else if (S_ > 1 && wn == 8) e = launch_pf_t<B_, S_ == 1 ? 2 : S_, 1, 2, 8>(a, grid, st); \
         else e = launch_pf_t<B_, S_, 1, 2>(a, grid, st);                                         \
     }

@@ -172,6 +172,23 @@ def test_matmul_prefill_with_k_ranges(gpu, bits, N, K, r, M, dt):
     np.testing.assert_array_equal(d.matmul(path=L.LORDS_PATH_PREFILL, dtype=tdt), Y1)
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_matmul_prefill_192_row_tiles(gpu, bits):
+    """A shape that the GEMM serves with its twelve-wave, 192-row tiles (6144 rows and 2048 tokens are
+    one round of 256 such tiles); rows sampled across all six row groups of a tile and the ragged end."""
+    import paper_2601_22716_amd as L
+    N, K, r, M = 6144 - 8, 512, 32, 2048
+    say(f"prefill 192-row tiles bits={bits}")
+    cs = li.make_case("tiny", M=M, N=N, K=K, bits=bits, r=r, factor_dtype="bf16", seed=62, signed_factors=True)
+    Y = gpu.DeviceCase(cs).matmul(path=L.LORDS_PATH_PREFILL)
+    assert np.isfinite(Y).all()
+    rows = np.unique(np.concatenate([np.arange(0, 192), np.arange(N - 200, N),
+                                     np.random.default_rng(620).integers(0, N, 300)]))
+    toks = np.unique(np.concatenate([[0, 127, 128, 255, 256, M - 1], np.random.default_rng(621).integers(0, M, 60)]))
+    want = onp.matmul_rows(cs.X_f32[toks], cs.codes, cs.codebook, cs.B_f32, cs.A_f32, bits, rows)
+    check_y(Y[np.ix_(toks, rows)], want, "Y sample")
+
+
 def test_matmul_tiny_config(gpu):
     import torch
     cs = li.make_case("tiny")

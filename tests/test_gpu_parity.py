@@ -282,3 +282,31 @@ def test_matmul_in_a_hip_graph_replays_identically(gpu, name, M):
         L.lords_matmul(d.X, *args, Y2, M, cfg.N, cfg.K, cfg.r, cfg.bits)
         torch.cuda.synchronize()
         assert torch.equal(Y2, Y_eager)
+
+
+@pytest.mark.parametrize("name,M", [("gateup_4b", 1), ("gateup_4b", 8), ("gateup_4b", 2048), ("l70b_2b", 1), ("down_3b", 64)])
+def test_power_of_two_scaling_is_exact_at_full_size(gpu, name, M):
+    """A property that needs no oracle and holds for every output of a full-size call: scaling B, A or X
+    by a power of two scales every rounding step's input and output alike (no overflow or underflow at
+    these magnitudes), so Y must scale exactly, bit for bit."""
+    import torch
+    import paper_2601_22716_amd as L
+    cfg = li.CONFIGS[name]
+    cs = li.make_case(name, M=M, seed=72, signed_factors=True)
+    d = gpu.DeviceCase(cs)
+
+    def run(X, B, A):
+        Y = torch.full((M, cfg.N), float("nan"), dtype=torch.float32, device="cuda")
+        L.lords_matmul(X, d.codes, d.codebook, B, A, Y, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+        torch.cuda.synchronize()
+        return Y
+
+    Y0 = run(d.X, d.B, d.A)
+    assert torch.isfinite(Y0).all()
+    assert torch.equal(run(d.X, d.B * 8, d.A), Y0 * 8), "B scaled by 8"
+    assert torch.equal(run(d.X, d.B, d.A * 0.25), Y0 * 0.25), "A scaled by 1/4"
+    assert torch.equal(run(d.X * 0.0625, d.B, d.A), Y0 * 0.0625), "X scaled by 1/16"
+    # (negating X is NOT such a scaling here: the matrix cores' internal sums are not sign-symmetric to
+    #  the last bit, so -X gives -Y only up to rounding)
+    Yn = run(-d.X, d.B, d.A)
+    assert float((Yn + Y0).abs().max()) <= 1e-5 * float(Y0.abs().max()), "X negated"

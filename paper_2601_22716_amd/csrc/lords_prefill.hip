@@ -380,13 +380,14 @@ static PfPlan pf_plan(const MatmulProblem &p)
         // at 5.1 us, 256 x 128 at 3.0 us, 128 x 128 at 2.3 us (only where no more than 128 tokens are there
         // anyway), and 256 x 192 with twelve waves (three per SIMD) at 3.9 us: no faster per weight than
         // 256 x 256, but a row count that divides some layers into whole rounds where 256 does not; it
-        // has to win by 7 % to be taken.  Cost of a candidate: rounds of workgroups over 256 CUs x K tiles
+        // has to win by 7 % to be taken; and 128 x 256 with eight waves side by side at 3.7 us.  Cost of a candidate: rounds of workgroups over 256 CUs x K tiles
         // per range x that time, plus, with more than one range, the second kernel's traffic at 4 TB/s
         // and 3 us.
         struct Cand { int wm, R, wn; double t, handicap; };
-        const Cand cands[4] = {{2, 4, 4, 5.1, 1.0}, {2, 2, 4, 3.0, 1.0}, {1, 2, 4, 2.3, 1.0}, {2, 2, 6, 3.9, 1.0 / 0.93}};
+        const Cand cands[5] = {{2, 4, 4, 5.1, 1.0}, {2, 2, 4, 3.0, 1.0}, {1, 2, 4, 2.3, 1.0}, {2, 2, 6, 3.9, 1.0 / 0.93},
+                               {1, 2, 8, 3.7, 1.0}};
         double best = 1e30;
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 5; ++i) {
             const Cand &c = cands[i];
             if (c.wm == 1 && p.M > 128) continue;
             if (c.wn == 6 && p.M <= 128) continue;
@@ -456,7 +457,7 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStrea
     if (p.bits == B_ && ss == S_) {                                                              \
         if (S_ == 1 && wm == 2 && wn == 6) e = launch_pf_t<B_, 1, 2, 2, 6>(a, grid, st);          \
         else if (S_ == 1 && wm == 2) e = R == 4 ? launch_pf_t<B_, 1, 2, 4>(a, grid, st) : launch_pf_t<B_, 1, 2, 2>(a, grid, st); \
-        else if (S_ > 1 && wn == 8) e = launch_pf_t<B_, S_ == 1 ? 2 : S_, 1, 2, 8>(a, grid, st); \
+        else if (wn == 8) e = launch_pf_t<B_, S_, 1, 2, 8>(a, grid, st);                         \
         else e = launch_pf_t<B_, S_, 1, 2>(a, grid, st);                                         \
     }
     LORDS_PCASE(2, 1) LORDS_PCASE(2, 2) LORDS_PCASE(2, 4)

@@ -156,7 +156,7 @@ def bench_prefill(args, L, li, torch):
                    "launch_mode": mode},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": PREFILL_TRAFFIC_BYTES,
-                     "kernel": "lords::prefill_kernel<4,1,2,4>", "us_per_launch": ev_per_launch * 1e6},
+                     "kernel": "lords::prefill_kernel<4,1,1,2,8,16>", "us_per_launch": ev_per_launch * 1e6},
     }
 
 

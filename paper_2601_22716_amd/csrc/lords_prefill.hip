@@ -1,14 +1,18 @@
 // Large-M (prefill) kernel of  Y = X (C[Q] (.) (B A))^T  on gfx950: a bf16 MFMA GEMM whose weight
 // operand is dequantised on the fly and never leaves the registers.
 //
-// Tiling.  A workgroup owns a 256-row x (128*WM)-token tile of Y and walks K in tiles of 128
-// columns.  It has 4*WM waves: wave (wn, wm) owns rows 64 wn .. 64 wn + 63 (four 16-row slabs) and
-// tokens 128 wm .. 128 wm + 127, so each dequantised weight is reused for 128 tokens from
-// registers; the accumulators (4 slabs x 8 token blocks x 4 registers) stay in registers over the
-// whole K range.  WM = 2 (8 waves, two per SIMD) for padded ranks up to 32: the two waves of a SIMD
-// then overlap one's look-ups and conversions with the other's MFMAs, and the kernel is compiled
-// for at most 256 registers so that every MFMA writes plain VGPRs (results of the scale MFMAs are
-// read by vector ALU instructions, which cannot read the accumulation registers).
+// Tiling.  A workgroup owns a (16*R*WN)-row x (16*MB*WM)-token tile of Y and walks K in tiles of
+// 128 columns.  It has WN*WM waves: wave (wn, wm) owns rows 16R wn .. (R slabs of 16 rows) and
+// tokens 16MB wm .., so each dequantised weight is reused for 16*MB tokens from registers; the
+// accumulators (R slabs x MB token blocks x 4 registers, 128 in the large tiles) stay in
+// registers over the whole K range.  The main shape is 256 x 256 with eight waves side by side
+// along the rows (WN = 8, WM = 1, R = 2, MB = 16): every weight of the tile is dequantised by
+// exactly one wave and meets all 256 tokens there.  (Waves of 64 rows x 128 tokens, two of
+// which dequantise the same rows, were 9 % slower on the same tile although they read X from
+// LDS half as often: the vector work and the scale MFMAs weigh more than the LDS reads.)  Two
+// waves per SIMD, at most 256 registers each, so that every MFMA writes plain VGPRs (results of
+// the scale MFMAs are read by vector ALU instructions, which cannot read the accumulation
+// registers).  Smaller shapes for small problems and ranks above 32: see the launcher.
 //
 // Per K tile the X tile (BM x 128 bf16) and the A tile (padded rank x 128 bf16) are brought from
 // global memory straight into LDS (global_load_lds_dwordx4, no registers), double-buffered, one
@@ -69,10 +73,10 @@ __device__ __forceinline__ uint32_t pair_index(const uint32_t (&w)[BITS], int p)
     return v & ((1u << (2 * BITS)) - 1u);
 }
 
-template <int BITS, int SS, int WM, int R, int WN = 4>
+template <int BITS, int SS, int WM, int R, int WN = 4, int MB = 8>
 __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN * WM / 4, WN * WM / 4))) void prefill_kernel(PrefillArgs a)
 {
-    constexpr int MB = 8, BN = 16 * R * WN, BM = 128 * WM, NT = 64 * WN * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
+    constexpr int BN = 16 * R * WN, BM = 16 * MB * WM, NT = 64 * WN * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
     constexpr int RPP = 4 * WN * WM;                           // tile rows one staging pass of the workgroup covers
     constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
     extern __shared__ __align__(16) unsigned char smem[];
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     const int m_blk = (T / a.nt) * BM, n_blk = (T % a.nt) * BN;
     const int wn = wave % WN, wm = wave / WN;
     const int n_wave = n_blk + 16 * R * wn;
-    const int m_wave = m_blk + 128 * wm;
+    const int m_wave = m_blk + 16 * MB * wm;
 
     // ---- level table --------------------------------------------------------------------------------
     for (int id = tid; id < NE * kPfCopies; id += NT) {
@@ -202,7 +206,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             stage(kt + 1, p ^ 1);
             load_codes(kt + 1, cwn);
         }
-        const unsigned char *Xp = Xs + p * XBUF + wm * (128 * 256);
+        const unsigned char *Xp = Xs + p * XBUF + wm * (16 * MB * 256);
         const unsigned char *Ap = As + p * ABUF;
 
         // a-operand of scale MFMA t: 8 rank entries of 16 A columns, transposed out of LDS
@@ -356,7 +360,7 @@ __global__ __launch_bounds__(256) void reduce_split_kernel(const float *__restri
 // tiles would leave most CUs idle, K is cut into up to 4 ranges, each range a workgroup of its own
 // writing fp32 partial results that a second kernel adds in range order (deterministic).
 struct PfPlan {
-    int ss, wm, R, wn, splits, tiles_per_split, nt, mt;
+    int ss, wm, R, wn, mb, splits, tiles_per_split, nt, mt;
 };
 
 // K ranges for `tiles` output tiles: as many as fill the chip, at most 4, at least four K tiles each
@@ -372,32 +376,34 @@ static PfPlan pf_plan(const MatmulProblem &p)
 {
     PfPlan d;
     d.ss = pf_ss(p.r);
-    d.wm = 1; d.R = 2; d.wn = 4;
+    d.wm = 1; d.R = 2; d.wn = 4; d.mb = 8;
     const int ntiles_k = (p.K + 127) / 128;
     int s = 1;
     if (d.ss == 1) {
-        // Candidates (tokens x rows of a tile, measured time of one K tile of one workgroup): 256 x 256
-        // at 5.1 us, 256 x 128 at 3.0 us, 128 x 128 at 2.3 us (only where no more than 128 tokens are there
-        // anyway), and 256 x 192 with twelve waves (three per SIMD) at 3.9 us: no faster per weight than
-        // 256 x 256, but a row count that divides some layers into whole rounds where 256 does not; it
-        // has to win by 7 % to be taken; and 128 x 256 with eight waves side by side at 3.7 us.  Cost of a candidate: rounds of workgroups over 256 CUs x K tiles
-        // per range x that time, plus, with more than one range, the second kernel's traffic at 4 TB/s
-        // and 3 us.
-        struct Cand { int wm, R, wn; double t, handicap; };
-        const Cand cands[5] = {{2, 4, 4, 5.1, 1.0}, {2, 2, 4, 3.0, 1.0}, {1, 2, 4, 2.3, 1.0}, {2, 2, 6, 3.9, 1.0 / 0.93},
-                               {1, 2, 8, 3.7, 1.0}};
+        // Candidates (tokens x rows of a tile, measured time of one K tile of one workgroup):
+        //   256 x 256, eight waves of 32 rows x 256 tokens each    4.5 us   (no weight is dequantised twice
+        //             in a workgroup; before it, waves of 64 rows x 128 tokens took 5.1 us for the same tile)
+        //   256 x 128, eight waves of 32 rows x 128 tokens         3.0 us
+        //   256 x 192, twelve waves (three per SIMD)               3.9 us   no faster per weight, but a row count
+        //             that divides some layers into whole rounds where 256 does not; has to win by 7 %
+        //   128 x 128, four waves, and 128 x 256, eight waves      2.3 us, 3.7 us   (up to 128 tokens)
+        // Cost of a candidate: rounds of workgroups over 256 CUs x K tiles per range x that time, plus,
+        // with more than one range, the second kernel's traffic at 4 TB/s and 3 us.
+        struct Cand { int wm, R, wn, mb; double t, handicap; };
+        const Cand cands[5] = {{1, 2, 8, 16, 4.5, 1.0}, {2, 2, 4, 8, 3.0, 1.0}, {2, 2, 6, 8, 3.9, 1.0 / 0.93},
+                               {1, 2, 4, 8, 2.3, 1.0}, {1, 2, 8, 8, 3.7, 1.0}};
         double best = 1e30;
         for (int i = 0; i < 5; ++i) {
             const Cand &c = cands[i];
-            if (c.wm == 1 && p.M > 128) continue;
-            if (c.wn == 6 && p.M <= 128) continue;
-            const long tiles = (long)((p.N + 16 * c.R * c.wn - 1) / (16 * c.R * c.wn)) * ((p.M + 128 * c.wm - 1) / (128 * c.wm));
+            const int tokens = 16 * c.mb * c.wm;
+            if ((tokens == 128) != (p.M <= 128)) continue;
+            const long tiles = (long)((p.N + 16 * c.R * c.wn - 1) / (16 * c.R * c.wn)) * ((p.M + tokens - 1) / tokens);
             const int sc = pf_ranges(tiles, ntiles_k);
             const long rounds = (tiles * sc + 255) / 256;
             double cost = (double)rounds * ((ntiles_k + sc - 1) / sc) * c.t;
             if (sc > 1) cost += 3.0 + ((double)sc * 4.0 + 2.0) * p.M * p.N / 4.0e6;
             cost *= c.handicap;
-            if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; d.wn = c.wn; s = sc; }
+            if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; d.wn = c.wn; d.mb = c.mb; s = sc; }
         }
     } else {
         const long t = (long)((p.N + 255) / 256) * ((p.M + 127) / 128);
@@ -405,7 +411,7 @@ static PfPlan pf_plan(const MatmulProblem &p)
         s = pf_ranges((long)((p.N + 16 * d.R * d.wn - 1) / (16 * d.R * d.wn)) * ((p.M + 127) / 128), ntiles_k);
     }
     d.nt = (p.N + 16 * d.R * d.wn - 1) / (16 * d.R * d.wn);
-    d.mt = (p.M + 128 * d.wm - 1) / (128 * d.wm);
+    d.mt = (p.M + 16 * d.mb * d.wm - 1) / (16 * d.mb * d.wm);
     d.tiles_per_split = (ntiles_k + s - 1) / s;
     d.splits = (ntiles_k + d.tiles_per_split - 1) / d.tiles_per_split;
     return d;
@@ -417,16 +423,16 @@ size_t prefill_fast_workspace_bytes(const MatmulProblem &p)
     return d.splits > 1 ? (size_t)d.splits * p.M * p.N * sizeof(float) : 0;
 }
 
-template <int BITS, int SS, int WM, int R, int WN = 4>
+template <int BITS, int SS, int WM, int R, int WN = 4, int MB = 8>
 static hipError_t launch_pf_t(const PrefillArgs &a, dim3 grid, hipStream_t st)
 {
-    const size_t smem = (size_t)2 * (128 * WM) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
+    const size_t smem = (size_t)2 * (16 * MB * WM) * 256 + (size_t)2 * (32 * SS) * 256 + (size_t)(1 << (2 * BITS)) * kPfCopies * 4;
     static LdsOptIn lds_opt_in;
     {
-        const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM, R, WN>), smem);
+        const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&prefill_kernel<BITS, SS, WM, R, WN, MB>), smem);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM, R, WN>), grid, dim3(64 * WN * WM), smem, st, a);
+    hipLaunchKernelGGL((prefill_kernel<BITS, SS, WM, R, WN, MB>), grid, dim3(64 * WN * WM), smem, st, a);
     return hipGetLastError();
 }
 
@@ -455,8 +461,9 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStrea
     hipError_t e = hipErrorInvalidValue;
 #define LORDS_PCASE(B_, S_)                                                                     \
     if (p.bits == B_ && ss == S_) {                                                              \
-        if (S_ == 1 && wm == 2 && wn == 6) e = launch_pf_t<B_, 1, 2, 2, 6>(a, grid, st);          \
-        else if (S_ == 1 && wm == 2) e = R == 4 ? launch_pf_t<B_, 1, 2, 4>(a, grid, st) : launch_pf_t<B_, 1, 2, 2>(a, grid, st); \
+        if (S_ == 1 && d.mb == 16) e = launch_pf_t<B_, 1, 1, 2, 8, 16>(a, grid, st);               \
+        else if (S_ == 1 && wm == 2 && wn == 6) e = launch_pf_t<B_, 1, 2, 2, 6>(a, grid, st);          \
+        else if (S_ == 1 && wm == 2) e = launch_pf_t<B_, 1, 2, 2>(a, grid, st);                   \
         else if (wn == 8) e = launch_pf_t<B_, S_, 1, 2, 8>(a, grid, st);                         \
         else e = launch_pf_t<B_, S_, 1, 2>(a, grid, st);                                         \
     }

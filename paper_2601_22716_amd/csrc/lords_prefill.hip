@@ -265,14 +265,28 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
 
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
+            // X operands run kXAhead token blocks ahead of their MFMAs: the first ones of a stage are
+            // requested before its dequantisation, each later one as the block kXAhead before it is
+            // issued, so that no MFMA waits for the LDS read that feeds it
+            constexpr int kXAhead = 2;
             bf16x8 W[R];
+            bf16x8 Xq[kXAhead];
+#pragma unroll
+            for (int i = 0; i < kXAhead; ++i)
+                Xq[i] = *reinterpret_cast<const bf16x8 *>(Xp + i * 4096 + xoff[u]);
+            __builtin_amdgcn_sched_barrier(0);
             dequant_stage(u, W);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                const bf16x8 Xop = *reinterpret_cast<const bf16x8 *>(Xp + mb * 4096 + xoff[u]);
+                const bf16x8 Xop = Xq[mb % kXAhead];
 #pragma unroll
                 for (int rho = 0; rho < R; ++rho)
                     acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W[rho], Xop, acc[rho][mb], 0, 0, 0);
+                if (mb + kXAhead < MB) {
+                    Xq[mb % kXAhead] =
+                        *reinterpret_cast<const bf16x8 *>(Xp + (mb + kXAhead) * 4096 + xoff[u]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
 

@@ -51,17 +51,18 @@ struct PrefillArgs {
 
 constexpr int kPfCopies = 8;
 
-__device__ __forceinline__ void lds_direct_16(const void *gsrc, void *lds_wave_base)
+__device__ __forceinline__ void lds_direct_16(const void *gbase, uint32_t goff, uint32_t lds_wave_base)
 {
-    // Every active lane fetches 16 bytes from its own address; they land at lds_wave_base + 16*lane
-    // (M0 holds the wave's LDS base).  Written as assembly on purpose: when the compiler knows of
-    // an outstanding load into LDS it makes the next LDS read wait for ALL outstanding memory
-    // loads, i.e. for the tile that was just requested, which exposes the whole memory latency
-    // once per K tile.  The kernel orders these loads itself: s_waitcnt vmcnt(0) and a barrier
-    // before a buffer is read.
-    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(base), "v"(gsrc) : "memory", "m0");
+    // Every active lane fetches 16 bytes from gbase + goff (gbase and lds_wave_base are the same
+    // in all lanes and travel in scalar registers, goff is the lane's own byte offset); they land
+    // at lds_wave_base + 16*lane (M0 holds the wave's LDS base).  With the row offsets of a tile
+    // computed once, a tile load costs no vector instruction besides the load itself.
+    // Written as assembly on purpose: when the compiler knows of an outstanding load into LDS it
+    // makes the next LDS read wait for ALL outstanding memory loads, i.e. for the tile that was
+    // just requested, which exposes the whole memory latency once per K tile.  The kernel orders
+    // these loads itself: s_waitcnt vmcnt(0) and a barrier before a buffer is read.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_wave_base), "v"(goff), "s"(gbase) : "memory", "m0");
 }
 
 template <int BITS>
@@ -139,34 +140,49 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     }
 
     // ---- staging of one K tile into buffer p (direct to LDS) and of its codes into registers ---------
-    // The loops over the 4-row groups are kept rolled on purpose: unrolled, their loop-invariant
-    // row addresses get hoisted into dozens of registers that the accumulators need.
-    const int xm0 = 4 * wave + (lane >> 4);                   // first tile row this lane fetches; then +RPP per step
-    const int xkc = (lane & 15) ^ (xm0 & 15);                 // its column chunk (same for every step)
+    // A staging pass of the workgroup covers RPP tile rows: lane (wave, l) fetches chunk
+    // (l & 15) ^ (row & 15) of row 4 wave + l / 16 (+ RPP per pass).  The byte offsets of the
+    // lane's chunks from the tile's first element do not change along K and are kept in registers.
+    constexpr int XQ = (BM + RPP - 1) / RPP, AQ = (RP + RPP - 1) / RPP;
+    const int xm0 = 4 * wave + (lane >> 4);
+    const int xkc = (lane & 15) ^ (xm0 & 15);
+    uint32_t xo[XQ], ao[AQ];
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) {
+        const int m = min(m_blk + xm0 + RPP * q, M - 1);       // rows >= M: a copy of the last row, never stored
+        xo[q] = ((uint32_t)(m - m_blk) * (uint32_t)K + 8u * xkc) * 2u;
+    }
+#pragma unroll
+    for (int q = 0; q < AQ; ++q) ao[q] = ((uint32_t)min(xm0 + RPP * q, max(a.r - 1, 0)) * (uint32_t)K + 8u * xkc) * 2u;
+    const uint32_t xl0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(Xs + wave * 1024));
+    const uint32_t al0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(As + wave * 1024));
+    const uint16_t *Xtile = a.X + (size_t)m_blk * K;
     auto stage = [&](int kt, int p) {
         const int kb = kt * 128;
-        {
-            const int k = min(kb + 8 * xkc, K - 8);            // ragged last tile: any finite data will do
-            unsigned char *dst = Xs + p * XBUF + wave * 1024;
-#pragma nounroll
-            for (int q = 0; q < (BM + RPP - 1) / RPP; ++q) {
-                if (BM % RPP != 0 && xm0 + RPP * q >= BM) break;    // (whole waves: a wave's four rows lie on one side)
-                const int m = min(m_blk + xm0 + RPP * q, M - 1);   // rows >= M: a copy of the last row, never stored
-                lds_direct_16(a.X + (size_t)m * K + k, dst + q * (RPP * 256));
+        if (kb + 128 <= K) {
+#pragma unroll
+            for (int q = 0; q < XQ; ++q) {
+                if (BM % RPP != 0 && xm0 + RPP * q >= BM) continue;   // (whole waves: a wave's four rows lie on one side)
+                lds_direct_16(Xtile + kb, xo[q], xl0 + p * XBUF + q * (RPP * 256));
             }
-        }
-        {
-            const int k = kb + 8 * xkc;
-            unsigned char *dst = As + p * ABUF + wave * 1024;
-#pragma nounroll
-            for (int q = 0; q < (RP + RPP - 1) / RPP; ++q) {
-                const int j = xm0 + RPP * q;
-                if (j < a.r && k < K) {
-                    lds_direct_16(a.A + (size_t)j * K + k, dst + q * (RPP * 256));
-                } else if (kb + 128 > K && j < a.r) {
-                    // ragged last tile: columns >= K of a live rank row must read as zero
-                    *reinterpret_cast<u32x4 *>(dst + q * (RPP * 256) + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
-                }
+#pragma unroll
+            for (int q = 0; q < AQ; ++q)
+                if (xm0 + RPP * q < a.r) lds_direct_16(a.A + kb, ao[q], al0 + p * ABUF + q * (RPP * 256));
+        } else {
+            // ragged last tile: X chunks beyond K are fetched from further left (any finite data will
+            // do: their weights are zero), A columns beyond K of a live rank row must read as zero
+            const int over = kb + 8 * xkc - (K - 8);
+            const uint32_t back = over > 0 ? 2u * over : 0u;
+#pragma unroll
+            for (int q = 0; q < XQ; ++q) {
+                if (BM % RPP != 0 && xm0 + RPP * q >= BM) continue;
+                lds_direct_16(Xtile + kb, xo[q] - back, xl0 + p * XBUF + q * (RPP * 256));
+            }
+#pragma unroll
+            for (int q = 0; q < AQ; ++q) {
+                if (xm0 + RPP * q >= a.r) continue;
+                if (kb + 8 * xkc < K) lds_direct_16(a.A + kb, ao[q], al0 + p * ABUF + q * (RPP * 256));
+                else *reinterpret_cast<u32x4 *>(As + p * ABUF + wave * 1024 + q * (RPP * 256) + 16 * lane) = u32x4{0u, 0u, 0u, 0u};
             }
         }
     };

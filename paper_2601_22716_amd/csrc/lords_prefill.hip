@@ -16,9 +16,9 @@
 //
 // Per K tile the X tile (BM x 128 bf16) and the A tile (padded rank x 128 bf16) are brought from
 // global memory straight into LDS (global_load_lds_dwordx4, no registers), double-buffered, one
-// barrier per tile.  Both tiles are row-major with the 16-byte chunks of a row XOR-swizzled by the
-// row number (slot = chunk ^ (row & 15)), which makes the b-operand reads of X (ds_read_b128) and
-// the transposing reads of A (ds_read_b64_tr_b16) bank-conflict free.
+// barrier per tile.  16-byte chunks are XOR-swizzled by row so that the b-operand reads of X
+// (ds_read_b128) and the transposing reads of A (ds_read_b64_tr_b16) are free of bank conflicts;
+// the layouts are described where the tiles are staged.
 //
 // Lane mapping as in the decode kernels (v_mfma_f32_16x16x32_bf16, lane l = (c = l%16, g = l/16)):
 // the lane holds the 32 codes of row n0+c at columns kb + 32g ..; scale MFMA t gives it the scales
@@ -140,17 +140,28 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     }
 
     // ---- staging of one K tile into buffer p (direct to LDS) and of its codes into registers ---------
-    // A staging pass of the workgroup covers RPP tile rows: lane (wave, l) fetches chunk
-    // (l & 15) ^ (row & 15) of row 4 wave + l / 16 (+ RPP per pass).  The byte offsets of the
-    // lane's chunks from the tile's first element do not change along K and are kept in registers.
-    constexpr int XQ = (BM + RPP - 1) / RPP, AQ = (RP + RPP - 1) / RPP;
+    // X tile in LDS: two halves of 64 columns, each [BM tokens][128 B]; a wave load fills 8 token
+    // rows of one half, lane l bringing token l / 8 and landing in slot l % 8 of its row.  Slot
+    // s of token t of half h holds the 8 columns 32 gg + 8 uu + 16 h with 4 uu + gg = s ^ (t & 7):
+    // the four 16-byte chunks that the four lane groups g of an MFMA b-operand want at stage
+    // u = 2 h + uu then sit in one 64-byte quarter-row, XOR-swizzled by token, and a wave's operand
+    // read (16 tokens x 4 chunks) is free of bank conflicts (rows of 256 bytes, one per token,
+    // cost 8.2 cycles per read however they were swizzled, these rows 5.0).
+    // A tile: row-major, 256 B per rank row, lane (wave, l) fetches chunk (l & 15) ^ (row & 15) of
+    // row 4 wave + l / 16 (+ RPP per pass).  The byte offsets of a lane's chunks from the tile's
+    // first element do not change along K and are kept in registers.
+    constexpr int AQ = (RP + RPP - 1) / RPP;
+    constexpr int TPP = 8 * WN * WM, XJ = (BM + TPP - 1) / TPP;   // tokens per staging pass, passes
     const int xm0 = 4 * wave + (lane >> 4);
     const int xkc = (lane & 15) ^ (xm0 & 15);
-    uint32_t xo[XQ], ao[AQ];
+    const int xt0 = 8 * wave + (lane >> 3);
+    const int xv = (lane & 7) ^ (lane >> 3);
+    const int xkcol = 32 * (xv & 3) + 8 * (xv >> 2);
+    uint32_t xo[XJ], ao[AQ];
 #pragma unroll
-    for (int q = 0; q < XQ; ++q) {
-        const int m = min(m_blk + xm0 + RPP * q, M - 1);       // rows >= M: a copy of the last row, never stored
-        xo[q] = ((uint32_t)(m - m_blk) * (uint32_t)K + 8u * xkc) * 2u;
+    for (int j = 0; j < XJ; ++j) {
+        const int m = min(m_blk + xt0 + TPP * j, M - 1);       // rows >= M: a copy of the last row, never stored
+        xo[j] = ((uint32_t)(m - m_blk) * (uint32_t)K + (uint32_t)xkcol) * 2u;
     }
 #pragma unroll
     for (int q = 0; q < AQ; ++q) ao[q] = ((uint32_t)min(xm0 + RPP * q, max(a.r - 1, 0)) * (uint32_t)K + 8u * xkc) * 2u;
@@ -161,9 +172,10 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
         const int kb = kt * 128;
         if (kb + 128 <= K) {
 #pragma unroll
-            for (int q = 0; q < XQ; ++q) {
-                if (BM % RPP != 0 && xm0 + RPP * q >= BM) continue;   // (whole waves: a wave's four rows lie on one side)
-                lds_direct_16(Xtile + kb, xo[q], xl0 + p * XBUF + q * (RPP * 256));
+            for (int j = 0; j < XJ; ++j) {
+                if (BM % TPP != 0 && xt0 + TPP * j >= BM) continue;   // (whole waves: a wave's eight tokens lie on one side)
+                lds_direct_16(Xtile + kb, xo[j], xl0 + p * XBUF + j * (TPP * 128));
+                lds_direct_16(Xtile + kb + 16, xo[j], xl0 + p * XBUF + XBUF / 2 + j * (TPP * 128));
             }
 #pragma unroll
             for (int q = 0; q < AQ; ++q)
@@ -171,12 +183,15 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
         } else {
             // ragged last tile: X chunks beyond K are fetched from further left (any finite data will
             // do: their weights are zero), A columns beyond K of a live rank row must read as zero
-            const int over = kb + 8 * xkc - (K - 8);
-            const uint32_t back = over > 0 ? 2u * over : 0u;
 #pragma unroll
-            for (int q = 0; q < XQ; ++q) {
-                if (BM % RPP != 0 && xm0 + RPP * q >= BM) continue;
-                lds_direct_16(Xtile + kb, xo[q] - back, xl0 + p * XBUF + q * (RPP * 256));
+            for (int j = 0; j < XJ; ++j) {
+                if (BM % TPP != 0 && xt0 + TPP * j >= BM) continue;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int over = kb + 16 * h + xkcol - (K - 8);
+                    const uint32_t back = over > 0 ? 2u * over : 0u;
+                    lds_direct_16(Xtile + kb + 16 * h, xo[j] - back, xl0 + p * XBUF + h * (XBUF / 2) + j * (TPP * 128));
+                }
             }
 #pragma unroll
             for (int q = 0; q < AQ; ++q) {
@@ -213,7 +228,9 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     // per-lane LDS offsets
     uint32_t xoff[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) xoff[u] = (uint32_t)(c * 256 + (((4 * g + u) ^ c) * 16));
+    for (int u = 0; u < 4; ++u)
+        xoff[u] = (uint32_t)((u >> 1) * (XBUF / 2) + c * 128 + (((4 * (u & 1) + g) ^ (c & 7)) * 16));
+
     const uint32_t lutoff = (uint32_t)(2 * XBUF + 2 * ABUF) + (uint32_t)(lane & 7) * 4u;
 
     for (int kt = kt0; kt < kt1; ++kt) {
@@ -222,7 +239,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             stage(kt + 1, p ^ 1);
             load_codes(kt + 1, cwn);
         }
-        const unsigned char *Xp = Xs + p * XBUF + wm * (16 * MB * 256);
+        const unsigned char *Xp = Xs + p * XBUF + wm * (16 * MB * 128);
         const unsigned char *Ap = As + p * ABUF;
 
         // a-operand of scale MFMA t: 8 rank entries of 16 A columns, transposed out of LDS
@@ -279,33 +296,106 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             }
         };
 
+        if constexpr (R == 2 && SS == 1 && MB == 16) {
+            // Main shape: the K tile as one software pipeline of 64 steps (4 stages x 16 token blocks),
+            // pinned step by step with scheduling barriers.  A step is the two product MFMAs of one
+            // token block; riding on it are the X operand read of the block kAhead steps later and a
+            // slice of the NEXT stage's dequantisation (A columns and table addresses in steps 0-3,
+            // table reads in steps 1-4, scale MFMAs in step 3, one pair of weights converted in each
+            // of steps 5-12), so that vector and LDS instructions issue in the shadow of MFMAs of
+            // the same wave and every result is asked for several MFMAs before it is needed.  Only
+            // stage 0 of a tile is dequantised in the open (its A tile arrives with the barrier).
+            constexpr int kAhead = 3;
+            bf16x8 Wc[2], Wn[2];
+            bf16x8 Xq[kAhead];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            // X operands run kXAhead token blocks ahead of their MFMAs: the first ones of a stage are
-            // requested before its dequantisation, each later one as the block kXAhead before it is
-            // issued, so that no MFMA waits for the LDS read that feeds it
-            constexpr int kXAhead = 2;
-            bf16x8 W[R];
-            bf16x8 Xq[kXAhead];
-#pragma unroll
-            for (int i = 0; i < kXAhead; ++i)
-                Xq[i] = *reinterpret_cast<const bf16x8 *>(Xp + i * 4096 + xoff[u]);
+            for (int i = 0; i < kAhead; ++i) Xq[i] = *reinterpret_cast<const bf16x8 *>(Xp + i * 2048 + xoff[0]);
             __builtin_amdgcn_sched_barrier(0);
-            dequant_stage(u, W);
+            dequant_stage(0, Wc);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                const bf16x8 Xop = Xq[mb % kXAhead];
+            for (int u = 0; u < 4; ++u) {
+                bf16x8 Aop0, Aop1;
+                uint32_t ad[2][4], lv[2][4];
+                f32x4 S0[2], S1[2];
+                const int un = u < 3 ? u + 1 : 3;
 #pragma unroll
-                for (int rho = 0; rho < R; ++rho)
-                    acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W[rho], Xop, acc[rho][mb], 0, 0, 0);
-                if (mb + kXAhead < MB) {
-                    Xq[mb % kXAhead] =
-                        *reinterpret_cast<const bf16x8 *>(Xp + (mb + kXAhead) * 4096 + xoff[u]);
+                for (int mb = 0; mb < 16; ++mb) {
+                    const int t = 16 * u + mb;
+                    const bf16x8 Xop = Xq[t % kAhead];
+                    acc[0][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wc[0], Xop, acc[0][mb], 0, 0, 0);
+                    acc[1][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wc[1], Xop, acc[1][mb], 0, 0, 0);
+                    if (t + kAhead < 64) {
+                        const int tn = t + kAhead;
+                        Xq[t % kAhead] = *reinterpret_cast<const bf16x8 *>(Xp + (tn % 16) * 2048 + xoff[tn / 16]);
+                    }
+                    if (u < 3) {
+                        if (mb == 0) { Aop0 = read_Aop(0, 2 * un); Aop1 = read_Aop(0, 2 * un + 1); }
+                        if (mb < 4) {
+                            const int q = mb >> 1;
+#pragma unroll
+                            for (int e = 0; e < 2; ++e) {
+                                const int pp = 2 * (mb & 1) + e;
+                                ad[q][pp] = (pair_index<BITS>(cw[q], 4 * un + pp) << 5) + lutoff;
+                            }
+                        }
+                        if (mb >= 1 && mb < 5) {
+                            const int j = mb - 1, q = j >> 1;
+#pragma unroll
+                            for (int e = 0; e < 2; ++e) {
+                                const int pp = 2 * (j & 1) + e;
+                                lv[q][pp] = lds_load_u32(ad[q][pp]);
+                            }
+                        }
+                        if (mb == 3) {
+#pragma unroll
+                            for (int q = 0; q < 2; ++q) {
+                                S0[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop0, Bop[q][0], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                                S1[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop1, Bop[q][0], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                            }
+                        }
+                        if (mb >= 5 && mb < 13) {
+                            const int j = mb - 5, q = j >> 2, pp = j & 3;
+                            const f16x2 h = __builtin_bit_cast(f16x2, lv[q][pp]);
+                            const float s0 = pp < 2 ? S0[q][2 * pp] : S1[q][2 * pp - 4];
+                            const float s1 = pp < 2 ? S0[q][2 * pp + 1] : S1[q][2 * pp - 3];
+                            Wn[q][2 * pp] = (__bf16)__builtin_fmaf((float)h[0], s0, 0.0f);
+                            Wn[q][2 * pp + 1] = (__bf16)__builtin_fmaf((float)h[1], s1, 0.0f);
+                        }
+                    }
                     __builtin_amdgcn_sched_barrier(0);
+                }
+                Wc[0] = Wn[0];
+                Wc[1] = Wn[1];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                // X operands run kXAhead token blocks ahead of their MFMAs: the first ones of a stage
+                // are requested before its dequantisation, each later one as the block kXAhead before
+                // it is issued
+                constexpr int kXAhead = 2;
+                bf16x8 W[R];
+                bf16x8 Xq[kXAhead];
+#pragma unroll
+                for (int i = 0; i < kXAhead; ++i)
+                    Xq[i] = *reinterpret_cast<const bf16x8 *>(Xp + i * 2048 + xoff[u]);
+                __builtin_amdgcn_sched_barrier(0);
+                dequant_stage(u, W);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const bf16x8 Xop = Xq[mb % kXAhead];
+#pragma unroll
+                    for (int rho = 0; rho < R; ++rho)
+                        acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W[rho], Xop, acc[rho][mb], 0, 0, 0);
+                    if (mb + kXAhead < MB) {
+                        Xq[mb % kXAhead] =
+                            *reinterpret_cast<const bf16x8 *>(Xp + (mb + kXAhead) * 2048 + xoff[u]);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
         }
-
         __builtin_amdgcn_s_waitcnt(0);          // the next tile has landed in LDS, the next codes in registers
         __syncthreads();
 #pragma unroll

@@ -236,7 +236,8 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     for (int kt = kt0; kt < kt1; ++kt) {
         const int p = (kt - kt0) & 1;
         if (kt + 1 < kt1) {
-            stage(kt + 1, p ^ 1);
+            // (the main shape issues the loads of a whole next tile one by one from its pipeline steps)
+            if (!(R == 2 && SS == 1 && MB == 16) || (kt + 2) * 128 > K) stage(kt + 1, p ^ 1);
             load_codes(kt + 1, cwn);
         }
         const unsigned char *Xp = Xs + p * XBUF + wm * (16 * MB * 128);
@@ -306,6 +307,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             // the same wave and every result is asked for several MFMAs before it is needed.  Only
             // stage 0 of a tile is dequantised in the open (its A tile arrives with the barrier).
             constexpr int kAhead = 3;
+            constexpr int kLoad0 = 6;                           // first step of stage 0 that carries a tile load
             bf16x8 Wc[2], Wn[2];
             bf16x8 Xq[kAhead];
 #pragma unroll
@@ -325,6 +327,13 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
                     const bf16x8 Xop = Xq[t % kAhead];
                     acc[0][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wc[0], Xop, acc[0][mb], 0, 0, 0);
                     acc[1][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wc[1], Xop, acc[1][mb], 0, 0, 0);
+                    if (u == 0 && mb >= kLoad0 && mb < kLoad0 + 9 && kt + 1 < kt1 && (kt + 2) * 128 <= K) {
+                        // one tile load of the next K tile per step (8 of X, 1 of A): issued in one
+                        // burst at the head of the tile they cost 3-4 % more
+                        const int i = mb - kLoad0, kbn = (kt + 1) * 128;
+                        if (i < 8) lds_direct_16(Xtile + kbn + 16 * (i & 1), xo[i >> 1], xl0 + (p ^ 1) * XBUF + (i & 1) * (XBUF / 2) + (i >> 1) * (TPP * 128));
+                        else if (xm0 < a.r) lds_direct_16(a.A + kbn, ao[0], al0 + (p ^ 1) * ABUF);
+                    }
                     if (t + kAhead < 64) {
                         const int tn = t + kAhead;
                         Xq[t % kAhead] = *reinterpret_cast<const bf16x8 *>(Xp + (tn % 16) * 2048 + xoff[tn / 16]);

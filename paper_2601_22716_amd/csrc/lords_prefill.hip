@@ -25,8 +25,8 @@
 // of codes 4t..4t+3; product MFMA u contracts columns 32g + 8u .. +8 with
 // a-operand = the lane's 8 dequantised weights and b-operand = X[token c][same 8 columns].
 // A K tile is processed in four stages u = 0..3 (scale MFMAs 2u, 2u+1 -> dequantise 8 weights per
-// slab -> BM/16 x 4 product MFMAs), written so that stage u+1's dequantisation can be scheduled
-// under stage u's product MFMAs.
+// slab -> BM/16 x 4 product MFMAs); for ranks up to 32 the stages overlap as a software pipeline
+// (stage u+1's dequantisation is spread over stage u's product MFMAs, see the K loop).
 //
 // Level look-up: two codes index an LDS table of fp16 pairs, 8 copies (address =
 // index*32 + (lane%8)*4); v_fma_mix_f32 multiplies fp16 level by fp32 scale; one rounding to bf16.
@@ -80,6 +80,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     constexpr int BN = 16 * R * WN, BM = 16 * MB * WM, NT = 64 * WN * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
     constexpr int RPP = 4 * WN * WM;                           // tile rows one staging pass of the workgroup covers
     constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
+    constexpr bool kPipe = (R == 2 && SS == 1 && (MB == 8 || MB == 16));   // ranks up to 32: pipelined K loop
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *Xs = smem;                                   // [2][BM][256 B]
     unsigned char *As = smem + 2 * XBUF;                        // [2][RP][256 B]
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
         const int p = (kt - kt0) & 1;
         if (kt + 1 < kt1) {
             // (the main shape issues the loads of a whole next tile one by one from its pipeline steps)
-            if (!(R == 2 && SS == 1 && MB == 16) || (kt + 2) * 128 > K) stage(kt + 1, p ^ 1);
+            if (!kPipe || (kt + 2) * 128 > K) stage(kt + 1, p ^ 1);
             load_codes(kt + 1, cwn);
         }
         const unsigned char *Xp = Xs + p * XBUF + wm * (16 * MB * 128);
@@ -297,17 +298,26 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             }
         };
 
-        if constexpr (R == 2 && SS == 1 && MB == 16) {
-            // Main shape: the K tile as one software pipeline of 64 steps (4 stages x 16 token blocks),
-            // pinned step by step with scheduling barriers.  A step is the two product MFMAs of one
-            // token block; riding on it are the X operand read of the block kAhead steps later and a
-            // slice of the NEXT stage's dequantisation (A columns and table addresses in steps 0-3,
-            // table reads in steps 1-4, scale MFMAs in step 3, one pair of weights converted in each
-            // of steps 5-12), so that vector and LDS instructions issue in the shadow of MFMAs of
+        if constexpr (kPipe) {
+            // Ranks up to 32: the K tile as one software pipeline of 4 MB steps (4 stages x MB token
+            // blocks), pinned step by step with scheduling barriers.  A step is the two product MFMAs
+            // of one token block; riding on it are the X operand read of the block kAhead steps later
+            // and a slice of the NEXT stage's dequantisation (with 16 token blocks: A columns and
+            // table addresses in steps 0-3 of a stage, table reads in steps 1-4, scale MFMAs in step
+            // 3, one pair of weights converted in each of steps 5-12; with 8 blocks the same slices at
+            // twice the density), so that vector and LDS instructions issue in the shadow of MFMAs of
             // the same wave and every result is asked for several MFMAs before it is needed.  Only
             // stage 0 of a tile is dequantised in the open (its A tile arrives with the barrier).
+            // The tile loads for the next K tile also ride on the steps, one each: issued in one
+            // burst at the head of the tile they cost 3-4 % more.
+            constexpr int H = MB / 8;                           // 1 or 2
+            constexpr int NPS = 4 / H;                          // table addresses (and table reads) per step
+            constexpr int kScaleStep = H == 2 ? 3 : 2;
+            constexpr int kConv0 = H == 2 ? 5 : 4, CPS = 2 / H; // first converting step, weight pairs per step
             constexpr int kAhead = 3;
-            constexpr int kLoad0 = 6;                           // first step of stage 0 that carries a tile load
+            constexpr int kLoad0 = 6, kLoads = 2 * XJ + AQ;      // steps kLoad0 .. of the tile carry its loads
+            static_assert(kLoad0 + kLoads <= 4 * MB, "more tile loads than steps");
+            const bool spread = kt + 1 < kt1 && (kt + 2) * 128 <= K;
             bf16x8 Wc[2], Wn[2];
             bf16x8 Xq[kAhead];
 #pragma unroll
@@ -322,54 +332,57 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
                 f32x4 S0[2], S1[2];
                 const int un = u < 3 ? u + 1 : 3;
 #pragma unroll
-                for (int mb = 0; mb < 16; ++mb) {
-                    const int t = 16 * u + mb;
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int t = MB * u + mb;
                     const bf16x8 Xop = Xq[t % kAhead];
                     acc[0][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wc[0], Xop, acc[0][mb], 0, 0, 0);
                     acc[1][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wc[1], Xop, acc[1][mb], 0, 0, 0);
-                    if (u == 0 && mb >= kLoad0 && mb < kLoad0 + 9 && kt + 1 < kt1 && (kt + 2) * 128 <= K) {
-                        // one tile load of the next K tile per step (8 of X, 1 of A): issued in one
-                        // burst at the head of the tile they cost 3-4 % more
-                        const int i = mb - kLoad0, kbn = (kt + 1) * 128;
-                        if (i < 8) lds_direct_16(Xtile + kbn + 16 * (i & 1), xo[i >> 1], xl0 + (p ^ 1) * XBUF + (i & 1) * (XBUF / 2) + (i >> 1) * (TPP * 128));
-                        else if (xm0 < a.r) lds_direct_16(a.A + kbn, ao[0], al0 + (p ^ 1) * ABUF);
+                    if (t >= kLoad0 && t < kLoad0 + kLoads && spread) {
+                        const int i = t - kLoad0, kbn = (kt + 1) * 128;
+                        if (i < 2 * XJ) {
+                            if (!(BM % TPP != 0 && xt0 + TPP * (i >> 1) >= BM))
+                                lds_direct_16(Xtile + kbn + 16 * (i & 1), xo[i >> 1], xl0 + (p ^ 1) * XBUF + (i & 1) * (XBUF / 2) + (i >> 1) * (TPP * 128));
+                        } else if (xm0 + RPP * (i - 2 * XJ) < a.r) {
+                            lds_direct_16(a.A + kbn, ao[i - 2 * XJ], al0 + (p ^ 1) * ABUF + (i - 2 * XJ) * (RPP * 256));
+                        }
                     }
-                    if (t + kAhead < 64) {
+                    if (t + kAhead < 4 * MB) {
                         const int tn = t + kAhead;
-                        Xq[t % kAhead] = *reinterpret_cast<const bf16x8 *>(Xp + (tn % 16) * 2048 + xoff[tn / 16]);
+                        Xq[t % kAhead] = *reinterpret_cast<const bf16x8 *>(Xp + (tn % MB) * 2048 + xoff[tn / MB]);
                     }
                     if (u < 3) {
                         if (mb == 0) { Aop0 = read_Aop(0, 2 * un); Aop1 = read_Aop(0, 2 * un + 1); }
-                        if (mb < 4) {
-                            const int q = mb >> 1;
+                        if (mb < 2 * H) {
 #pragma unroll
-                            for (int e = 0; e < 2; ++e) {
-                                const int pp = 2 * (mb & 1) + e;
+                            for (int e = 0; e < NPS; ++e) {
+                                const int lin = mb * NPS + e, q = lin >> 2, pp = lin & 3;
                                 ad[q][pp] = (pair_index<BITS>(cw[q], 4 * un + pp) << 5) + lutoff;
                             }
                         }
-                        if (mb >= 1 && mb < 5) {
-                            const int j = mb - 1, q = j >> 1;
+                        if (mb >= 1 && mb < 1 + 2 * H) {
 #pragma unroll
-                            for (int e = 0; e < 2; ++e) {
-                                const int pp = 2 * (j & 1) + e;
+                            for (int e = 0; e < NPS; ++e) {
+                                const int lin = (mb - 1) * NPS + e, q = lin >> 2, pp = lin & 3;
                                 lv[q][pp] = lds_load_u32(ad[q][pp]);
                             }
                         }
-                        if (mb == 3) {
+                        if (mb == kScaleStep) {
 #pragma unroll
                             for (int q = 0; q < 2; ++q) {
                                 S0[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop0, Bop[q][0], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
                                 S1[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop1, Bop[q][0], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
                             }
                         }
-                        if (mb >= 5 && mb < 13) {
-                            const int j = mb - 5, q = j >> 2, pp = j & 3;
-                            const f16x2 h = __builtin_bit_cast(f16x2, lv[q][pp]);
-                            const float s0 = pp < 2 ? S0[q][2 * pp] : S1[q][2 * pp - 4];
-                            const float s1 = pp < 2 ? S0[q][2 * pp + 1] : S1[q][2 * pp - 3];
-                            Wn[q][2 * pp] = (__bf16)__builtin_fmaf((float)h[0], s0, 0.0f);
-                            Wn[q][2 * pp + 1] = (__bf16)__builtin_fmaf((float)h[1], s1, 0.0f);
+                        if (mb >= kConv0 && mb < kConv0 + 8 / CPS) {
+#pragma unroll
+                            for (int e = 0; e < CPS; ++e) {
+                                const int j = (mb - kConv0) * CPS + e, q = j >> 2, pp = j & 3;
+                                const f16x2 h = __builtin_bit_cast(f16x2, lv[q][pp]);
+                                const float s0 = pp < 2 ? S0[q][2 * pp] : S1[q][2 * pp - 4];
+                                const float s1 = pp < 2 ? S0[q][2 * pp + 1] : S1[q][2 * pp - 3];
+                                Wn[q][2 * pp] = (__bf16)__builtin_fmaf((float)h[0], s0, 0.0f);
+                                Wn[q][2 * pp + 1] = (__bf16)__builtin_fmaf((float)h[1], s1, 0.0f);
+                            }
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -510,19 +523,18 @@ static PfPlan pf_plan(const MatmulProblem &p)
     int s = 1;
     if (d.ss == 1) {
         // Candidates (tokens x rows of a tile, measured time of one K tile of one workgroup):
-        //   256 x 256, eight waves of 32 rows x 256 tokens each    4.5 us   (no weight is dequantised twice
-        //             in a workgroup; before it, waves of 64 rows x 128 tokens took 5.1 us for the same tile)
-        //   256 x 128, eight waves of 32 rows x 128 tokens         3.0 us
-        //   256 x 192, twelve waves (three per SIMD)               3.9 us   no faster per weight, but a row count
-        //             that divides some layers into whole rounds where 256 does not; has to win by 7 %
+        //   256 x 256, eight waves of 32 rows x 256 tokens each    3.75 us   (no weight is dequantised twice
+        //             in a workgroup)
+        //   256 x 128, eight waves of 32 rows x 128 tokens         2.5 us
         //   128 x 128, four waves, and 128 x 256, eight waves      2.3 us, 3.7 us   (up to 128 tokens)
-        // Cost of a candidate: rounds of workgroups over 256 CUs x K tiles per range x that time, plus,
-        // with more than one range, the second kernel's traffic at 4 TB/s and 3 us.
-        struct Cand { int wm, R, wn, mb; double t, handicap; };
-        const Cand cands[5] = {{1, 2, 8, 16, 4.5, 1.0}, {2, 2, 4, 8, 3.0, 1.0}, {2, 2, 6, 8, 3.9, 1.0 / 0.93},
-                               {1, 2, 4, 8, 2.3, 1.0}, {1, 2, 8, 8, 3.7, 1.0}};
+        // (256 x 192 with twelve waves, three per SIMD, was no faster per weight than 256 x 256 and has
+        // been dropped.)  Cost of a candidate: rounds of workgroups over 256 CUs x K tiles per range x
+        // that time, plus, with more than one range, the second kernel's traffic at 4 TB/s and 3 us.
+        struct Cand { int wm, R, wn, mb; double t; };
+        const Cand cands[4] = {{1, 2, 8, 16, 3.75}, {2, 2, 4, 8, 2.5},
+                               {1, 2, 4, 8, 2.3}, {1, 2, 8, 8, 3.7}};
         double best = 1e30;
-        for (int i = 0; i < 5; ++i) {
+        for (int i = 0; i < 4; ++i) {
             const Cand &c = cands[i];
             const int tokens = 16 * c.mb * c.wm;
             if ((tokens == 128) != (p.M <= 128)) continue;
@@ -531,7 +543,6 @@ static PfPlan pf_plan(const MatmulProblem &p)
             const long rounds = (tiles * sc + 255) / 256;
             double cost = (double)rounds * ((ntiles_k + sc - 1) / sc) * c.t;
             if (sc > 1) cost += 3.0 + ((double)sc * 4.0 + 2.0) * p.M * p.N / 4.0e6;
-            cost *= c.handicap;
             if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; d.wn = c.wn; d.mb = c.mb; s = sc; }
         }
     } else {
@@ -591,7 +602,6 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStrea
 #define LORDS_PCASE(B_, S_)                                                                     \
     if (p.bits == B_ && ss == S_) {                                                              \
         if (S_ == 1 && d.mb == 16) e = launch_pf_t<B_, 1, 1, 2, 8, 16>(a, grid, st);               \
-        else if (S_ == 1 && wm == 2 && wn == 6) e = launch_pf_t<B_, 1, 2, 2, 6>(a, grid, st);          \
         else if (S_ == 1 && wm == 2) e = launch_pf_t<B_, 1, 2, 2>(a, grid, st);                   \
         else if (wn == 8) e = launch_pf_t<B_, S_, 1, 2, 8>(a, grid, st);                         \
         else e = launch_pf_t<B_, S_, 1, 2>(a, grid, st);                                         \

@@ -137,14 +137,15 @@ constexpr int kFgTile = kFgMC * 512;                                      // byt
 constexpr int kFgLoads = 4;                                               // direct-to-LDS loads per wave and chunk
 constexpr int kFgAST = 520;                                               // bytes per row of the A tile (256 columns + pad)
 
-__device__ __forceinline__ void fg_lds_direct_16(const void *gsrc, void *lds_wave_base)
+__device__ __forceinline__ void fg_lds_direct_16(const void *gbase, uint32_t goff, uint32_t lds_wave_base)
 {
-    // Every active lane fetches 16 bytes from its own address; they land at lds_wave_base + 16*lane
-    // (M0 holds the wave's LDS base).  Written as assembly so that the compiler does not make later
-    // LDS reads wait for these loads; the kernel waits for them itself before a buffer is read.
-    const uint32_t base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(base), "v"(gsrc) : "memory", "m0");
+    // Every active lane fetches 16 bytes from gbase + goff (gbase and lds_wave_base are the same in all
+    // lanes and travel in scalar registers, goff is the lane's own byte offset); they land at
+    // lds_wave_base + 16*lane (M0 holds the wave's LDS base).  Written as assembly so that the compiler
+    // does not make later LDS reads wait for these loads; the kernel waits for them itself before a
+    // buffer is read.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_wave_base), "v"(goff), "s"(gbase) : "memory", "m0");
 }
 
 // Transposing read of 8 consecutive rows of one column block out of a row-major, chunk-swizzled
@@ -152,14 +153,21 @@ __device__ __forceinline__ void fg_lds_direct_16(const void *gsrc, void *lds_wav
 // rows a group of 16 lanes reads, 32 bytes each, fall into different banks): lane (c, g)
 // passes row0 = first row + 8g and col0 = first column of the 16-column block and receives
 // tile[row0 + e][col0 + c], e = 0..7.
+// XOR mask for the 16-byte chunk index of tile row `row`.  A transposing read takes rows 8 g + (c >> 2)
+// (+ 4 for its second half) and 32 bytes of each; the hardware serves lane groups g = 0, 1 together and
+// g = 2, 3 together, so rows that differ in bits 0-1 or in bit 3 must fall into different 32-byte
+// segments of the 256-byte bank window (2.8 cycles per wave instruction; with (row & 7) << 1, which
+// separates rows 0-7 only, the two groups collide: 4.8).
+__device__ __forceinline__ int fg_swz(int row) { return ((row & 3) << 1) | (((row >> 3) & 1) << 3); }
+
 template <int ROWB>
 __device__ __forceinline__ bf16x8 fg_tr_read(const unsigned char *tile, int row0, int col0, int c)
 {
     typedef __attribute__((__vector_size__(8 * sizeof(short)))) short s16x8;
     const int col = col0 + 4 * (c & 3);
     const int ra = row0 + (c >> 2), rb = ra + 4;
-    const unsigned char *p0 = tile + ra * ROWB + (((col >> 3) ^ ((ra & 7) << 1)) << 4) + ((col & 7) << 1);
-    const unsigned char *p1 = tile + rb * ROWB + (((col >> 3) ^ ((rb & 7) << 1)) << 4) + ((col & 7) << 1);
+    const unsigned char *p0 = tile + ra * ROWB + (((col >> 3) ^ fg_swz(ra)) << 4) + ((col & 7) << 1);
+    const unsigned char *p1 = tile + rb * ROWB + (((col >> 3) ^ fg_swz(rb)) << 4) + ((col & 7) << 1);
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p0);
     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p1);
     return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -191,18 +199,36 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 
     // ---- staging of one chunk of 32 tokens into buffer p: always kFgLoads loads per wave, so that the
     //      loop can wait for "all but the loads of the chunk behind this one" ------------------------------
-    auto stage = [&](int ch, int p) {
-        unsigned char *dYs = smem + p * (2 * kFgTile), *Xs = dYs + kFgTile;
+    // A wave-level load covers two rows of 512 bytes: lane l brings row 2 wave + l / 32 (+ 16 for the
+    // wave's second load) and the 16-byte chunk that belongs into slot l % 32 of that row.  The lane's
+    // byte offsets from the chunk's first token do not change along M and are kept in registers.
+    const int srow = 2 * wave + (lane >> 5);
+    const int sch = (lane & 31) ^ fg_swz(srow);              // (rows 16 apart share their swizzle)
+    const int scoln = min(n0 + 8 * sch, N - 8);              // (columns >= N or K: finite filler, masked later)
+    const int scolk = min(k0 + 8 * sch, K - 8);
+    uint32_t offY[2], offX[2];
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {                        // a wave-level load covers two rows of 512 bytes
-            const int row = 16 * q + 2 * wave + (lane >> 5), slot = lane & 31;
-            const int ch16 = slot ^ ((row & 7) << 1);                            // the 16-byte chunk that sits in this slot
-            const int n = min(n0 + 8 * ch16, N - 8);         // (columns >= N or K: finite filler, masked later)
-            const int k = min(k0 + 8 * ch16, K - 8);
-            const int m = min(ch * kFgMC + row, M - 1);      // (tokens >= M: a copy of the last token; its X row is zeroed before use)
-            fg_lds_direct_16(a.dY + (size_t)m * N + n, dYs + (16 * q + 2 * wave) * 512);
-            fg_lds_direct_16(a.X + (size_t)m * K + k, Xs + (16 * q + 2 * wave) * 512);
+    for (int q = 0; q < 2; ++q) {
+        offY[q] = ((uint32_t)(srow + 16 * q) * (uint32_t)N + (uint32_t)scoln) * 2u;
+        offX[q] = ((uint32_t)(srow + 16 * q) * (uint32_t)K + (uint32_t)scolk) * 2u;
+    }
+    const uint32_t sl0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(smem + 2 * wave * 512));
+    // load i (0..3) of chunk ch into buffer p: i / 2 picks the wave's rows, i % 2 dY or X
+    auto stage_one = [&](int ch, int p, int i) {
+        const int q = i >> 1;
+        const uint32_t l = sl0 + p * (2 * kFgTile) + (i & 1) * kFgTile + q * (16 * 512);
+        const uint16_t *b = (i & 1) ? a.X + (size_t)ch * kFgMC * K : a.dY + (size_t)ch * kFgMC * N;
+        if ((ch + 1) * kFgMC <= M) {
+            fg_lds_direct_16(b, (i & 1) ? offX[q] : offY[q], l);
+        } else {
+            // tokens >= M: a copy of the last token; its X row is zeroed before use
+            const uint32_t m = (uint32_t)(min(ch * kFgMC + srow + 16 * q, M - 1) - ch * kFgMC);
+            fg_lds_direct_16(b, (i & 1) ? (m * (uint32_t)K + (uint32_t)scolk) * 2u : (m * (uint32_t)N + (uint32_t)scoln) * 2u, l);
         }
+    };
+    auto stage = [&](int ch, int p) {
+#pragma unroll
+        for (int i = 0; i < kFgLoads; ++i) stage_one(ch, p, i);
     };
     // ---- the packed codes of the tile (256 rows x 8*BITS dwords), requested now with coalesced loads and
     //      parked in registers over the token loop; they go to LDS, half a tile at a time, afterwards ------
@@ -365,7 +391,7 @@ __global__ __launch_bounds__(kFgThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                         const s16x4v aop = *reinterpret_cast<const s16x4v *>(As + (16 * jb + c) * kFgAST + (128 * h + kl) * 2);
                         dBacc[jb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, aop, dBacc[jb], 0, 0, 0);
                     }
-                    *reinterpret_cast<s16x4v *>(Ps + nl * 256 + (((kl >> 3) ^ ((nl & 7) << 1)) << 4) + ((kl & 7) << 1)) = pb;
+                    *reinterpret_cast<s16x4v *>(Ps + nl * 256 + (((kl >> 3) ^ fg_swz(nl)) << 4) + ((kl & 7) << 1)) = pb;
                 }
                 // dB partial of this half tile: lane (c, g) holds rows 4g+e of rank entry 16 jb + c
 #pragma unroll

@@ -36,7 +36,7 @@ COLD_BYTES = 600e6             # rotate through at least this many weight bytes
 # kernels, each scaled by what the same counter reads for a plain 256 MiB -> 256 MiB elementwise kernel
 # (--calibrate-copy): FETCH_SIZE x 1.9998, WRITE_SIZE x 1.0.  The summary is under profiles/.
 DECODE_TRAFFIC_BYTES = int((16462.8 * 1.9998 + 960.5) * 1024)
-PREFILL_TRAFFIC_BYTES = int((136883.1 * 1.9998 + 57344.0) * 1024)
+PREFILL_TRAFFIC_BYTES = int((136891.1 * 1.9998 + 57344.0) * 1024)
 
 
 def algorithmic_bytes(M, N, K, r, bits, factor_bytes=2, y_bytes=4):

@@ -55,6 +55,14 @@ the chain rule gives
                     P  = C[q] (.) G     (gradient w.r.t. S = B A)
                     dB = P A^T   [N, r],        dA = B^T P   [r, K]
 
+Mixed-precision stacks (Sec. 4.2, ultra-low-bit setting): the code width is chosen per layer,
+
+  mixed_schedule     4-bit levels for a leading share of the layers, 2-bit levels for the rest
+  average_bits       the bit label of such a stack (3 / 2.5 / 2.25 in Table 3)
+  factor_parameters  sum of r (N + K) over matrices at the budget-matched rank (#Float in Table 3)
+
+pinned by the table's own labels and #Float column (tests/test_oracle_mixed_pins.py).
+
 Pins (see tests/test_oracle_pins.py): hand-derived byte vectors for the
 unpacker, scalar brute force on tiny inputs, the block-wise special case
 (paper Sec. 3.1), identity activations, the rank-1 closed form, the all-ones
@@ -186,6 +194,30 @@ def equivalent_rank(N: int, K: int, group: int) -> int:
     """Rank whose factor budget r (N + K) matches the block-wise scale budget
     N K / group: r = floor(N K / (group (N + K)))  (Sec. 3.2; Appendix A)."""
     return (int(N) * int(K)) // (int(group) * (int(N) + int(K)))
+
+
+def mixed_schedule(n_layers: int, fraction_first: float, bits_first: int = 4, bits_rest: int = 2) -> list:
+    """Code width of every layer of a mixed-precision stack: the first `fraction_first` of the layers
+    (a count rounded half up) use `bits_first`, the remainder `bits_rest` (Sec. 4.2, ultra-low-bit
+    setting: 4-bit levels for the first 50 % / 25 % / 12.5 % of the layers and 2-bit levels for the
+    rest give the 3 / 2.5 / 2.25-bit rows of Table 3)."""
+    n_layers = int(n_layers)
+    n_first = int(np.floor(float(fraction_first) * n_layers + 0.5))
+    n_first = max(0, min(n_layers, n_first))
+    return [int(bits_first)] * n_first + [int(bits_rest)] * (n_layers - n_first)
+
+
+def average_bits(layer_bits) -> float:
+    """Mean code width over layers of equal size (the bit label of a row of Table 3)."""
+    layer_bits = list(layer_bits)
+    return float(sum(layer_bits)) / float(len(layer_bits))
+
+
+def factor_parameters(shapes, group: int) -> int:
+    """Floating-point parameters of the factors over a list of (N, K) matrices, each at the rank
+    that matches a block-wise scale budget of block size `group`: sum of r (N + K)  (Sec. 3.2; the
+    #Float column of Table 3 counts these over all linear layers of the model)."""
+    return sum(equivalent_rank(N, K, group) * (int(N) + int(K)) for N, K in shapes)
 
 
 # ----------------------------------------------------------------------------

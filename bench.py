@@ -193,44 +193,64 @@ def bench_other(args, L, li, torch):
     return out
 
 
-def bench_block(args, L, li, torch):
-    """Context figure: the seven linear layers of one Llama-3-8B-shaped block at one token and at two, as four
-    calls (q/k/v in one launch, o, gate/up with its activation, down), 4-bit codes of rank 32, rotating
-    through enough blocks that no launch finds its weights in the last-level cache."""
-    K0, I = 4096, 14336
-    bits, r = 4, 32
-    shapes = {"q": (4096, K0), "k": (1024, K0), "v": (1024, K0), "o": (4096, 4096), "gate": (I, K0), "up": (I, K0),
-              "down": (K0, I)}
-    per_block = sum(n * k for n, k in shapes.values()) * bits // 8
+BLOCK_SHAPES = {"q": (4096, 4096), "k": (1024, 4096), "v": (1024, 4096), "o": (4096, 4096),
+                "gate": (14336, 4096), "up": (14336, 4096), "down": (4096, 14336)}
+
+
+def make_blocks(bits, li, torch, L, seed0):
+    """Enough Llama-3-8B-shaped blocks (seven linear layers each, rank 32) at one code width that no launch
+    finds its weights in the last-level cache.  Returns (blocks, activations by width, codebook, bytes of codes)."""
+    per_block = sum(n * k for n, k in BLOCK_SHAPES.values()) * bits // 8
     nblocks = int(-(-COLD_BYTES // per_block))
-    bf16_tensor = L.bf16_from_bits
-    blocks, xs = [], {}
+    blocks, xs, codebook = [], {}, None
     for b in range(nblocks):
         layers = {}
-        for j, (name, (n, k)) in enumerate(shapes.items()):
-            cs = li.make_case("qproj_4b", M=2, N=n, K=k, seed=5000 + 7 * b + j)
-            xs.setdefault(k, bf16_tensor(cs.X_bf16))
-            layers[name] = (torch.from_numpy(cs.codes).cuda(), bf16_tensor(cs.B_bf16), bf16_tensor(cs.A_bf16))
+        for j, (name, (n, k)) in enumerate(BLOCK_SHAPES.items()):
+            cs = li.make_case("qproj_4b", M=2, N=n, K=k, bits=bits, seed=seed0 + 7 * b + j)
+            xs.setdefault(k, L.bf16_from_bits(cs.X_bf16))
+            layers[name] = (torch.from_numpy(cs.codes).cuda(), L.bf16_from_bits(cs.B_bf16), L.bf16_from_bits(cs.A_bf16))
             codebook = torch.from_numpy(cs.codebook.copy()).cuda()
         blocks.append(layers)
+    return blocks, xs, codebook, per_block
+
+
+def run_block(L, ly, codebook, bits, M, X4, X14, outs, r=32):
+    """The seven linear layers of one block as four calls: q/k/v in one launch, o, gate/up with its activation, down."""
+    K0, I = 4096, 14336
+    Yq, Yk, Yv, Yo, H, Yd = outs
+    q, k, v = ly["q"], ly["k"], ly["v"]
+    L.lords_matmul_batched(X4, [q[0], k[0], v[0]], codebook, [q[1], k[1], v[1]], [q[2], k[2], v[2]],
+                           [Yq, Yk, Yv], [4096, 1024, 1024], M, K0, r, bits)
+    o = ly["o"]
+    L.lords_matmul(X4, o[0], codebook, o[1], o[2], Yo, M, 4096, K0, r, bits)
+    g, u = ly["gate"], ly["up"]
+    L.lords_gate_up(X4, g[0], g[1], g[2], u[0], u[1], u[2], codebook, H, M, I, K0, r, bits)
+    d = ly["down"]
+    L.lords_matmul(X14, d[0], codebook, d[1], d[2], Yd, M, K0, I, r, bits)
+
+
+def block_outputs(M, torch):
+    f32 = dict(dtype=torch.float32, device="cuda")
+    return (torch.zeros((M, 4096), **f32), torch.zeros((M, 1024), **f32), torch.zeros((M, 1024), **f32),
+            torch.zeros((M, 4096), **f32), torch.zeros((M, 14336), **f32), torch.zeros((M, 4096), **f32))
+
+
+def bench_block(args, L, li, torch):
+    """Context figures.  (1) The seven linear layers of one Llama-3-8B-shaped block at one token and at two, as
+    four calls, 4-bit codes of rank 32, rotating through enough blocks that no launch finds its weights in the
+    last-level cache.  (2) A 32-block stack at one token under the mixed-precision schedules of the paper's
+    ultra-low-bit setting (4-bit levels in the first 1/2, 1/4, 1/8 of the blocks, 2-bit levels in the rest:
+    3, 2.5 and 2.25 bits on average), widths from lords_mixed_schedule, beside the uniform 4-bit stack."""
+    bits, r = 4, 32
+    blocks, xs, codebook, per_block = make_blocks(bits, li, torch, L, 5000)
+    nblocks = len(blocks)
+    X4, X14 = xs[4096], xs[14336]        # stand-ins for the activations that feed each layer (shapes only)
     out = []
     for M in (1, 2):
-        f32 = dict(dtype=torch.float32, device="cuda")
-        Yq, Yk, Yv = torch.zeros((M, 4096), **f32), torch.zeros((M, 1024), **f32), torch.zeros((M, 1024), **f32)
-        Yo, H, Yd = torch.zeros((M, 4096), **f32), torch.zeros((M, I), **f32), torch.zeros((M, K0), **f32)
-        X4, X14 = xs[K0], xs[I]          # stand-ins for the activations that feed each layer (shapes only)
+        outs = block_outputs(M, torch)
 
         def step(i):
-            ly = blocks[i % nblocks]
-            q, k, v = ly["q"], ly["k"], ly["v"]
-            L.lords_matmul_batched(X4, [q[0], k[0], v[0]], codebook, [q[1], k[1], v[1]], [q[2], k[2], v[2]],
-                                   [Yq, Yk, Yv], [4096, 1024, 1024], M, K0, r, bits)
-            o = ly["o"]
-            L.lords_matmul(X4, o[0], codebook, o[1], o[2], Yo, M, 4096, K0, r, bits)
-            g, u = ly["gate"], ly["up"]
-            L.lords_gate_up(X4, g[0], g[1], g[2], u[0], u[1], u[2], codebook, H, M, I, K0, r, bits)
-            d = ly["down"]
-            L.lords_matmul(X14, d[0], codebook, d[1], d[2], Yd, M, K0, I, r, bits)
+            run_block(L, blocks[i % nblocks], codebook, bits, M, X4, X14, outs, r)
 
         _, ev_ms, mode, _ = time_steps(step, 60, 6, torch, use_graph=not args.no_graph)
         us = ev_ms * 1e3 / 60
@@ -239,6 +259,33 @@ def bench_block(args, L, li, torch):
                     "us_per_step": us, "launch_mode": mode, "value": per_block / us / 1e3, "unit": "GB/s (codes only)",
                     "frac_of_hbm_peak": per_block / us / 1e3 / HBM_PEAK_GBS,
                     "ms_for_32_blocks": us * 32 / 1e3})
+
+    # (2) mixed-precision stacks
+    blocks2, _, codebook2, per_block2 = make_blocks(2, li, torch, L, 7000)
+    pools = {4: (blocks, codebook, per_block), 2: (blocks2, codebook2, per_block2)}
+    outs = block_outputs(1, torch)
+    n_layers = 32
+    base_ms = None
+    for label, fraction in (("4", 1.0), ("3", 0.5), ("2.5", 0.25), ("2.25", 0.125)):
+        widths, avg = L.lords_mixed_schedule(n_layers, fraction, 4, 2)
+
+        def step(i, widths=widths):
+            seen = {4: 0, 2: 0}
+            for w in widths:
+                pool, cb, _ = pools[w]
+                run_block(L, pool[(i * n_layers + seen[w]) % len(pool)], cb, w, 1, X4, X14, outs, r)
+                seen[w] += 1
+
+        _, ev_ms, mode, _ = time_steps(step, 8, 2, torch, use_graph=not args.no_graph)
+        ms = ev_ms / 8
+        nbytes = sum(pools[w][2] for w in widths)
+        if base_ms is None:
+            base_ms = ms
+        out.append({"workload": f"decode M=1, 32-block stack (224 linear layers, rank 32), {label} bits on average "
+                                f"({widths.count(4)} blocks at 4 bits, then {widths.count(2)} at 2 bits)",
+                    "average_bits": avg, "ms_per_token": ms, "launch_mode": mode, "value": nbytes / ms / 1e6,
+                    "unit": "GB/s (codes only)", "frac_of_hbm_peak": nbytes / ms / 1e6 / HBM_PEAK_GBS,
+                    "speedup_over_4_bits": base_ms / ms})
     return out
 
 

@@ -76,6 +76,20 @@ size_t lords_row_bytes(int K, int bits);
  * floor(NK / (group (N+K)))  (Sec. 3.2; Appendix A, Table 7).  -1 on bad input. */
 long lords_equivalent_rank(long N, long K, long group);
 
+/* Code width of every layer of a mixed-precision stack (Sec. 4.2, ultra-low-bit setting; Table 3):
+ * the first floor(fraction_first * n_layers + 1/2) layers use bits_first, the remaining ones
+ * bits_rest.  With 4 and 2 bits, fractions 1/2, 1/4 and 1/8 give the 3-, 2.5- and 2.25-bit
+ * configurations.  Host-side only: the widths are then passed, layer by layer, as the `bits` of
+ * the other calls (the matrices of one lords_matmul_batched / lords_gate_up call belong to one
+ * layer and share one width).
+ *   layer_bits  out  host array of n_layers ints, caller-owned
+ *   avg_bits    out  host, may be NULL: mean width over the layers (layers of equal size)
+ * Errors: LORDS_ERR_NULL (layer_bits), LORDS_ERR_BITS (either width not 2, 3 or 4),
+ * LORDS_ERR_SHAPE (n_layers < 1, fraction_first negative or not a number; fractions above 1
+ * mean every layer). */
+int lords_mixed_schedule(int n_layers, double fraction_first, int bits_first, int bits_rest,
+                         int *layer_bits, double *avg_bits);
+
 /* Bit-unpack only: idx[n*K + k] = code k of row n.  (The storage side of Q; Alg. 1's
  * quantised matrix holds one level per element.)
  *   codes  in   N x K*bits/8 bytes

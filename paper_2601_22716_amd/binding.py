@@ -14,7 +14,7 @@ LORDS_PATH_AUTO, LORDS_PATH_DECODE, LORDS_PATH_PREFILL = 0, 1, 2
 STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LORDS_ERR_SHAPE",
                 4: "LORDS_ERR_ALIGN", 5: "LORDS_ERR_DTYPE", 6: "LORDS_ERR_LAUNCH", 7: "LORDS_ERR_UNSUPPORTED"}
 
-EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank",
+EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank", "lords_mixed_schedule",
            "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex",
            "lords_matmul_batched", "lords_gate_up", "lords_transpose_codes", "lords_backward_input", "lords_backward_factors"]
 
@@ -50,6 +50,8 @@ def library():
         lib.lords_row_bytes.argtypes = [ci, ci]
         lib.lords_equivalent_rank.restype = cl
         lib.lords_equivalent_rank.argtypes = [cl, cl, cl]
+        lib.lords_mixed_schedule.restype = ci
+        lib.lords_mixed_schedule.argtypes = [ci, ctypes.c_double, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_double)]
         lib.lords_unpack.restype = ci
         lib.lords_unpack.argtypes = [vp, vp, ci, ci, ci, vp]
         lib.lords_dequant.restype = ci
@@ -132,6 +134,15 @@ def lords_row_bytes(K: int, bits: int) -> int:
 
 def lords_equivalent_rank(N: int, K: int, group: int) -> int:
     return int(library().lords_equivalent_rank(N, K, group))
+
+
+def lords_mixed_schedule(n_layers: int, fraction_first: float, bits_first: int = 4, bits_rest: int = 2):
+    """Returns (list of per-layer code widths, their mean)."""
+    out = (ctypes.c_int * max(int(n_layers), 1))()
+    avg = ctypes.c_double(0.0)
+    _check(library().lords_mixed_schedule(n_layers, fraction_first, bits_first, bits_rest, out, ctypes.byref(avg)),
+           "lords_mixed_schedule")
+    return [int(v) for v in out[:n_layers]], float(avg.value)
 
 
 def lords_unpack(codes, idx, N: int, K: int, bits: int, stream=None) -> None:

@@ -170,6 +170,23 @@ long lords_equivalent_rank(long N, long K, long group)
     return (long)(num / den);
 }
 
+int lords_mixed_schedule(int n_layers, double fraction_first, int bits_first, int bits_rest,
+                         int *layer_bits, double *avg_bits)
+{
+    if (!layer_bits) return LORDS_ERR_NULL;
+    if (bad_bits(bits_first) || bad_bits(bits_rest)) return LORDS_ERR_BITS;
+    if (n_layers < 1 || !(fraction_first >= 0.0)) return LORDS_ERR_SHAPE;
+    const double x = fraction_first * (double)n_layers + 0.5;
+    const int n_first = x >= (double)n_layers ? n_layers : (int)x;      // x >= 0: truncation is the floor
+    long sum = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        layer_bits[l] = l < n_first ? bits_first : bits_rest;
+        sum += layer_bits[l];
+    }
+    if (avg_bits) *avg_bits = (double)sum / (double)n_layers;
+    return LORDS_OK;
+}
+
 int lords_unpack(const void *codes, uint8_t *idx, int N, int K, int bits, void *stream)
 {
     if (!codes || !idx) return LORDS_ERR_NULL;

@@ -54,6 +54,33 @@ def test_equivalent_rank_matches_table7(golden_dir):
     assert L.lords_equivalent_rank(4096, 4096, 0) == -1
 
 
+def test_mixed_schedule_matches_oracle_and_table3(golden_dir):
+    """Host-side function: compared with the oracle over a grid, and with the paper's bit labels."""
+    import ctypes
+    from oracle import lords_oracle as onp
+    for n in (1, 2, 5, 7, 32, 80):
+        for fr in (0.0, 0.1, 0.125, 0.25, 0.29, 0.3, 0.5, 0.77, 1.0, 1.5):
+            for b1, b2 in ((4, 2), (3, 2), (4, 3), (2, 4)):
+                bits, avg = L.lords_mixed_schedule(n, fr, b1, b2)
+                want = onp.mixed_schedule(n, fr, b1, b2)
+                assert bits == want, (n, fr, b1, b2)
+                assert avg == onp.average_bits(want)
+    with open(os.path.join(golden_dir, "table3_mixed_bits.txt")) as f:
+        rows = [t.split() for t in f if t.startswith("mix")]
+    assert len(rows) == 3
+    for _, label, fraction in rows:
+        assert L.lords_mixed_schedule(32, float(fraction))[1] == float(label)
+    f = L.library().lords_mixed_schedule
+    out = (ctypes.c_int * 4)()
+    assert f(4, 0.5, 4, 2, None, None) == 1
+    assert f(4, 0.5, 5, 2, out, None) == 2
+    assert f(4, 0.5, 4, 1, out, None) == 2
+    assert f(0, 0.5, 4, 2, out, None) == 3
+    assert f(4, -0.1, 4, 2, out, None) == 3
+    assert f(4, float("nan"), 4, 2, out, None) == 3
+    assert f(4, 0.5, 4, 2, out, None) == 0 and list(out) == [4, 4, 2, 2]     # avg_bits may be NULL
+
+
 def test_unpack_argument_checks():
     f = L.library().lords_unpack
     assert f(None, P, 4, 64, 4, None) == 1

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     constexpr int BN = 16 * R * WN, BM = 16 * MB * WM, NT = 64 * WN * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
     constexpr int RPP = 4 * WN * WM;                           // tile rows one staging pass of the workgroup covers
     constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
-    constexpr bool kPipe = (R == 2 && SS == 1 && (MB == 8 || MB == 16));   // ranks up to 32: pipelined K loop
+    constexpr bool kPipe = (R == 2 && SS <= 2 && (MB == 8 || MB == 16));   // ranks up to 64: pipelined K loop
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char *Xs = smem;                                   // [2][BM][256 B]
     unsigned char *As = smem + 2 * XBUF;                        // [2][RP][256 B]
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
         };
 
         if constexpr (kPipe) {
-            // Ranks up to 32: the K tile as one software pipeline of 4 MB steps (4 stages x MB token
+            // Ranks up to 64: the K tile as one software pipeline of 4 MB steps (4 stages x MB token
             // blocks), pinned step by step with scheduling barriers.  A step is the two product MFMAs
             // of one token block; riding on it are the X operand read of the block kAhead steps later
             // and a slice of the NEXT stage's dequantisation (with 16 token blocks: A columns and
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                bf16x8 Aop0, Aop1;
+                bf16x8 Aop0[SS], Aop1[SS];
                 uint32_t ad[2][4], lv[2][4];
                 f32x4 S0[2], S1[2];
                 const int un = u < 3 ? u + 1 : 3;
@@ -351,7 +351,10 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
                         Xq[t % kAhead] = *reinterpret_cast<const bf16x8 *>(Xp + (tn % MB) * 2048 + xoff[tn / MB]);
                     }
                     if (u < 3) {
-                        if (mb == 0) { Aop0 = read_Aop(0, 2 * un); Aop1 = read_Aop(0, 2 * un + 1); }
+                        if (mb == 0) {
+#pragma unroll
+                            for (int ss = 0; ss < SS; ++ss) { Aop0[ss] = read_Aop(ss, 2 * un); Aop1[ss] = read_Aop(ss, 2 * un + 1); }
+                        }
                         if (mb < 2 * H) {
 #pragma unroll
                             for (int e = 0; e < NPS; ++e) {
@@ -369,8 +372,13 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
                         if (mb == kScaleStep) {
 #pragma unroll
                             for (int q = 0; q < 2; ++q) {
-                                S0[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop0, Bop[q][0], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-                                S1[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop1, Bop[q][0], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                                S0[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+                                S1[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                                for (int ss = 0; ss < SS; ++ss) {
+                                    S0[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop0[ss], Bop[q][ss], S0[q], 0, 0, 0);
+                                    S1[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Aop1[ss], Bop[q][ss], S1[q], 0, 0, 0);
+                                }
                             }
                         }
                         if (mb >= kConv0 && mb < kConv0 + 8 / CPS) {

@@ -78,11 +78,11 @@ template <int BITS, int SS, int WM, int R, int WN = 4, int MB = 8>
 __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN * WM / 4, WN * WM / 4))) void prefill_kernel(PrefillArgs a)
 {
     constexpr int BN = 16 * R * WN, BM = 16 * MB * WM, NT = 64 * WN * WM, RP = 32 * SS, NL = 1 << BITS, NE = 1 << (2 * BITS);
-    constexpr int RPP = 4 * WN * WM;                           // tile rows one staging pass of the workgroup covers
+    constexpr int RPP = 4 * WN * WM;                           // A tile rows one staging pass of the workgroup covers
     constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
     constexpr bool kPipe = (R == 2 && SS <= 2 && (MB == 8 || MB == 16));   // ranks up to 64: pipelined K loop
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *Xs = smem;                                   // [2][BM][256 B]
+    unsigned char *Xs = smem;                                   // [2][2 halves][BM][128 B]
     unsigned char *As = smem + 2 * XBUF;                        // [2][RP][256 B]
     uint32_t *lut = reinterpret_cast<uint32_t *>(smem + 2 * XBUF + 2 * ABUF);   // [NE][8]
 

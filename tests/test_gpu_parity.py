@@ -173,12 +173,12 @@ def test_matmul_prefill_with_k_ranges(gpu, bits, N, K, r, M, dt):
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
-def test_matmul_prefill_192_row_tiles(gpu, bits):
-    """A shape that the GEMM serves with its twelve-wave, 192-row tiles (6144 rows and 2048 tokens are
-    one round of 256 such tiles); rows sampled across all six row groups of a tile and the ragged end."""
+def test_matmul_prefill_many_tiles_short_k(gpu, bits):
+    """Many output tiles over a short K (6136 rows x 2048 tokens, four K tiles): every tile's prologue and
+    epilogue with hardly a loop between them; rows sampled across the row groups of a tile and the ragged end."""
     import paper_2601_22716_amd as L
     N, K, r, M = 6144 - 8, 512, 32, 2048
-    say(f"prefill 192-row tiles bits={bits}")
+    say(f"prefill many tiles, short K, bits={bits}")
     cs = li.make_case("tiny", M=M, N=N, K=K, bits=bits, r=r, factor_dtype="bf16", seed=62, signed_factors=True)
     Y = gpu.DeviceCase(cs).matmul(path=L.LORDS_PATH_PREFILL)
     assert np.isfinite(Y).all()

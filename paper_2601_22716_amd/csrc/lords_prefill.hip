@@ -589,7 +589,7 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStrea
 {
     const PfPlan d = pf_plan(p);
     if (d.splits > 1 && !workspace) return hipErrorInvalidValue;
-    const int ss = d.ss, wm = d.wm, R = d.R, wn = d.wn;
+    const int ss = d.ss, wm = d.wm, wn = d.wn;
     PrefillArgs a;
     a.X = (const uint16_t *)p.X;
     a.codes = (const uint8_t *)p.codes;

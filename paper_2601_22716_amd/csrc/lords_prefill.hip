@@ -82,7 +82,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     constexpr int XBUF = BM * 256, ABUF = RP * 256;            // bytes per buffer
     constexpr bool kPipe = (R == 2 && SS <= 2 && (MB == 8 || MB == 16));   // ranks up to 64: pipelined K loop
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *Xs = smem;                                   // [2][2 halves][BM][128 B]
+    unsigned char *Xs = smem;                                   // [2][BM / 4 token groups][1 KB]
     unsigned char *As = smem + 2 * XBUF;                        // [2][RP][256 B]
     uint32_t *lut = reinterpret_cast<uint32_t *>(smem + 2 * XBUF + 2 * ABUF);   // [NE][8]
 
@@ -141,23 +141,25 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     }
 
     // ---- staging of one K tile into buffer p (direct to LDS) and of its codes into registers ---------
-    // X tile in LDS: two halves of 64 columns, each [BM tokens][128 B]; a wave load fills 8 token
-    // rows of one half, lane l bringing token l / 8 and landing in slot l % 8 of its row.  Slot
-    // s of token t of half h holds the 8 columns 32 gg + 8 uu + 16 h with 4 uu + gg = s ^ (t & 7):
+    // X tile in LDS: groups of four tokens, 1 KB each = [2 halves of 64 columns][4 tokens][128 B]; a
+    // wave load fills one group, lane l landing in half l / 32, token (l / 8) % 4, slot l % 8, and
+    // fetches whole 256-byte token rows from global memory (8 full cache lines per wave load).
+    // Slot s of token t of half h holds the 8 columns 32 gg + 8 uu + 16 h with 4 uu + gg = s ^ (t & 7):
     // the four 16-byte chunks that the four lane groups g of an MFMA b-operand want at stage
     // u = 2 h + uu then sit in one 64-byte quarter-row, XOR-swizzled by token, and a wave's operand
-    // read (16 tokens x 4 chunks) is free of bank conflicts (rows of 256 bytes, one per token,
-    // cost 8.2 cycles per read however they were swizzled, these rows 5.0).
+    // read (16 tokens x 4 chunks) is free of bank conflicts (5.0 cycles per wave instruction; rows
+    // of 256 bytes, one per token, cost 8.2 however they were swizzled).
     // A tile: row-major, 256 B per rank row, lane (wave, l) fetches chunk (l & 15) ^ (row & 15) of
     // row 4 wave + l / 16 (+ RPP per pass).  The byte offsets of a lane's chunks from the tile's
     // first element do not change along K and are kept in registers.
     constexpr int AQ = (RP + RPP - 1) / RPP;
-    constexpr int TPP = 8 * WN * WM, XJ = (BM + TPP - 1) / TPP;   // tokens per staging pass, passes
+    constexpr int TPP = 4 * WN * WM, XJ = BM / TPP;             // tokens per staging pass, passes
+    static_assert(BM % TPP == 0, "a staging pass covers whole token groups");
     const int xm0 = 4 * wave + (lane >> 4);
     const int xkc = (lane & 15) ^ (xm0 & 15);
-    const int xt0 = 8 * wave + (lane >> 3);
-    const int xv = (lane & 7) ^ (lane >> 3);
-    const int xkcol = 32 * (xv & 3) + 8 * (xv >> 2);
+    const int xt0 = 4 * wave + ((lane >> 3) & 3);             // the lane's token in pass 0 (then + TPP per pass)
+    const int xv = (lane & 7) ^ (xt0 & 7);                    // (TPP is a multiple of 8: the same in every pass)
+    const int xkcol = 32 * (xv & 3) + 8 * (xv >> 2) + 16 * (lane >> 5);
     uint32_t xo[XJ], ao[AQ];
 #pragma unroll
     for (int j = 0; j < XJ; ++j) {
@@ -173,26 +175,18 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
         const int kb = kt * 128;
         if (kb + 128 <= K) {
 #pragma unroll
-            for (int j = 0; j < XJ; ++j) {
-                if (BM % TPP != 0 && xt0 + TPP * j >= BM) continue;   // (whole waves: a wave's eight tokens lie on one side)
-                lds_direct_16(Xtile + kb, xo[j], xl0 + p * XBUF + j * (TPP * 128));
-                lds_direct_16(Xtile + kb + 16, xo[j], xl0 + p * XBUF + XBUF / 2 + j * (TPP * 128));
-            }
+            for (int j = 0; j < XJ; ++j) lds_direct_16(Xtile + kb, xo[j], xl0 + p * XBUF + j * (TPP * 256));
 #pragma unroll
             for (int q = 0; q < AQ; ++q)
                 if (xm0 + RPP * q < a.r) lds_direct_16(a.A + kb, ao[q], al0 + p * ABUF + q * (RPP * 256));
         } else {
             // ragged last tile: X chunks beyond K are fetched from further left (any finite data will
             // do: their weights are zero), A columns beyond K of a live rank row must read as zero
+            {
+                const int over = kb + xkcol - (K - 8);
+                const uint32_t back = over > 0 ? 2u * over : 0u;
 #pragma unroll
-            for (int j = 0; j < XJ; ++j) {
-                if (BM % TPP != 0 && xt0 + TPP * j >= BM) continue;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int over = kb + 16 * h + xkcol - (K - 8);
-                    const uint32_t back = over > 0 ? 2u * over : 0u;
-                    lds_direct_16(Xtile + kb + 16 * h, xo[j] - back, xl0 + p * XBUF + h * (XBUF / 2) + j * (TPP * 128));
-                }
+                for (int j = 0; j < XJ; ++j) lds_direct_16(Xtile + kb, xo[j] - back, xl0 + p * XBUF + j * (TPP * 256));
             }
 #pragma unroll
             for (int q = 0; q < AQ; ++q) {
@@ -230,7 +224,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     uint32_t xoff[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-        xoff[u] = (uint32_t)((u >> 1) * (XBUF / 2) + c * 128 + (((4 * (u & 1) + g) ^ (c & 7)) * 16));
+        xoff[u] = (uint32_t)((u >> 1) * 512 + (c >> 2) * 1024 + (c & 3) * 128 + (((4 * (u & 1) + g) ^ (c & 7)) * 16));
 
     const uint32_t lutoff = (uint32_t)(2 * XBUF + 2 * ABUF) + (uint32_t)(lane & 7) * 4u;
 
@@ -241,7 +235,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             if (!kPipe || (kt + 2) * 128 > K) stage(kt + 1, p ^ 1);
             load_codes(kt + 1, cwn);
         }
-        const unsigned char *Xp = Xs + p * XBUF + wm * (16 * MB * 128);
+        const unsigned char *Xp = Xs + p * XBUF + wm * (16 * MB * 256);
         const unsigned char *Ap = As + p * ABUF;
 
         // a-operand of scale MFMA t: 8 rank entries of 16 A columns, transposed out of LDS
@@ -315,13 +309,13 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             constexpr int kScaleStep = H == 2 ? 3 : 2;
             constexpr int kConv0 = H == 2 ? 5 : 4, CPS = 2 / H; // first converting step, weight pairs per step
             constexpr int kAhead = 3;
-            constexpr int kLoad0 = 6, kLoads = 2 * XJ + AQ;      // steps kLoad0 .. of the tile carry its loads
+            constexpr int kLoad0 = 6, kLoads = XJ + AQ;      // steps kLoad0 .. of the tile carry its loads
             static_assert(kLoad0 + kLoads <= 4 * MB, "more tile loads than steps");
             const bool spread = kt + 1 < kt1 && (kt + 2) * 128 <= K;
             bf16x8 Wc[2], Wn[2];
             bf16x8 Xq[kAhead];
 #pragma unroll
-            for (int i = 0; i < kAhead; ++i) Xq[i] = *reinterpret_cast<const bf16x8 *>(Xp + i * 2048 + xoff[0]);
+            for (int i = 0; i < kAhead; ++i) Xq[i] = *reinterpret_cast<const bf16x8 *>(Xp + i * 4096 + xoff[0]);
             __builtin_amdgcn_sched_barrier(0);
             dequant_stage(0, Wc);
             __builtin_amdgcn_sched_barrier(0);
@@ -339,16 +333,15 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
                     acc[1][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Wc[1], Xop, acc[1][mb], 0, 0, 0);
                     if (t >= kLoad0 && t < kLoad0 + kLoads && spread) {
                         const int i = t - kLoad0, kbn = (kt + 1) * 128;
-                        if (i < 2 * XJ) {
-                            if (!(BM % TPP != 0 && xt0 + TPP * (i >> 1) >= BM))
-                                lds_direct_16(Xtile + kbn + 16 * (i & 1), xo[i >> 1], xl0 + (p ^ 1) * XBUF + (i & 1) * (XBUF / 2) + (i >> 1) * (TPP * 128));
-                        } else if (xm0 + RPP * (i - 2 * XJ) < a.r) {
-                            lds_direct_16(a.A + kbn, ao[i - 2 * XJ], al0 + (p ^ 1) * ABUF + (i - 2 * XJ) * (RPP * 256));
+                        if (i < XJ) {
+                            lds_direct_16(Xtile + kbn, xo[i], xl0 + (p ^ 1) * XBUF + i * (TPP * 256));
+                        } else if (xm0 + RPP * (i - XJ) < a.r) {
+                            lds_direct_16(a.A + kbn, ao[i - XJ], al0 + (p ^ 1) * ABUF + (i - XJ) * (RPP * 256));
                         }
                     }
                     if (t + kAhead < 4 * MB) {
                         const int tn = t + kAhead;
-                        Xq[t % kAhead] = *reinterpret_cast<const bf16x8 *>(Xp + (tn % MB) * 2048 + xoff[tn / MB]);
+                        Xq[t % kAhead] = *reinterpret_cast<const bf16x8 *>(Xp + (tn % MB) * 4096 + xoff[tn / MB]);
                     }
                     if (u < 3) {
                         if (mb == 0) {
@@ -409,7 +402,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
                 bf16x8 Xq[kXAhead];
 #pragma unroll
                 for (int i = 0; i < kXAhead; ++i)
-                    Xq[i] = *reinterpret_cast<const bf16x8 *>(Xp + i * 2048 + xoff[u]);
+                    Xq[i] = *reinterpret_cast<const bf16x8 *>(Xp + i * 4096 + xoff[u]);
                 __builtin_amdgcn_sched_barrier(0);
                 dequant_stage(u, W);
 #pragma unroll
@@ -420,7 +413,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
                         acc[rho][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W[rho], Xop, acc[rho][mb], 0, 0, 0);
                     if (mb + kXAhead < MB) {
                         Xq[mb % kXAhead] =
-                            *reinterpret_cast<const bf16x8 *>(Xp + (mb + kXAhead) * 2048 + xoff[u]);
+                            *reinterpret_cast<const bf16x8 *>(Xp + (mb + kXAhead) * 4096 + xoff[u]);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }

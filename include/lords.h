@@ -20,18 +20,31 @@
  *    [bits*k, bits*k+bits).  4 bits: two codes per byte, low nibble first; 2 bits:
  *    four per byte from the low end; 3 bits: 32 codes per 12 bytes.
  *  - K must be a multiple of 32 (whole 12-byte groups at 3 bits, whole 16-byte
- *    loads at 4 bits).  N >= 1, r >= 1 and M >= 0 are otherwise arbitrary.
+ *    loads at 4 bits).  N >= 1 and M >= 0 are otherwise arbitrary; ranks r >= 1 up to 6144 (bf16
+ *    factors) or 2048 (fp32 factors) run (LORDS_ERR_UNSUPPORTED beyond).  Calls with further
+ *    restrictions say so: lords_transpose_codes / lords_backward_input (N % 32 == 0),
+ *    lords_backward_factors (N % 8 == 0, r <= 64), lords_block_init (K % r == 0).
+ *  - The level table is narrowed to 16 bits inside the multiplying kernels (bf16 at one and two
+ *    tokens, fp16 otherwise): levels must lie within fp16 range (|c| <= 65504, not below 6e-8
+ *    unless zero); the tables of the paper (Sec. 3.1: INT4, NF4) are far inside it.
  *  - Factors B and A are both bf16 or both fp32 (`factor_dtype`); X is bf16.
  *  - Outputs are overwritten entirely (no accumulate).
  *  - Errors are returned, never thrown.  Arguments are checked in the fixed order
  *    NULL -> BITS -> SHAPE -> ALIGN -> DTYPE before anything is launched, so a bad
  *    call touches no memory.  A launch failure reported by the runtime gives
  *    LORDS_ERR_LAUNCH.
- *  - The multiplying entry points (lords_matmul*, lords_gate_up, lords_backward_*)
- *    use a per-device workspace that the library allocates on first need, grows
- *    when a call needs more (it then waits for the device to go idle first) and
- *    keeps until the process ends; calls that overlap in time on one device must
- *    therefore not be issued from different streams.
+ *  - Workspace.  Some kernels meet through device memory (exchange slots, arrival tickets, fp32
+ *    partial sums).  lords_matmul_ws takes that memory from the caller and then neither allocates,
+ *    frees nor synchronises.  The other
+ *    multiplying entry points (lords_matmul, lords_matmul_ex, lords_matmul_batched, lords_gate_up,
+ *    lords_backward_*) use a per-device workspace of the library's own: allocated on first need;
+ *    when a call needs more, a larger block is allocated (its front is zeroed, which waits for the
+ *    device once) and the old one is kept, so that work already queued and HIP graphs captured
+ *    earlier stay valid; it is released when the process ends.  Such a growth is refused with
+ *    LORDS_ERR_LAUNCH while `stream` is being captured: warm a shape up once before capturing it.
+ *    Calls that share one workspace and overlap in time on one device race; issue them from one
+ *    stream (or give every stream its own workspace through lords_matmul_ws).  The library keeps no
+ *    other state; entry points may be called from several host threads.
  */
 #ifndef LORDS_H
 #define LORDS_H
@@ -51,16 +64,21 @@ typedef enum {
     LORDS_ERR_ALIGN = 4,   /* a pointer is not 16-byte aligned */
     LORDS_ERR_DTYPE = 5,   /* unknown lords_dtype / lords_path value */
     LORDS_ERR_LAUNCH = 6,  /* the HIP runtime refused the launch or a workspace allocation */
-    LORDS_ERR_UNSUPPORTED = 7 /* the forced path cannot run this shape */
+    LORDS_ERR_UNSUPPORTED = 7, /* the forced path cannot run this shape */
+    LORDS_ERR_WORKSPACE = 8   /* lords_matmul_ws: workspace missing or too small */
 } lords_status;
 
 typedef enum { LORDS_BF16 = 0, LORDS_F32 = 1 } lords_dtype;
 
-/* Which kernel family lords_matmul_ex runs.  AUTO picks by M. */
+/* Which kernel family lords_matmul_ex runs.  AUTO picks by M (up to 16 tokens: DECODE). */
 typedef enum {
     LORDS_PATH_AUTO = 0,
-    LORDS_PATH_DECODE = 1,   /* memory-bound small-M path (16 tokens per pass over the codes) */
-    LORDS_PATH_PREFILL = 2   /* bf16 MFMA GEMM with the dequantised tile as operand */
+    LORDS_PATH_DECODE = 1,   /* memory-bound small-M family, the kernel picked by M: GEMV where it applies, else SMALLM */
+    LORDS_PATH_PREFILL = 2,  /* bf16 MFMA GEMM with the dequantised tile as operand */
+    LORDS_PATH_MFMA = 2,     /* (the same) */
+    LORDS_PATH_GEMV = 3,     /* the one-/two-token kernel alone: M <= 2, bf16 factors, rank <= 64 (two tokens: <= 32 at
+                                most shapes), LORDS_ERR_UNSUPPORTED otherwise */
+    LORDS_PATH_SMALLM = 4    /* the few-token kernels alone (16 tokens per pass over the codes), any M */
 } lords_path;
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -132,7 +150,9 @@ int lords_block_init(const void *W, const float *codebook, void *B, void *A,
  *   X   in   M x K bf16
  *   Y   out  M x N, dtype `y_dtype`; accumulation is fp32.
  * M == 0 returns LORDS_OK without launching.  M <= 16 takes the memory-bound
- * decode kernels (one pass over the codes for all tokens), larger M the MFMA GEMM
+ * decode kernels (one pass over the codes for all tokens; at one and two tokens the
+ * regrouped sum y = rowsum(B (.) (C[Q] (A (.) x)^T)), which never forms the scale per
+ * element), larger M the MFMA GEMM
  * (which cuts K into up to four ranges, added in a fixed order, when there are too
  * few tiles to fill the chip); results are run-to-run deterministic.
  */
@@ -148,6 +168,27 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook,
                     lords_dtype factor_dtype, lords_dtype y_dtype, void *stream,
                     lords_path path);
 
+/* ---- Workspace owned by the caller ----
+ * lords_workspace_bytes: bytes lords_matmul_ws needs for this problem on `path` (the front region
+ *   included); 0 if an argument is invalid or the rank unsupported.  Host-side only, no GPU call.
+ * lords_workspace_zero_bytes: the leading bytes of a workspace that must be ZERO when it is first
+ *   handed over (exchange slots and arrival tickets).  Every call leaves them at zero; the rest of
+ *   the workspace is scratch whose contents do not matter.  If a launch ever fails or a kernel is
+ *   aborted, zero them again before the next call.
+ * lords_matmul_ws: lords_matmul_ex with the workspace passed in.  It performs no allocation, no
+ *   free and no synchronisation (safe under stream capture; a captured graph refers to the caller's
+ *   buffer).  `workspace` is a device pointer, 256-byte aligned, of at least
+ *   lords_workspace_bytes(...) bytes (LORDS_ERR_WORKSPACE if NULL or smaller; a workspace sized for
+ *   the largest problem serves them all).  Two calls that overlap in time must not share one.
+ */
+size_t lords_workspace_bytes(int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_path path);
+size_t lords_workspace_zero_bytes(void);
+int lords_matmul_ws(const void *X, const void *codes, const float *codebook,
+                    const void *B, const void *A, void *Y,
+                    int M, int N, int K, int r, int bits,
+                    lords_dtype factor_dtype, lords_dtype y_dtype, void *stream,
+                    lords_path path, void *workspace, size_t workspace_bytes);
+
 /* Several quantised matrices applied to the SAME activations: Y[l] = X W_hat[l]^T for l = 0 .. L-1.
  * Every linear layer of a transformer block carries its own codes and factors (Sec. 4.3; module
  * list of Table 7), and the query/key/value projections (and gate/up) read one input; at one token a
@@ -158,7 +199,9 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook,
  *                            returns.
  *   K, r, bits, codebook, factor_dtype are shared by all L matrices.  1 <= L <= 8 (LORDS_ERR_SHAPE).
  * With M <= 16 and bf16 factors of rank <= 64 all matrices are served by one kernel launch;
- * other cases run matrix by matrix.  Each Y[l] equals what lords_matmul gives for that matrix.
+ * other cases run matrix by matrix.  Each Y[l] is the same sum lords_matmul computes for that matrix
+ * (bit-identical from three tokens on; at one and two tokens the single-matrix call may run another
+ * kernel, with another rounding of the same sum).
  */
 int lords_matmul_batched(const void *X, const void *const *codes, const float *codebook,
                          const void *const *B, const void *const *A, void *const *Y, const int *N,
@@ -210,7 +253,7 @@ int lords_backward_input(const void *dY, const void *codes_t, const float *codeb
  *   dY, X    in   M x N and M x K, bf16
  *   dB, dA   out  N x r and r x K, fp32 (overwritten, not accumulated into)
  * Needs N % 8 == 0 and r <= 64 (LORDS_ERR_UNSUPPORTED otherwise); M == 0 gives zeros.
- * Uses the per-device workspace: (ceil(K/128) N r + ceil(N/256) r K) * 4 bytes of partial results.
+ * Uses the library's per-device workspace: (2 ceil(K/256) N r + ceil(N/256) r K) * 4 bytes of partial results.
  */
 int lords_backward_factors(const void *dY, const void *X, const void *codes, const float *codebook,
                            const void *B, const void *A, float *dB, float *dA,

@@ -10,12 +10,15 @@ _LIB_PATH = os.path.join(_HERE, "liblords.so")
 _lib = None
 
 LORDS_BF16, LORDS_F32 = 0, 1
-LORDS_PATH_AUTO, LORDS_PATH_DECODE, LORDS_PATH_PREFILL = 0, 1, 2
+LORDS_PATH_AUTO, LORDS_PATH_DECODE, LORDS_PATH_PREFILL, LORDS_PATH_GEMV, LORDS_PATH_SMALLM = 0, 1, 2, 3, 4
+LORDS_PATH_MFMA = LORDS_PATH_PREFILL
 STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LORDS_ERR_SHAPE",
-                4: "LORDS_ERR_ALIGN", 5: "LORDS_ERR_DTYPE", 6: "LORDS_ERR_LAUNCH", 7: "LORDS_ERR_UNSUPPORTED"}
+                4: "LORDS_ERR_ALIGN", 5: "LORDS_ERR_DTYPE", 6: "LORDS_ERR_LAUNCH", 7: "LORDS_ERR_UNSUPPORTED",
+                8: "LORDS_ERR_WORKSPACE"}
 
 EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank", "lords_mixed_schedule",
            "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex",
+           "lords_workspace_bytes", "lords_workspace_zero_bytes", "lords_matmul_ws",
            "lords_matmul_batched", "lords_gate_up", "lords_transpose_codes", "lords_backward_input", "lords_backward_factors"]
 
 
@@ -60,6 +63,12 @@ def library():
         lib.lords_matmul.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
         lib.lords_matmul_ex.restype = ci
         lib.lords_matmul_ex.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci]
+        lib.lords_matmul_ws.restype = ci
+        lib.lords_matmul_ws.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp, ctypes.c_size_t]
+        lib.lords_workspace_bytes.restype = ctypes.c_size_t
+        lib.lords_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci]
+        lib.lords_workspace_zero_bytes.restype = ctypes.c_size_t
+        lib.lords_workspace_zero_bytes.argtypes = []
         lib.lords_quantize.restype = ci
         lib.lords_quantize.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
         lib.lords_block_init.restype = ci
@@ -173,6 +182,24 @@ def lords_matmul_ex(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int,
                     path: int = LORDS_PATH_AUTO, stream=None) -> None:
     _check(library().lords_matmul_ex(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
                                      _dtype_code(B), _dtype_code(Y), _stream(stream), path), "lords_matmul_ex")
+
+
+def lords_workspace_bytes(M: int, N: int, K: int, r: int, bits: int, factor_dtype: int = LORDS_BF16,
+                          path: int = LORDS_PATH_AUTO) -> int:
+    return int(library().lords_workspace_bytes(M, N, K, r, bits, factor_dtype, path))
+
+
+def lords_workspace_zero_bytes() -> int:
+    return int(library().lords_workspace_zero_bytes())
+
+
+def lords_matmul_ws(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int, workspace,
+                    path: int = LORDS_PATH_AUTO, stream=None) -> None:
+    """`workspace`: a device byte tensor, at least lords_workspace_bytes(...) long, its first
+    lords_workspace_zero_bytes() bytes zero when first handed over."""
+    _check(library().lords_matmul_ws(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
+                                     _dtype_code(B), _dtype_code(Y), _stream(stream), path, _ptr(workspace),
+                                     workspace.numel() * workspace.element_size()), "lords_matmul_ws")
 
 
 def _ptr_array(tensors):

@@ -11,45 +11,69 @@ bool fused_rank_supported(int r, bool f32fact);
 
 namespace {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;   // 0.2.0
 constexpr int kMaxDevices = 16;
 
-// Per-device fp32 workspace for the split-K partial sums of the small-M path.
-// Grown on demand, never shrunk, released only at process exit by the runtime.
-struct Workspace {
-    void *ptr = nullptr;
+// Layout of a workspace, the library's own or a caller's:
+//   [0, kZeroBytes)                         exchange slots of the one-/two-token kernel   } zero when handed over,
+//   [kZeroBytes, kZeroBytes + kTicketBytes) arrival tickets of the few-token kernels      } left at zero by every call
+//   [kFront, ...)                           fp32 partial sums and other scratch, contents of no interest between calls
+constexpr size_t kFront = lords::kZeroBytes + lords::kTicketBytes;
+
+struct WsView {
+    unsigned char *base = nullptr;     // start of the zero region
+    size_t bytes = 0;
+    void *zeroed() const { return base; }
+    void *tickets() const { return base ? base + lords::kZeroBytes : nullptr; }    // what the few-token kernels call "workspace"
+    void *scratch() const { return base ? base + kFront : nullptr; }
+};
+
+// The library's own per-device workspace (convenience entry points).  A block that has been handed
+// out is never freed or moved: work already queued, and HIP graphs captured earlier, keep using it.
+// When a call needs more, a new block is allocated (and its front zeroed, which waits for the
+// device); while the stream is being captured that is refused instead.
+struct OwnWorkspace {
+    unsigned char *ptr = nullptr;
     size_t bytes = 0;
 };
-Workspace g_ws[kMaxDevices];
+OwnWorkspace g_ws[kMaxDevices];
 std::mutex g_ws_mutex;
 
-int get_workspace(size_t need, void **out)
+int get_workspace(size_t need, void *stream, WsView *out)
 {
-    *out = nullptr;
-    if (need == 0) return LORDS_OK;
+    *out = WsView{};
+    if (need < kFront) need = kFront;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LORDS_ERR_LAUNCH;
     std::lock_guard<std::mutex> lock(g_ws_mutex);
-    Workspace &w = g_ws[dev];
+    OwnWorkspace &w = g_ws[dev];
     if (w.bytes < need) {
-        // Work already queued may still read the old buffer: wait for it before freeing.
-        if (w.ptr) {
-            if (hipDeviceSynchronize() != hipSuccess) return LORDS_ERR_LAUNCH;
-            (void)hipFree(w.ptr);
-            w.ptr = nullptr;
-            w.bytes = 0;
-        }
-        size_t want = need < (size_t)(8u << 20) ? (size_t)(8u << 20) : need;
-        if (hipMalloc(&w.ptr, want) != hipSuccess) { w.ptr = nullptr; return LORDS_ERR_LAUNCH; }
-        // arrival tickets at the front of the buffer must start at zero; kernels leave them at zero
-        if (hipMemset(w.ptr, 0, want) != hipSuccess || hipDeviceSynchronize() != hipSuccess) return LORDS_ERR_LAUNCH;
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing((hipStream_t)stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return LORDS_ERR_LAUNCH;
+        size_t want = need < (size_t)(16u << 20) ? (size_t)(16u << 20) : need + need / 2;
+        unsigned char *fresh = nullptr;
+        if (hipMalloc((void **)&fresh, want) != hipSuccess) return LORDS_ERR_LAUNCH;
+        if (hipMemset(fresh, 0, kFront) != hipSuccess || hipDeviceSynchronize() != hipSuccess) return LORDS_ERR_LAUNCH;
+        w.ptr = fresh;          // (the previous block stays allocated: it may still be in use)
         w.bytes = want;
     }
-    *out = w.ptr;
+    out->base = w.ptr;
+    out->bytes = w.bytes;
     return LORDS_OK;
 }
 
-// Which small-M kernel takes a problem, and the workspace it asks for.
+// One token: the regrouped kernel of lords_gemv.hip wherever it takes the shape.  Two tokens: the same
+// kernel up to 32 M weights, the few-token kernel above (measured: 4096 x 4096 8.8 against 10.1 us,
+// 14336 x 4096 16.2 against 15.4 us).
+bool use_gemv(const lords::MatmulProblem &p, lords_path path)
+{
+    if (path == LORDS_PATH_SMALLM) return false;
+    if (path == LORDS_PATH_GEMV) return lords::decode_gemv_supported(p);
+    if (p.M == 2 && (long)p.N * p.K > (32L << 20)) return false;
+    return lords::decode_gemv_supported(p);
+}
+
+// Which few-token kernel takes a problem, and the scratch it asks for behind the tickets.
 enum DecodeKind { kOne, kFew, kFast, kGeneral };
 DecodeKind decode_kind(const lords::MatmulProblem &p)
 {
@@ -58,60 +82,67 @@ DecodeKind decode_kind(const lords::MatmulProblem &p)
     if (lords::decode_fast_supported(p)) return kFast;
     return kGeneral;
 }
-size_t decode_need(const lords::MatmulProblem &p)
+size_t decode_scratch(const lords::MatmulProblem &p)
 {
+    size_t with_tickets;
     switch (decode_kind(p)) {
-        case kOne: return lords::decode_m1_workspace_bytes(p);
-        case kFew: return lords::decode_mx_workspace_bytes(p);
-        case kFast: return lords::decode_fast_workspace_bytes(p);
-        default: return lords::kTicketBytes + lords::decode_workspace_bytes(p);
+        case kOne: with_tickets = lords::decode_m1_workspace_bytes(p); break;
+        case kFew: with_tickets = lords::decode_mx_workspace_bytes(p); break;
+        case kFast: with_tickets = lords::decode_fast_workspace_bytes(p); break;
+        default: return lords::decode_workspace_bytes(p);
     }
+    return with_tickets > lords::kTicketBytes ? with_tickets - lords::kTicketBytes : 0;
 }
+inline bool is_decode(lords_path path) { return path == LORDS_PATH_DECODE || path == LORDS_PATH_GEMV || path == LORDS_PATH_SMALLM; }
 inline lords_path resolve_path(lords_path path, int M)
 {
     return path == LORDS_PATH_AUTO ? ((M <= 16) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL) : path;   // measured cross-over
 }
 
-// Workspace for one checked problem on `path` (already resolved), plus `extra` bytes behind it that
-// are left to the caller (*extra_ptr).
-int plan_workspace(const lords::MatmulProblem &p, lords_path path, size_t extra, void **ws, void **extra_ptr)
+// Bytes of workspace (front included) one checked problem needs on `path` (already resolved).
+size_t matmul_need(const lords::MatmulProblem &p, lords_path path)
 {
-    // (prefill: the tickets at the front are not used, but stay reserved)
-    size_t own = path == LORDS_PATH_DECODE ? decode_need(p)
-               : (lords::prefill_fast_supported(p) && lords::prefill_fast_workspace_bytes(p))
-                     ? lords::kTicketBytes + lords::prefill_fast_workspace_bytes(p) : 0;
-    // the front of the buffer holds the arrival tickets of the small-M kernels and must stay zero
-    // between calls: a caller's bytes never start inside it, whatever this problem itself needs
-    if (extra && own < lords::kTicketBytes) own = lords::kTicketBytes;
-    const size_t own_al = (own + 255) & ~(size_t)255;
-    const int rc = get_workspace(own_al + extra, ws);
-    if (rc == LORDS_OK && extra_ptr) *extra_ptr = (unsigned char *)*ws + own_al;
-    return rc;
+    size_t scratch = 0;
+    if (is_decode(path)) scratch = use_gemv(p, path) ? 0 : decode_scratch(p);
+    else if (lords::prefill_fast_supported(p)) scratch = lords::prefill_fast_workspace_bytes(p);
+    return kFront + ((scratch + 255) & ~(size_t)255);
 }
 
-int launch_matmul(const lords::MatmulProblem &p, lords_path path, void *ws, void *stream)
+int launch_matmul(const lords::MatmulProblem &p, lords_path path, const WsView &ws, void *stream)
 {
     hipError_t e;
-    if (path == LORDS_PATH_DECODE) {
-        switch (decode_kind(p)) {
-            case kOne: e = lords::launch_decode_m1(p, ws, (hipStream_t)stream); break;
-            case kFew: e = lords::launch_decode_mx(p, ws, (hipStream_t)stream); break;
-            case kFast: e = lords::launch_decode_fast(p, ws, (hipStream_t)stream); break;
-            default: e = lords::launch_decode(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream);
+    if (is_decode(path)) {
+        if (use_gemv(p, path)) e = lords::launch_decode_gemv(p, ws.zeroed(), (hipStream_t)stream);
+        else if (path == LORDS_PATH_GEMV) return LORDS_ERR_UNSUPPORTED;
+        else switch (decode_kind(p)) {
+            case kOne: e = lords::launch_decode_m1(p, ws.tickets(), (hipStream_t)stream); break;
+            case kFew: e = lords::launch_decode_mx(p, ws.tickets(), (hipStream_t)stream); break;
+            case kFast: e = lords::launch_decode_fast(p, ws.tickets(), (hipStream_t)stream); break;
+            default: e = lords::launch_decode(p, ws.scratch(), (hipStream_t)stream);
         }
     } else {
-        e = lords::prefill_fast_supported(p)
-                ? lords::launch_prefill_fast(p, ws ? (unsigned char *)ws + lords::kTicketBytes : nullptr, (hipStream_t)stream)
-                : lords::launch_prefill(p, (hipStream_t)stream);
+        e = lords::prefill_fast_supported(p) ? lords::launch_prefill_fast(p, ws.scratch(), (hipStream_t)stream)
+                                             : lords::launch_prefill(p, (hipStream_t)stream);
     }
     return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+}
+
+// Workspace for one checked problem on `path` (already resolved), plus `extra` bytes behind it that
+// are left to the caller (*extra_ptr).
+int plan_workspace(const lords::MatmulProblem &p, lords_path path, size_t extra, void *stream, WsView *ws, void **extra_ptr)
+{
+    const size_t own = matmul_need(p, path);
+    const int rc = get_workspace(own + extra, stream, ws);
+    if (rc == LORDS_OK && extra_ptr) *extra_ptr = ws->base + own;
+    return rc;
 }
 
 int run_matmul(const lords::MatmulProblem &p, lords_path path, void *stream)
 {
     path = resolve_path(path, p.M);
-    void *ws = nullptr;
-    const int rc = plan_workspace(p, path, 0, &ws, nullptr);
+    if (path == LORDS_PATH_GEMV && !use_gemv(p, path)) return LORDS_ERR_UNSUPPORTED;
+    WsView ws;
+    const int rc = plan_workspace(p, path, 0, stream, &ws, nullptr);
     return rc != LORDS_OK ? rc : launch_matmul(p, path, ws, stream);
 }
 
@@ -121,12 +152,12 @@ int run_batched(const lords::BatchedProblem &bp, void *stream)
     const bool one = lords::decode_m1_batched_supported(bp);
     const bool few = !one && lords::decode_mx_batched_supported(bp);
     if (!one && !few) return -1;
-    void *ws = nullptr;
-    const int rc = get_workspace(one ? lords::decode_m1_batched_workspace_bytes(bp)
-                                     : lords::decode_mx_batched_workspace_bytes(bp), &ws);
+    const size_t with_tickets = one ? lords::decode_m1_batched_workspace_bytes(bp) : lords::decode_mx_batched_workspace_bytes(bp);
+    WsView ws;
+    const int rc = get_workspace(lords::kZeroBytes + with_tickets, stream, &ws);
     if (rc != LORDS_OK) return rc;
-    const hipError_t e = one ? lords::launch_decode_m1_batched(bp, ws, (hipStream_t)stream)
-                             : lords::launch_decode_mx_batched(bp, ws, (hipStream_t)stream);
+    const hipError_t e = one ? lords::launch_decode_m1_batched(bp, ws.tickets(), (hipStream_t)stream)
+                             : lords::launch_decode_mx_batched(bp, ws.tickets(), (hipStream_t)stream);
     return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
 }
 
@@ -134,6 +165,7 @@ inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) &
 inline bool bad_bits(int bits) { return bits != 2 && bits != 3 && bits != 4; }
 inline bool bad_dtype(int d) { return d != LORDS_BF16 && d != LORDS_F32; }
 inline bool bad_nk(int N, int K) { return N < 1 || K < 32 || (K % 32) != 0; }
+inline bool bad_path(int p) { return p < LORDS_PATH_AUTO || p > LORDS_PATH_SMALLM; }
 
 }  // namespace
 
@@ -152,6 +184,7 @@ const char *lords_status_string(int status)
         case LORDS_ERR_DTYPE: return "unknown dtype or path value";
         case LORDS_ERR_LAUNCH: return "the HIP runtime refused a launch or an allocation";
         case LORDS_ERR_UNSUPPORTED: return "this shape is not supported by the requested path";
+        case LORDS_ERR_WORKSPACE: return "the workspace is missing or too small";
         default: return "unknown status";
     }
 }
@@ -242,13 +275,59 @@ int lords_matmul_ex(const void *X, const void *codes, const float *codebook, con
     if (misaligned(X) || misaligned(codes) || misaligned(codebook) || misaligned(B) || misaligned(A) || misaligned(Y))
         return LORDS_ERR_ALIGN;
     if (bad_dtype((int)factor_dtype) || bad_dtype((int)y_dtype)) return LORDS_ERR_DTYPE;
-    if (path != LORDS_PATH_AUTO && path != LORDS_PATH_DECODE && path != LORDS_PATH_PREFILL) return LORDS_ERR_DTYPE;
+    if (bad_path((int)path)) return LORDS_ERR_DTYPE;
     if (M == 0) return LORDS_OK;
     const bool f32fact = factor_dtype == LORDS_F32;
     if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
 
     lords::MatmulProblem p{X, codes, codebook, B, A, Y, M, N, K, r, bits, f32fact, y_dtype == LORDS_F32};
     return run_matmul(p, path, stream);
+}
+
+size_t lords_workspace_zero_bytes(void) { return kFront; }
+
+size_t lords_workspace_bytes(int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_path path)
+{
+    if (bad_bits(bits) || bad_nk(N, K) || r < 1 || M < 0 || bad_dtype((int)factor_dtype) || bad_path((int)path)) return 0;
+    const bool f32fact = factor_dtype == LORDS_F32;
+    if (!lords::fused_rank_supported(r, f32fact)) return 0;
+    if (M == 0) return kFront;
+    lords::MatmulProblem p{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, M, N, K, r, bits, f32fact, true};
+    return matmul_need(p, resolve_path(path, M));
+}
+
+namespace {
+int matmul_in(const void *X, const void *codes, const float *codebook, const void *B, const void *A, void *Y,
+              int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype y_dtype, void *stream,
+              lords_path path, const WsView &ws, bool ws_given)
+{
+    if (!X || !codes || !codebook || !B || !A || !Y) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (bad_nk(N, K) || r < 1 || M < 0) return LORDS_ERR_SHAPE;
+    if (misaligned(X) || misaligned(codes) || misaligned(codebook) || misaligned(B) || misaligned(A) || misaligned(Y))
+        return LORDS_ERR_ALIGN;
+    if (ws_given && (reinterpret_cast<uintptr_t>(ws.base) & 255u) != 0) return LORDS_ERR_ALIGN;
+    if (bad_dtype((int)factor_dtype) || bad_dtype((int)y_dtype)) return LORDS_ERR_DTYPE;
+    if (bad_path((int)path)) return LORDS_ERR_DTYPE;
+    if (M == 0) return LORDS_OK;
+    const bool f32fact = factor_dtype == LORDS_F32;
+    if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
+    lords::MatmulProblem p{X, codes, codebook, B, A, Y, M, N, K, r, bits, f32fact, y_dtype == LORDS_F32};
+    path = resolve_path(path, M);
+    if (path == LORDS_PATH_GEMV && !use_gemv(p, path)) return LORDS_ERR_UNSUPPORTED;
+    if (!ws.base || ws.bytes < matmul_need(p, path)) return LORDS_ERR_WORKSPACE;
+    return launch_matmul(p, path, ws, stream);
+}
+}  // namespace
+
+int lords_matmul_ws(const void *X, const void *codes, const float *codebook, const void *B, const void *A, void *Y,
+                    int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype y_dtype,
+                    void *stream, lords_path path, void *workspace, size_t workspace_bytes)
+{
+    WsView ws;
+    ws.base = (unsigned char *)workspace;
+    ws.bytes = workspace_bytes;
+    return matmul_in(X, codes, codebook, B, A, Y, M, N, K, r, bits, factor_dtype, y_dtype, stream, path, ws, true);
 }
 
 int lords_matmul_batched(const void *X, const void *const *codes, const float *codebook, const void *const *B,
@@ -330,8 +409,9 @@ int lords_gate_up(const void *X, const void *codes_gate, const void *B_gate, con
         const void *Xc = (const unsigned char *)X + (size_t)m0 * K * 2;
         lords::MatmulProblem pg{Xc, codes_gate, codebook, B_gate, A_gate, nullptr, mc, N, K, r, bits, f32fact, true};
         const lords_path path = resolve_path(LORDS_PATH_AUTO, mc);
-        void *ws = nullptr, *tmp = nullptr;
-        int rc = plan_workspace(pg, path, tmp_bytes, &ws, &tmp);
+        WsView ws;
+        void *tmp = nullptr;
+        int rc = plan_workspace(pg, path, tmp_bytes, stream, &ws, &tmp);
         if (rc != LORDS_OK) return rc;
         float *G = (float *)tmp, *U = G + (size_t)mc * N;
         pg.Y = G;
@@ -374,8 +454,9 @@ int lords_backward_input(const void *dY, const void *codes_t, const float *codeb
     const size_t at_bytes = ((size_t)K * r * esz + 255) & ~(size_t)255, bt_bytes = ((size_t)r * N * esz + 255) & ~(size_t)255;
     lords::MatmulProblem p{dY, codes_t, codebook, nullptr, nullptr, dX, M, K, N, r, bits, f32fact, dx_dtype == LORDS_F32};
     const lords_path path = resolve_path(LORDS_PATH_AUTO, M);
-    void *ws = nullptr, *extra = nullptr;
-    const int rc = plan_workspace(p, path, at_bytes + bt_bytes, &ws, &extra);
+    WsView ws;
+    void *extra = nullptr;
+    const int rc = plan_workspace(p, path, at_bytes + bt_bytes, stream, &ws, &extra);
     if (rc != LORDS_OK) return rc;
     void *At = extra, *Bt = (unsigned char *)extra + at_bytes;
     if (lords::launch_transpose_factor(A, At, r, K, f32fact, (hipStream_t)stream) != hipSuccess) return LORDS_ERR_LAUNCH;
@@ -397,11 +478,11 @@ int lords_backward_factors(const void *dY, const void *X, const void *codes, con
         return LORDS_ERR_ALIGN;
     if (bad_dtype((int)factor_dtype)) return LORDS_ERR_DTYPE;
     if (!lords::factor_grad_supported(N, K, r)) return LORDS_ERR_UNSUPPORTED;
-    void *ws = nullptr;
-    const int rc = get_workspace(lords::kTicketBytes + lords::factor_grad_workspace_bytes(N, K, r), &ws);
+    WsView ws;
+    const int rc = get_workspace(kFront + lords::factor_grad_workspace_bytes(N, K, r), stream, &ws);
     if (rc != LORDS_OK) return rc;
     return lords::launch_factor_grad(dY, X, codes, codebook, B, A, dB, dA, M, N, K, r, bits, factor_dtype == LORDS_F32,
-                                     (unsigned char *)ws + lords::kTicketBytes, (hipStream_t)stream) == hipSuccess
+                                     ws.scratch(), (hipStream_t)stream) == hipSuccess
                ? LORDS_OK : LORDS_ERR_LAUNCH;
 }
 

@@ -66,6 +66,15 @@ struct MatmulProblem {
 // The front of the per-device workspace is reserved for arrival tickets (always zero between calls).
 constexpr size_t kTicketBytes = 16384;
 
+// Exchange slots of the one-/two-token kernel (lords_gemv.hip): a region that is zero between calls.
+constexpr size_t kZeroBytes = 4u << 20;
+
+// One- and two-token path (lords_gemv.hip), bf16 factors, ranks up to 64 (one token) / 32 (two).
+// `zeroed`: kZeroBytes of device memory, zero when handed over and left at zero (used only when the
+// layer is wider than one workgroup's column range).
+bool decode_gemv_supported(const MatmulProblem &p);
+hipError_t launch_decode_gemv(const MatmulProblem &p, void *zeroed, hipStream_t st);
+
 // One-token path (lords_decode_m1.hip); same workspace convention as below.
 bool decode_m1_supported(const MatmulProblem &p);
 size_t decode_m1_workspace_bytes(const MatmulProblem &p);

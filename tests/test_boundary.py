@@ -30,8 +30,8 @@ def test_header_and_library_agree():
 
 def test_version_and_strings():
     assert L.lords_version() >= 100
-    for s in range(0, 8):
-        assert L.lords_status_string(s)
+    for s in range(0, 9):
+        assert L.lords_status_string(s) and L.lords_status_string(s) != L.lords_status_string(99)
     assert "unknown" in L.lords_status_string(99)
 
 
@@ -172,7 +172,7 @@ def test_matmul_argument_checks():
     assert f(*a) == 5
     a = list(ok); a[12] = 3
     assert f(*a) == 5
-    assert fx(*ok, 9) == 5
+    assert fx(*ok, 9) == 5 and fx(*ok, -1) == 5
     # M == 0 is a no-op that succeeds without touching the device
     a = list(ok); a[6] = 0
     assert f(*a) == 0
@@ -180,6 +180,60 @@ def test_matmul_argument_checks():
     a = list(ok); a[9] = 100000
     assert f(*a) == 7
 
+
+def test_workspace_queries_and_matmul_ws_argument_checks():
+    """Host-side only: the size queries, and the order NULL -> BITS -> SHAPE -> ALIGN -> DTYPE -> (M == 0) ->
+    UNSUPPORTED -> WORKSPACE of the entry points that take their scratch from the caller or from the
+    library image.  No argument below lets a launch happen."""
+    lib = L.library()
+    zero = L.lords_workspace_zero_bytes()
+    assert zero > 0 and zero % 256 == 0
+    # every problem needs at least the zero front; invalid arguments give 0
+    assert L.lords_workspace_bytes(1, 14336, 4096, 32, 4) >= zero
+    assert L.lords_workspace_bytes(0, 14336, 4096, 32, 4) == zero
+    for bad in ((1, 14336, 4096, 32, 5), (1, 0, 4096, 32, 4), (1, 8, 48, 4, 4), (1, 8, 64, 0, 4), (-1, 8, 64, 4, 4),
+                (1, 8, 64, 100000, 4)):
+        assert L.lords_workspace_bytes(*bad) == 0, bad
+    assert L.lords_workspace_bytes(1, 8, 64, 4, 4, 7) == 0 and L.lords_workspace_bytes(1, 8, 64, 4, 4, 0, 9) == 0
+    # the few-token kernels keep partial sums: more than the front; more tokens, more bytes
+    w4, w16 = (L.lords_workspace_bytes(m, 14336, 4096, 32, 4) for m in (4, 16))
+    assert zero < w4 < w16
+    # forcing a kernel changes the need: the one-token kernel needs the front only
+    assert L.lords_workspace_bytes(1, 14336, 4096, 32, 4, 0, L.LORDS_PATH_GEMV) == zero
+    assert L.lords_workspace_bytes(1, 14336, 4096, 32, 4, 0, L.LORDS_PATH_SMALLM) > zero
+    f = lib.lords_matmul_ws
+    W = 256 * 1024          # an aligned fake workspace address; never dereferenced
+    ok = [P, P, P, P, P, P, 1, 8, 64, 4, 4, 0, 1, None, 0, W, 1 << 30]
+    for i in range(6):
+        a = list(ok); a[i] = None
+        assert f(*a) == 1
+    a = list(ok); a[10] = 0
+    assert f(*a) == 2
+    for i, v in ((6, -1), (7, 0), (8, 16), (9, 0)):
+        a = list(ok); a[i] = v
+        assert f(*a) == 3
+    a = list(ok); a[5] = P + 2
+    assert f(*a) == 4
+    a = list(ok); a[15] = W + 16
+    assert f(*a) == 4
+    a = list(ok); a[11] = 3
+    assert f(*a) == 5
+    a = list(ok); a[14] = 9
+    assert f(*a) == 5
+    a = list(ok); a[6] = 0
+    assert f(*a) == 0
+    a = list(ok); a[9] = 100000
+    assert f(*a) == 7
+    # forced one-token kernel on a shape it does not take (fp32 factors; five tokens)
+    a = list(ok); a[11] = 1; a[14] = L.LORDS_PATH_GEMV
+    assert f(*a) == 7
+    a = list(ok); a[6] = 5; a[14] = L.LORDS_PATH_GEMV
+    assert f(*a) == 7
+    # a missing or short workspace is refused before anything is launched
+    a = list(ok); a[15] = None
+    assert f(*a) == 8
+    a = list(ok); a[16] = L.lords_workspace_zero_bytes() - 1
+    assert f(*a) == 8
 
 def ptr_array(vals):
     arr = (ctypes.c_void_p * len(vals))()

@@ -29,6 +29,20 @@ def say(*a):
     print(*a, flush=True)
     sys.stdout.flush()
 
+def same_as_single(Y, single, M, what):
+    """A batched call against the single-matrix call on the same inputs.  From three tokens on both
+    run the same kernel and sum every row in the same order: bit-identical.  With one or two tokens
+    the single-matrix call takes the regrouped one-/two-token kernel and the batched call the
+    shared-launch kernels: two roundings of the same sums, each inside the gates against the oracle,
+    so they may differ by twice the element-wise gate at most."""
+    if M > 2:
+        np.testing.assert_array_equal(Y, single, err_msg=f"{what}: batched and single-matrix calls differ")
+    elif single.size >= 16:                  # (the rms of a handful of outputs is no scale: those are judged against the oracle only)
+        rms = float(np.sqrt(np.mean(single.astype(np.float64) ** 2))) + 1e-30
+        worst = float(np.abs(Y.astype(np.float64) - single).max()) / rms
+        assert worst <= 2 * Y_MAX_TOL, (what, worst)
+
+
 
 @pytest.fixture(scope="module")
 def gpu():
@@ -98,8 +112,7 @@ def test_batched_one_token(gpu, bits, Ns, K, r):
             mx = float(np.abs(Y - w).max()) / rms_all
             say(f"   matrix {l} ({w.size} outputs): max/rms={mx:.2e}")
             assert mx <= Y_MAX_TOL, (l, mx)
-        single = dev[l].matmul(X=dev[0].X, M=1)
-        np.testing.assert_array_equal(Y, single, err_msg=f"matrix {l}: batched and single-matrix calls differ")
+        same_as_single(Y, dev[l].matmul(X=dev[0].X, M=1), 1, f"matrix {l}")
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
@@ -118,8 +131,7 @@ def test_batched_few_tokens(gpu, bits, M, Ns, K, r):
         else:
             mx = float(np.abs(Y - w).max()) / rms_all
             assert mx <= Y_MAX_TOL, (l, mx)
-        single = dev[l].matmul(X=dev[0].X, M=M)
-        np.testing.assert_array_equal(Y, single, err_msg=f"matrix {l}: batched and single-matrix calls differ")
+        same_as_single(Y, dev[l].matmul(X=dev[0].X, M=M), M, f"matrix {l}")
 
 
 @pytest.mark.parametrize("bits", [2, 4])
@@ -251,7 +263,7 @@ def test_full_size_qkv_sampled(gpu, M):
         rows = np.unique(np.concatenate([[0, c.N - 1], rng.integers(0, c.N, 190)]))
         want = onp.matmul_rows(cases[0].X_f32, c.codes, c.codebook, c.B_f32, c.A_f32, bits, rows)
         check(Y[:, rows], want, f"matrix {l}, {rows.size} rows")
-        np.testing.assert_array_equal(Y, dev[l].matmul(X=dev[0].X, M=M))
+        same_as_single(Y, dev[l].matmul(X=dev[0].X, M=M), M, f"matrix {l}")
 
 
 @pytest.mark.parametrize("M", [1, 2, 16, 2048])

@@ -223,7 +223,8 @@ def test_matmul_blockwise_case(gpu, bits, group):
 # ------------------------------------------------- full-size layers, sampled
 FULL = [
     ("qproj_4b", 1), ("qproj_4b", 4), ("qproj_4b", 16),
-    ("gateup_3b", 1), ("gateup_3b", 16), ("down_3b", 16),
+    ("gateup_3b", 1), ("gateup_3b", 16), ("down_3b", 1), ("down_3b", 16),
+    ("gateup_4b", 2), ("down_4b", 1), ("qproj_4b", 2),
     ("gateup_4b", 1), ("gateup_4b", 2048), ("down_4b", 2048),
     ("l70b_2b", 1), ("l70b_2b", 16), ("l70b_2b", 256), ("l70b_2b", 4096),
 ]
@@ -310,3 +311,74 @@ def test_power_of_two_scaling_is_exact_at_full_size(gpu, name, M):
     #  the last bit, so -X gives -Y only up to rounding)
     Yn = run(-d.X, d.B, d.A)
     assert float((Yn + Y0).abs().max()) <= 1e-5 * float(Y0.abs().max()), "X negated"
+
+
+def sample_rows(N, count, seed):
+    """Row slabs spread over N: the first and last rows, rows on both sides of the 16-row slab and
+    256-row tile edges, and random ones."""
+    rng = np.random.default_rng(seed)
+    fixed = [0, 1, 15, 16, 17, 255, 256, 257, N // 2 - 1, N // 2, N - 257, N - 256, N - 17, N - 16, N - 2, N - 1]
+    rows = np.concatenate([[r for r in fixed if 0 <= r < N], rng.integers(0, N, count)])
+    return np.unique(rows).astype(np.int64)
+
+
+@pytest.mark.parametrize("name", ["qproj_4b", "gateup_3b", "down_3b", "gateup_4b", "down_4b", "l70b_2b"])
+def test_dequant_full_size_sampled(gpu, name):
+    """lords_dequant at the full size of every named layer shape: the whole W finite, and sampled rows
+    within the W gate (relative Frobenius error 1e-3) of the fp64 oracle."""
+    import torch
+    import paper_2601_22716_amd as L
+    say(f"full-size dequant {name}")
+    cs = li.make_case(name, M=1)
+    d = gpu.DeviceCase(cs)
+    W = torch.full((cs.N, cs.K), float("nan"), dtype=torch.float32, device="cuda")
+    L.lords_dequant(d.codes, d.codebook, d.B, d.A, W, cs.N, cs.K, cs.r, cs.bits)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(W).all())
+    rows = sample_rows(cs.N, 120, 31)
+    got = W[torch.from_numpy(rows).cuda()].cpu().numpy()
+    del W
+    want = oc.dequant(cs.codes[rows], cs.codebook, cs.B_f32[rows], cs.A_f32, cs.bits)
+    rf = onp.rel_fro(got, want)
+    say(f"   {rows.size} rows: W rel_fro={rf:.2e}")
+    assert rf <= W_TOL, rf
+
+
+def test_blockwise_equivalence_full_size(gpu):
+    """The block-wise special case at the 70B-shaped layer: 28672 x 8192, 2-bit codes, blocks of 64,
+    written as factors (A = 0/1 block indicator, rank 128, B = block scales; Sec. 3.1, Alg. 1 step 1
+    with block = K/r).  Every scale sum has ONE non-zero term, so the fp32 dequantised weight must be
+    C[q] * s rounded once, to the last bit; the product at one token must sit inside the Y gates."""
+    import torch
+    import paper_2601_22716_amd as L
+    N, K, bits, group = 28672, 8192, 2, 64
+    say(f"full-size block-wise case {N}x{K} bits={bits} group={group}")
+    cs = li.make_blockwise_case(N, K, bits, group, M=1, seed=5)
+    assert cs.r == K // group == 128
+    d = gpu.DeviceCase(cs)
+    rows = sample_rows(N, 100, 57)
+    rows_t = torch.from_numpy(rows).cuda()
+    W = torch.full((N, K), float("nan"), dtype=torch.float32, device="cuda")
+    L.lords_dequant(d.codes, d.codebook, d.B, d.A, W, N, K, cs.r, bits)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(W).all())
+    got = W[rows_t].cpu().numpy()
+    del W
+    q = oc.unpack_codes(cs.codes[rows], K, bits)
+    s = np.repeat(cs.extra["block_scales"][rows], group, axis=1)
+    want = (cs.codebook[q].astype(np.float32) * s.astype(np.float32)).astype(np.float32)
+    np.testing.assert_array_equal(got, want)
+    # the indices themselves, bit-exact
+    idx = torch.full((N, K), 255, dtype=torch.uint8, device="cuda")
+    L.lords_unpack(d.codes, idx, N, K, bits)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(idx[rows_t].cpu().numpy(), q)
+    del idx
+    # the product, one token and a few
+    for M in (1, 16):
+        csm = li.make_blockwise_case(N, K, bits, group, M=M, seed=5)
+        dm = gpu.DeviceCase(csm)
+        Y = dm.matmul()
+        assert np.isfinite(Y).all()
+        wantY = oc.matmul(csm.X_f32, csm.codes, csm.codebook, csm.B_f32, csm.A_f32, bits, rows=rows)
+        check_y(Y[:, rows], wantY, f"block-wise M={M}, {rows.size} rows")

@@ -19,6 +19,20 @@ def say(*a):
     print(*a, flush=True)
     sys.stdout.flush()
 
+def same_as_single(Y, single, M, what):
+    """A batched call against the single-matrix call on the same inputs.  From three tokens on both
+    run the same kernel and sum every row in the same order: bit-identical.  With one or two tokens
+    the single-matrix call takes the regrouped one-/two-token kernel and the batched call the
+    shared-launch kernels: two roundings of the same sums, each inside the gates against the oracle,
+    so they may differ by twice the element-wise gate at most."""
+    if M > 2:
+        np.testing.assert_array_equal(Y, single, err_msg=f"{what}: batched and single-matrix calls differ")
+    elif single.size >= 16:                  # (the rms of a handful of outputs is no scale: those are judged against the oracle only)
+        rms = float(np.sqrt(np.mean(single.astype(np.float64) ** 2))) + 1e-30
+        worst = float(np.abs(Y.astype(np.float64) - single).max()) / rms
+        assert worst <= 2 * Y_MAX_TOL, (what, worst)
+
+
 
 @pytest.fixture(scope="module")
 def gpu():
@@ -44,9 +58,8 @@ def check(Y, want, what, floor_rms=None):
     rf, mx = onp.rel_fro(Y, want), onp.max_abs_over_rms(Y, want)
     say(f"   {what}: rel_fro={rf:.2e} max/rms={mx:.2e}")
     assert np.isfinite(Y).all(), what
-    if want.size >= 64:                       # (a Frobenius ratio over a handful of outputs is one sample)
-        assert rf <= Y_TOL, (what, rf)
-    assert mx <= Y_MAX_TOL * (1.0 if want.size >= 64 else 2.0), (what, mx)
+    assert rf <= Y_TOL, (what, rf)
+    assert mx <= Y_MAX_TOL, (what, mx)
 
 
 @pytest.mark.parametrize("i", range(48))
@@ -82,7 +95,7 @@ def test_shared_input_random_shape(gpu, i):
     want = onp.matmul_batched(cases[0].X_f32, [(c.codes, c.B_f32, c.A_f32) for c in cases], cases[0].codebook, bits)
     for l, (Y, w) in enumerate(zip(Ys, want)):
         got = Y.cpu().numpy()
-        np.testing.assert_array_equal(got, dev[l].matmul(X=dev[0].X, M=M), err_msg=f"matrix {l}")
+        same_as_single(got, dev[l].matmul(X=dev[0].X, M=M), M, f"matrix {l}")
         check(got, w, f"matrix {l}")
 
 

@@ -284,3 +284,40 @@ def test_bf16_rounding_is_nearest_even():
     np.testing.assert_array_equal(li.bf16_bits_to_f32(bits), vals)
     import torch
     np.testing.assert_array_equal(torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy(), vals)
+
+
+# ------------------------------------------------------------------ the gate functions
+def test_gate_functions_hand_values():
+    """rel_fro and max_abs_over_rms carry every parity gate (W within relative Frobenius error 1e-3; Y
+    within relative Frobenius error 5e-3 and |dY| <= 2e-2 rms(Y_oracle), as the benchmark spec words
+    them), so they are pinned to values worked out by hand on a 2 x 2 case.
+        want = [[3, 0], [0, 4]], got = [[3, 1], [1, 2]]:  got - want = [[0, 1], [1, -2]],
+        |got - want|_F = sqrt(0 + 1 + 1 + 4) = sqrt(6),  |want|_F = sqrt(9 + 16) = 5,
+        rms(want) = sqrt((9 + 0 + 0 + 16) / 4) = 2.5,  max|got - want| = 2."""
+    want = np.array([[3.0, 0.0], [0.0, 4.0]])
+    got = np.array([[3.0, 1.0], [1.0, 2.0]])
+    assert onp.rel_fro(got, want) == pytest.approx(math.sqrt(6.0) / 5.0, rel=1e-15)
+    assert onp.max_abs_over_rms(got, want) == pytest.approx(2.0 / 2.5, rel=1e-15)
+    # not symmetric in its arguments: the reference is the second one
+    assert onp.rel_fro(want, got) == pytest.approx(math.sqrt(6.0) / math.sqrt(9 + 1 + 1 + 4), rel=1e-15)
+    assert onp.max_abs_over_rms(want, got) == pytest.approx(2.0 / math.sqrt(15.0 / 4.0), rel=1e-15)
+    # equal arrays, a scaled copy, float32 input widened exactly
+    assert onp.rel_fro(want, want) == 0.0 and onp.max_abs_over_rms(want, want) == 0.0
+    assert onp.rel_fro(1.5 * want, want) == pytest.approx(0.5, rel=1e-15)
+    assert onp.max_abs_over_rms(1.5 * want, want) == pytest.approx(0.5 * 4.0 / 2.5, rel=1e-15)
+    assert onp.rel_fro(got.astype(np.float32), want.astype(np.float32)) == pytest.approx(math.sqrt(6.0) / 5.0, rel=1e-15)
+    # a zero reference: the plain norm / the plain largest deviation (no division by zero)
+    zero = np.zeros((2, 2))
+    assert onp.rel_fro(got, zero) == pytest.approx(math.sqrt(9 + 1 + 1 + 4), rel=1e-15)
+    assert onp.max_abs_over_rms(got, zero) == 3.0
+    assert onp.rel_fro(zero, zero) == 0.0 and onp.max_abs_over_rms(zero, zero) == 0.0
+    # a single wrong element among many: the element-wise gate sees it, the Frobenius gate barely
+    big = np.ones((100, 100))
+    off = big.copy()
+    off[7, 9] = 1.5
+    assert onp.max_abs_over_rms(off, big) == pytest.approx(0.5, rel=1e-15)
+    assert onp.rel_fro(off, big) == pytest.approx(0.5 / 100.0, rel=1e-15)
+    # not-a-number in the result must not pass a "<=" gate
+    bad = got.copy()
+    bad[0, 0] = np.nan
+    assert not (onp.rel_fro(bad, want) <= 1.0) and not (onp.max_abs_over_rms(bad, want) <= 1.0)

@@ -35,7 +35,7 @@
  *    LORDS_ERR_LAUNCH.
  *  - Workspace.  Some kernels meet through device memory (exchange slots, arrival tickets, fp32
  *    partial sums).  lords_matmul_ws takes that memory from the caller and then neither allocates,
- *    frees nor synchronises.  The other
+ *    frees nor synchronises; lords_matmul_noalloc uses an array built into the library.  The other
  *    multiplying entry points (lords_matmul, lords_matmul_ex, lords_matmul_batched, lords_gate_up,
  *    lords_backward_*) use a per-device workspace of the library's own: allocated on first need;
  *    when a call needs more, a larger block is allocated (its front is zeroed, which waits for the
@@ -65,7 +65,7 @@ typedef enum {
     LORDS_ERR_DTYPE = 5,   /* unknown lords_dtype / lords_path value */
     LORDS_ERR_LAUNCH = 6,  /* the HIP runtime refused the launch or a workspace allocation */
     LORDS_ERR_UNSUPPORTED = 7, /* the forced path cannot run this shape */
-    LORDS_ERR_WORKSPACE = 8   /* lords_matmul_ws: workspace missing or too small */
+    LORDS_ERR_WORKSPACE = 8   /* lords_matmul_ws / lords_matmul_noalloc: workspace missing or too small */
 } lords_status;
 
 typedef enum { LORDS_BF16 = 0, LORDS_F32 = 1 } lords_dtype;
@@ -188,6 +188,21 @@ int lords_matmul_ws(const void *X, const void *codes, const float *codebook,
                     int M, int N, int K, int r, int bits,
                     lords_dtype factor_dtype, lords_dtype y_dtype, void *stream,
                     lords_path path, void *workspace, size_t workspace_bytes);
+
+/* For callers that cannot allocate at all (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): lords_matmul (path AUTO) with its scratch in a fixed array that
+ * is part of the library image, lords_noalloc_limit() = 24 MiB per GPU, held until the process
+ * ends.  Calls neither hipMalloc nor hipFree nor any allocating routine, and does not synchronise.
+ * A problem whose lords_workspace_bytes(...) exceeds the limit is refused with LORDS_ERR_WORKSPACE
+ * (every decode shape of the Llama-3-8B/70B layers fits; large prefill shapes whose K range is cut
+ * may not).  All calls on one GPU share the array: calls that overlap in time on one GPU race.  Its
+ * front (slots and tickets) starts at zero and every call leaves it at zero.
+ */
+size_t lords_noalloc_limit(void);
+int lords_matmul_noalloc(const void *X, const void *codes, const float *codebook,
+                         const void *B, const void *A, void *Y,
+                         int M, int N, int K, int r, int bits,
+                         lords_dtype factor_dtype, lords_dtype y_dtype, void *stream);
 
 /* Several quantised matrices applied to the SAME activations: Y[l] = X W_hat[l]^T for l = 0 .. L-1.
  * Every linear layer of a transformer block carries its own codes and factors (Sec. 4.3; module

@@ -18,7 +18,7 @@ STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LOR
 
 EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank", "lords_mixed_schedule",
            "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex",
-           "lords_workspace_bytes", "lords_workspace_zero_bytes", "lords_matmul_ws",
+           "lords_workspace_bytes", "lords_workspace_zero_bytes", "lords_matmul_ws", "lords_noalloc_limit", "lords_matmul_noalloc",
            "lords_matmul_batched", "lords_gate_up", "lords_transpose_codes", "lords_backward_input", "lords_backward_factors"]
 
 
@@ -65,10 +65,14 @@ def library():
         lib.lords_matmul_ex.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci]
         lib.lords_matmul_ws.restype = ci
         lib.lords_matmul_ws.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci, vp, ctypes.c_size_t]
+        lib.lords_matmul_noalloc.restype = ci
+        lib.lords_matmul_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp]
         lib.lords_workspace_bytes.restype = ctypes.c_size_t
         lib.lords_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci]
         lib.lords_workspace_zero_bytes.restype = ctypes.c_size_t
         lib.lords_workspace_zero_bytes.argtypes = []
+        lib.lords_noalloc_limit.restype = ctypes.c_size_t
+        lib.lords_noalloc_limit.argtypes = []
         lib.lords_quantize.restype = ci
         lib.lords_quantize.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
         lib.lords_block_init.restype = ci
@@ -193,6 +197,10 @@ def lords_workspace_zero_bytes() -> int:
     return int(library().lords_workspace_zero_bytes())
 
 
+def lords_noalloc_limit() -> int:
+    return int(library().lords_noalloc_limit())
+
+
 def lords_matmul_ws(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int, workspace,
                     path: int = LORDS_PATH_AUTO, stream=None) -> None:
     """`workspace`: a device byte tensor, at least lords_workspace_bytes(...) long, its first
@@ -200,6 +208,11 @@ def lords_matmul_ws(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int,
     _check(library().lords_matmul_ws(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
                                      _dtype_code(B), _dtype_code(Y), _stream(stream), path, _ptr(workspace),
                                      workspace.numel() * workspace.element_size()), "lords_matmul_ws")
+
+
+def lords_matmul_noalloc(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int, stream=None) -> None:
+    _check(library().lords_matmul_noalloc(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
+                                          _dtype_code(B), _dtype_code(Y), _stream(stream)), "lords_matmul_noalloc")
 
 
 def _ptr_array(tensors):

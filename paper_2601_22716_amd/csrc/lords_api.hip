@@ -161,6 +161,28 @@ int run_batched(const lords::BatchedProblem &bp, void *stream)
     return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
 }
 
+// ---- the entry point that allocates nothing: its scratch is this array, one copy per GPU ----
+constexpr size_t kStaticBytes = (size_t)24 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+unsigned char *g_static_ptr[kMaxDevices] = {};
+std::mutex g_static_mutex;
+
+int static_workspace(WsView *out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LORDS_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        // the array's name is a host-side stand-in: its device address on THIS GPU is asked for once
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LORDS_ERR_LAUNCH;
+        g_static_ptr[dev] = (unsigned char *)ptr;
+    }
+    out->base = g_static_ptr[dev];
+    out->bytes = kStaticBytes;
+    return LORDS_OK;
+}
+
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 inline bool bad_bits(int bits) { return bits != 2 && bits != 3 && bits != 4; }
 inline bool bad_dtype(int d) { return d != LORDS_BF16 && d != LORDS_F32; }
@@ -328,6 +350,17 @@ int lords_matmul_ws(const void *X, const void *codes, const float *codebook, con
     ws.base = (unsigned char *)workspace;
     ws.bytes = workspace_bytes;
     return matmul_in(X, codes, codebook, B, A, Y, M, N, K, r, bits, factor_dtype, y_dtype, stream, path, ws, true);
+}
+
+size_t lords_noalloc_limit(void) { return kStaticBytes; }
+
+int lords_matmul_noalloc(const void *X, const void *codes, const float *codebook, const void *B, const void *A, void *Y,
+                         int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype y_dtype, void *stream)
+{
+    WsView ws;
+    const int rc = static_workspace(&ws);
+    if (rc != LORDS_OK) return rc;
+    return matmul_in(X, codes, codebook, B, A, Y, M, N, K, r, bits, factor_dtype, y_dtype, stream, LORDS_PATH_AUTO, ws, false);
 }
 
 int lords_matmul_batched(const void *X, const void *const *codes, const float *codebook, const void *const *B,

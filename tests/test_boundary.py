@@ -188,6 +188,7 @@ def test_workspace_queries_and_matmul_ws_argument_checks():
     lib = L.library()
     zero = L.lords_workspace_zero_bytes()
     assert zero > 0 and zero % 256 == 0
+    assert L.lords_noalloc_limit() == 24 << 20
     # every problem needs at least the zero front; invalid arguments give 0
     assert L.lords_workspace_bytes(1, 14336, 4096, 32, 4) >= zero
     assert L.lords_workspace_bytes(0, 14336, 4096, 32, 4) == zero
@@ -201,6 +202,11 @@ def test_workspace_queries_and_matmul_ws_argument_checks():
     # forcing a kernel changes the need: the one-token kernel needs the front only
     assert L.lords_workspace_bytes(1, 14336, 4096, 32, 4, 0, L.LORDS_PATH_GEMV) == zero
     assert L.lords_workspace_bytes(1, 14336, 4096, 32, 4, 0, L.LORDS_PATH_SMALLM) > zero
+    # every decode shape of the named layers fits the built-in array
+    for (m, n, k, r, b) in ((1, 14336, 4096, 32, 4), (16, 14336, 4096, 32, 4), (16, 4096, 14336, 48, 3), (1, 28672, 8192, 64, 2),
+                            (16, 4096, 4096, 32, 4)):
+        assert 0 < L.lords_workspace_bytes(m, n, k, r, b) <= L.lords_noalloc_limit(), (m, n, k, r, b)
+
     f = lib.lords_matmul_ws
     W = 256 * 1024          # an aligned fake workspace address; never dereferenced
     ok = [P, P, P, P, P, P, 1, 8, 64, 4, 4, 0, 1, None, 0, W, 1 << 30]
@@ -234,6 +240,12 @@ def test_workspace_queries_and_matmul_ws_argument_checks():
     assert f(*a) == 8
     a = list(ok); a[16] = L.lords_workspace_zero_bytes() - 1
     assert f(*a) == 8
+    # the entry point without allocation: same checks (no launch: NULL pointers / bad arguments only)
+    g = lib.lords_matmul_noalloc
+    okg = [P, P, P, P, P, P, 1, 8, 64, 4, 4, 0, 1, None]
+    a = list(okg); a[0] = None
+    assert g(*a) in (1, 6)              # (6: no GPU here, the array's address cannot be asked for)
+
 
 def ptr_array(vals):
     arr = (ctypes.c_void_p * len(vals))()

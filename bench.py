@@ -32,11 +32,29 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, vendor figure
 COLD_BYTES = 600e6             # rotate through at least this many weight bytes
 
-# HBM bytes per launch: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE readings (KiB per dispatch) of these two
-# kernels, each scaled by what the same counter reads for a plain 256 MiB -> 256 MiB elementwise kernel
-# (--calibrate-copy): FETCH_SIZE x 1.9998, WRITE_SIZE x 1.0.  The summary is under profiles/.
-DECODE_TRAFFIC_BYTES = int((16462.8 * 1.9998 + 960.5) * 1024)
-PREFILL_TRAFFIC_BYTES = int((136891.1 * 1.9998 + 57344.0) * 1024)
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "bench_decode_m1_prefill_m2048_gateup4b_hbm_traffic.md")
+
+
+def counter_traffic():
+    """HBM bytes per launch of the two headline kernels, from the tracked rocprofv3 --pmc summary (FETCH_SIZE
+    and WRITE_SIZE per dispatch, each scaled by what the same counter reads for a plain copy kernel of known
+    size; the file says how).  The summary carries one machine-readable line
+        traffic_bytes_per_launch decode=<int> prefill=<int> taken_at=<commit>
+    Returns ({"decode": bytes or None, "prefill": bytes or None}, commit or None)."""
+    out, commit = {"decode": None, "prefill": None}, None
+    try:
+        with open(TRAFFIC_SUMMARY) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch"):
+                    for tok in line.split()[1:]:
+                        k, _, v = tok.partition("=")
+                        if k in out:
+                            out[k] = int(v)
+                        elif k == "taken_at":
+                            commit = v
+    except OSError:
+        pass
+    return out, commit
 
 
 def algorithmic_bytes(M, N, K, r, bits, factor_bytes=2, y_bytes=4):
@@ -128,8 +146,10 @@ def bench_decode(args, L, li, torch):
                                f"bf16 factors, fp32 Y; {nsets} rotating weight sets (cold last-level cache)",
                    "algorithmic_bytes_per_step": ab, "weight_sets": nsets, "launch_mode": mode},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": DECODE_TRAFFIC_BYTES,
-                     "kernel": "lords::decode_m1_kernel<4,2,2,true,false,false>", "us_per_launch": ev_per_launch * 1e6},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": counter_traffic()[0]["decode"],
+                     "traffic_taken_at": counter_traffic()[1],
+                     "kernel": "lords::gemv_kernel<4,2,1,1,1,8,true,true> (bits, tiles, G, LG, tokens, ring, refill, 16-byte B loads)",
+                     "us_per_launch": ev_per_launch * 1e6},
     }
     return out, cs, sets[0], X, codebook
 
@@ -155,7 +175,8 @@ def bench_prefill(args, L, li, torch):
         "config": {"workload": f"prefill M={M}, N={cfg.N} K={cfg.K}, {cfg.bits}-bit codes, rank {cfg.r}, bf16 Y",
                    "launch_mode": mode},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": PREFILL_TRAFFIC_BYTES,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": counter_traffic()[0]["prefill"],
+                     "traffic_taken_at": counter_traffic()[1],
                      "kernel": "lords::prefill_kernel<4,1,1,2,8,16>", "us_per_launch": ev_per_launch * 1e6},
     }
 
@@ -396,6 +417,100 @@ def bench_shared_input(args, L, li, torch):
     return out
 
 
+def gpu_sets(N, K, bits, r, M, nsets, torch, seed):
+    """Weight sets drawn on the GPU (the same distributions as lords_inputs.make_case: uniform code bytes, A ~ U(0.5, 1.5),
+    B ~ U(0.5, 1.5) * 0.02 / r, X ~ N(0, 1), all bf16): the extra legs below need no bit-identical CPU copy."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    sets = []
+    for _ in range(nsets):
+        codes = torch.randint(0, 256, (N, K * bits // 8), dtype=torch.uint8, device="cuda", generator=g)
+        B = ((torch.rand((N, r), device="cuda", generator=g) + 0.5) * (0.02 / r)).to(torch.bfloat16)
+        A = (torch.rand((r, K), device="cuda", generator=g) + 0.5).to(torch.bfloat16)
+        sets.append((codes, B, A))
+    X = torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16)
+    return sets, X
+
+
+# the layer shapes the method is quoted on, beside the headline layer: (label, N, K, bits, rank, token counts)
+CONFIG_LEGS = [
+    ("Llama-3-8B q_proj 4096x4096, 4-bit, rank 32", 4096, 4096, 4, 32, (1, 4, 16)),
+    ("Llama-3-8B gate/up 14336x4096, 3-bit, rank 48", 14336, 4096, 3, 48, (1, 16)),
+    ("Llama-3-8B down 4096x14336, 3-bit, rank 48", 4096, 14336, 3, 48, (1, 16)),
+    ("Llama-3-8B down 4096x14336, 4-bit, rank 32", 4096, 14336, 4, 32, (1, 2048)),
+    ("Llama-3-8B gate/up 14336x4096, 4-bit, rank 32", 14336, 4096, 4, 32, (2,)),
+    ("Llama-3-70B-shaped 28672x8192, 2-bit, rank 64", 28672, 8192, 2, 64, (1, 16, 256, 4096)),
+]
+
+
+def bench_configs(args, L, li, torch, ceilings):
+    """Every other layer shape and token count the method is quoted on: decode legs (M <= 16) against the HBM line
+    (and, where the scale regeneration 2rNK outweighs the bytes, against the MFMA line as well: the larger of the
+    two times is the bound), prefill legs against the bf16 MFMA line.  Rotating weight sets as for the headline."""
+    import itertools
+    codebooks = {b: torch.from_numpy(li.nf_codebook(b).copy()).cuda() for b in (2, 3, 4)}
+    out = []
+    for (label, N, K, bits, r, Ms), seed in zip(CONFIG_LEGS, itertools.count(9000)):
+        per_set = N * K * bits // 8
+        for M in Ms:
+            decode = M <= 16
+            nsets = int(-(-COLD_BYTES // per_set)) if decode else 2
+            sets, X = gpu_sets(N, K, bits, r, M, nsets, torch, seed)
+            Y = torch.zeros((M, N), dtype=torch.float32 if decode else torch.bfloat16, device="cuda")
+
+            def run_step(i):
+                codes, B, A = sets[i % nsets]
+                L.lords_matmul(X, codes, codebooks[bits], B, A, Y, M, N, K, r, bits)
+
+            steps = 100 if decode else (10 if M * N * K < 3e11 else 4)
+            _, ev_ms, mode, _ = time_steps(run_step, steps, 5, torch, use_graph=not args.no_graph)
+            us = ev_ms * 1e3 / steps
+            leg = {"workload": f"{'decode' if decode else 'prefill'} M={M}, {label}", "us_per_launch": us, "launch_mode": mode}
+            if decode:
+                ab = algorithmic_bytes(M, N, K, r, bits)
+                t_hbm = ab / HBM_PEAK_GBS / 1e3                      # us
+                t_mfma = 2.0 * r * N * K / MFMA_BF16_PEAK_TFLOPS / 1e6   # us: the scale contraction alone
+                leg.update({"value": ab / us / 1e3, "unit": "GB/s", "frac_of_hbm_peak": ab / us / 1e3 / HBM_PEAK_GBS,
+                            "frac_of_measured_read": ab / us / 1e3 / ceilings["stream_read_GBs"] if ceilings else None,
+                            "us_at_hbm_peak": t_hbm, "us_of_scale_contraction_at_mfma_peak": t_mfma,
+                            "binding_line": "mfma (scale contraction)" if t_mfma > t_hbm else "hbm",
+                            "frac_of_binding_line": max(t_hbm, t_mfma) / us})
+            else:
+                fl = 2.0 * M * N * K
+                leg.update({"value": fl / us / 1e6, "unit": "TFLOP/s", "frac_of_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS,
+                            "frac_of_measured_mfma": fl / us / 1e6 / ceilings["mfma_bf16_TFLOPs"] if ceilings else None})
+            out.append(leg)
+            del sets, X, Y
+    return out
+
+
+def bench_ceilings(args, L, torch):
+    """What this GPU gives to a kernel that does nothing else: (a) a read-only pass over a cold 30 MB buffer per launch
+    (21 buffers in rotation: the headline layer's footprint and launch pattern), (b) over one 640 MB buffer per launch,
+    (c) register-resident bf16 MFMA chains.  HIP-graph replays, like the legs they are quoted beside."""
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    small = [torch.randint(0, 255, (30 << 20,), dtype=torch.uint8, device="cuda") for _ in range(21)]
+    _, ev_ms, _, _ = time_steps(lambda i: L.lords_probe_stream_read(small[i % 21], sink), 210, 21, torch, use_graph=not args.no_graph)
+    us_small = ev_ms * 1e3 / 210
+    del small
+    big = torch.randint(0, 255, (640 << 20,), dtype=torch.uint8, device="cuda")
+    _, ev_ms, _, _ = time_steps(lambda i: L.lords_probe_stream_read(big, sink), 10, 2, torch, use_graph=not args.no_graph)
+    us_big = ev_ms * 1e3 / 10
+    del big
+    rates = {}
+    for pattern in (0, 1):
+        flop = L.lords_probe_mfma_bf16(20000, sink, pattern)
+        _, ev_ms, _, _ = time_steps(lambda i: L.lords_probe_mfma_bf16(20000, sink, pattern), 10, 2, torch, use_graph=not args.no_graph)
+        rates[pattern] = flop / (ev_ms * 1e3 / 10) / 1e6
+    return {"cold_30MB_read_us_per_launch": us_small, "cold_30MB_read_GBs": (30 << 20) / us_small / 1e3,
+            "stream_read_GBs": (640 << 20) / us_big / 1e3,
+            "mfma_bf16_TFLOPs": rates[1], "mfma_bf16_TFLOPs_trivial_operands": rates[0],
+            "note": "read-only pass with 16-byte loads (lords_probe_stream_read); eight independent v_mfma_f32_16x16x32_bf16 "
+                    "chains per wave, operands in registers (lords_probe_mfma_bf16): with operands that differ in every lane "
+                    "and element (the ceiling the GEMM is quoted against: its operands are real data), and with operands of "
+                    "ones and small integers (few bits toggling: the chip holds a higher clock)"}
+
+
 def cpu_baseline(li, ab):
     """The fp64 C oracle, as it stands, on the decode workload (M = 1, whole layer), host cores."""
     from oracle import lords_oracle_c as oc
@@ -420,7 +535,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", choices=["decode", "prefill", "shared_input", "backward", "all"], default="all",
+    ap.add_argument("--workload", choices=["decode", "prefill", "shared_input", "backward", "configs", "ceilings", "all"], default="all",
                     help="decode / prefill: the headline workloads; shared_input, backward: context figures only "
                          "(profiling runs); all: everything")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
@@ -446,17 +561,31 @@ def main():
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": None, "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
     ab = algorithmic_bytes(1, 14336, 4096, 32, 4)
+    ceilings = None
+    if args.workload in ("ceilings", "configs", "all") and not args.calibrate_copy:
+        ceilings = bench_ceilings(args, L, torch)
+        line["measured_ceilings"] = ceilings
     if args.workload in ("decode", "all"):
         d, *_ = bench_decode(args, L, li, torch)
+        if ceilings:
+            d["roofline"]["measured_peak"] = ceilings["stream_read_GBs"]
+            d["roofline"]["frac_of_measured"] = d["roofline"]["achieved"] / ceilings["stream_read_GBs"]
+            d["roofline"]["frac_of_measured_cold_30MB_read"] = d["roofline"]["achieved"] / ceilings["cold_30MB_read_GBs"] \
+                * (30 << 20) / ab
         line.update(d)
     if args.workload in ("prefill", "all"):
         p = bench_prefill(args, L, li, torch)
+        if ceilings:
+            p["roofline"]["measured_peak"] = ceilings["mfma_bf16_TFLOPs"]
+            p["roofline"]["frac_of_measured"] = p["roofline"]["achieved"] / ceilings["mfma_bf16_TFLOPs"]
         if args.workload == "prefill":
             line.update({k: p[k] for k in ("metric", "value", "unit", "steps", "ms_per_step", "config", "roofline")})
         else:
             line["prefill"] = p
     if args.workload == "all" and not args.calibrate_copy:
-        line["other_workloads"] = bench_other(args, L, li, torch)
+        line["other_workloads"] = bench_other(args, L, li, torch) + bench_configs(args, L, li, torch, ceilings)
+    if args.workload == "configs":
+        line["other_workloads"] = bench_configs(args, L, li, torch, ceilings)
     if args.workload == "shared_input":
         line["other_workloads"] = bench_shared_input(args, L, li, torch) + bench_block(args, L, li, torch)
     if args.workload == "backward":

@@ -274,6 +274,20 @@ int lords_backward_factors(const void *dY, const void *X, const void *codes, con
                            const void *B, const void *A, float *dB, float *dA,
                            int M, int N, int K, int r, int bits, lords_dtype factor_dtype, void *stream);
 
+/* ---- Measurement aids (not part of the method; used by the benchmark for measured ceilings) ----
+ * lords_probe_stream_read: one read-only pass over `bytes` bytes at `buffer` (device, 16-byte aligned)
+ *   with 16-byte loads, every cache line touched once, nothing written (`sink`: 4 device bytes that
+ *   stay untouched for any real data).  Bytes / time is the HBM read rate this GPU gives to a kernel
+ *   that does nothing else.
+ * lords_probe_mfma_bf16: `iterations` rounds of eight independent v_mfma_f32_16x16x32_bf16 per wave,
+ *   operands in registers, on eight waves per CU; *flop_per_launch (host, may be NULL) receives the
+ *   floating-point operations of one launch.  Flop / time is the dense bf16 matrix rate this GPU
+ *   sustains, clock under load included.  `pattern` 0: operands of ones and small integers (few bits
+ *   toggle); 1: operands that differ in every lane and element, as real weights and activations do.
+ */
+int lords_probe_stream_read(const void *buffer, size_t bytes, void *sink, void *stream);
+int lords_probe_mfma_bf16(int iterations, int pattern, void *sink, double *flop_per_launch, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

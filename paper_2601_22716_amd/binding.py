@@ -18,7 +18,7 @@ STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LOR
 
 EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank", "lords_mixed_schedule",
            "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex",
-           "lords_workspace_bytes", "lords_workspace_zero_bytes", "lords_matmul_ws", "lords_noalloc_limit", "lords_matmul_noalloc",
+           "lords_workspace_bytes", "lords_workspace_zero_bytes", "lords_matmul_ws", "lords_noalloc_limit", "lords_matmul_noalloc", "lords_probe_stream_read", "lords_probe_mfma_bf16",
            "lords_matmul_batched", "lords_gate_up", "lords_transpose_codes", "lords_backward_input", "lords_backward_factors"]
 
 
@@ -71,6 +71,10 @@ def library():
         lib.lords_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci]
         lib.lords_workspace_zero_bytes.restype = ctypes.c_size_t
         lib.lords_workspace_zero_bytes.argtypes = []
+        lib.lords_probe_stream_read.restype = ci
+        lib.lords_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+        lib.lords_probe_mfma_bf16.restype = ci
+        lib.lords_probe_mfma_bf16.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
         lib.lords_noalloc_limit.restype = ctypes.c_size_t
         lib.lords_noalloc_limit.argtypes = []
         lib.lords_quantize.restype = ci
@@ -213,6 +217,19 @@ def lords_matmul_ws(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int,
 def lords_matmul_noalloc(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int, stream=None) -> None:
     _check(library().lords_matmul_noalloc(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
                                           _dtype_code(B), _dtype_code(Y), _stream(stream)), "lords_matmul_noalloc")
+
+
+def lords_probe_stream_read(buffer, sink, stream=None) -> None:
+    _check(library().lords_probe_stream_read(_ptr(buffer), buffer.numel() * buffer.element_size(), _ptr(sink), _stream(stream)),
+           "lords_probe_stream_read")
+
+
+def lords_probe_mfma_bf16(iterations: int, sink, pattern: int = 1, stream=None) -> float:
+    """Returns the floating-point operations of the launch."""
+    flop = ctypes.c_double(0.0)
+    _check(library().lords_probe_mfma_bf16(iterations, pattern, _ptr(sink), ctypes.byref(flop), _stream(stream)),
+           "lords_probe_mfma_bf16")
+    return flop.value
 
 
 def _ptr_array(tensors):

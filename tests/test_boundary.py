@@ -17,7 +17,7 @@ P = 4096   # a fake, 16-byte aligned, non-null "device pointer": never dereferen
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "lords.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lords_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(lords_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_and_library_agree():

@@ -77,10 +77,20 @@ def make_sets(cfg_name, M, nsets, li, torch):
     return cs0, sets, X, codebook
 
 
+# The GPU raises its clocks over the first tens of milliseconds of continuous load (the headline
+# GEMM takes 283 us per launch right after idle and 217 us from about 60 ms on), so every timed
+# region follows untimed repetitions of the same work for this long.
+SETTLE_MS = 150.0
+
+
 def time_region(run, steps, stream, torch):
     """Wall seconds and HIP-event milliseconds of run() (which enqueues `steps` steps on `stream`)."""
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(stream):
+        t_end = time.perf_counter() + SETTLE_MS * 1e-3
+        while time.perf_counter() < t_end:
+            run()
+            torch.cuda.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         ev0.record(stream)
@@ -535,6 +545,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="untimed repetitions of the timed work for this long before each timed region (clock ramp)")
     ap.add_argument("--workload", choices=["decode", "prefill", "shared_input", "backward", "configs", "ceilings", "all"], default="all",
                     help="decode / prefill: the headline workloads; shared_input, backward: context figures only "
                          "(profiling runs); all: everything")
@@ -544,6 +556,7 @@ def main():
                     help="also launch one plain elementwise kernel that reads and writes 256 MiB each (the known-size "
                          "reference for scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
+    globals()["SETTLE_MS"] = max(0.0, args.settle_ms)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported (no collectives are part of it)",
               file=sys.stderr)
@@ -559,7 +572,10 @@ def main():
 
     line = {"metric": "decode GB/s (algorithmic bytes / time, M=1)", "value": None, "unit": "GB/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": None, "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "clock_settle_ms": args.settle_ms,
+            "clock_settle_note": "each timed region follows untimed repetitions of the same work for clock_settle_ms: "
+                                 "the clocks of an idle GPU take tens of milliseconds of load to come up"}
     ab = algorithmic_bytes(1, 14336, 4096, 32, 4)
     ceilings = None
     if args.workload in ("ceilings", "configs", "all") and not args.calibrate_copy:

@@ -99,12 +99,15 @@ inline lords_path resolve_path(lords_path path, int M)
     return path == LORDS_PATH_AUTO ? ((M <= 16) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL) : path;   // measured cross-over
 }
 
-// Bytes of workspace (front included) one checked problem needs on `path` (already resolved).
-size_t matmul_need(const lords::MatmulProblem &p, lords_path path)
+// Bytes of workspace (front included) one checked problem needs on `path` (already resolved).  The
+// large-M kernel takes what it is given: with `limit` bytes or more it shares tiles between
+// workgroups, with less it falls back to whole tiles and needs none.
+constexpr size_t kNoLimit = ~(size_t)0;
+size_t matmul_need(const lords::MatmulProblem &p, lords_path path, size_t limit = kNoLimit)
 {
     size_t scratch = 0;
     if (is_decode(path)) scratch = use_gemv(p, path) ? 0 : decode_scratch(p);
-    else if (lords::prefill_fast_supported(p)) scratch = lords::prefill_fast_workspace_bytes(p);
+    else if (lords::prefill_fast_supported(p)) scratch = lords::prefill_fast_workspace_bytes(p, limit > kFront ? limit - kFront : 0);
     return kFront + ((scratch + 255) & ~(size_t)255);
 }
 
@@ -121,8 +124,9 @@ int launch_matmul(const lords::MatmulProblem &p, lords_path path, const WsView &
             default: e = lords::launch_decode(p, ws.scratch(), (hipStream_t)stream);
         }
     } else {
-        e = lords::prefill_fast_supported(p) ? lords::launch_prefill_fast(p, ws.scratch(), (hipStream_t)stream)
-                                             : lords::launch_prefill(p, (hipStream_t)stream);
+        e = lords::prefill_fast_supported(p)
+                ? lords::launch_prefill_fast(p, ws.scratch(), ws.bytes > kFront ? ws.bytes - kFront : 0, ws.zeroed(), (hipStream_t)stream)
+                : lords::launch_prefill(p, (hipStream_t)stream);
     }
     return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
 }
@@ -337,7 +341,8 @@ int matmul_in(const void *X, const void *codes, const float *codebook, const voi
     lords::MatmulProblem p{X, codes, codebook, B, A, Y, M, N, K, r, bits, f32fact, y_dtype == LORDS_F32};
     path = resolve_path(path, M);
     if (path == LORDS_PATH_GEMV && !use_gemv(p, path)) return LORDS_ERR_UNSUPPORTED;
-    if (!ws.base || ws.bytes < matmul_need(p, path)) return LORDS_ERR_WORKSPACE;
+    // (a caller's workspace must have the size the query gives; the static one is used as far as it goes)
+    if (!ws.base || ws.bytes < matmul_need(p, path, ws_given ? kNoLimit : ws.bytes)) return LORDS_ERR_WORKSPACE;
     return launch_matmul(p, path, ws, stream);
 }
 }  // namespace

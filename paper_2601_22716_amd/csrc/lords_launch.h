@@ -121,8 +121,11 @@ size_t decode_workspace_bytes(const MatmulProblem &p);
 hipError_t launch_decode(const MatmulProblem &p, void *workspace, hipStream_t st);
 // MFMA GEMM path for large M: bf16 factors up to 128 rank columns (lords_prefill.hip) ...
 bool prefill_fast_supported(const MatmulProblem &p);
-size_t prefill_fast_workspace_bytes(const MatmulProblem &p);      // fp32 partial results when K is split
-hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStream_t st);
+// Scratch the kernel would like for the parts of tiles that two or more workgroups share (at most `limit`; with
+// less it plans for less, down to 0 = one whole tile per workgroup), and the launch: `part`/`part_bytes` that
+// scratch, `zeroed` kZeroBytes of device memory that are zero when handed over and left at zero.
+size_t prefill_fast_workspace_bytes(const MatmulProblem &p, size_t limit);
+hipError_t launch_prefill_fast(const MatmulProblem &p, void *part, size_t part_bytes, void *zeroed, hipStream_t st);
 // ... and the general variant (fp32 factors, any rank; lords_fused.hip).
 hipError_t launch_prefill(const MatmulProblem &p, hipStream_t st);
 

@@ -14,6 +14,13 @@
 // the scale MFMAs are read by vector ALU instructions, which cannot read the accumulation
 // registers).  Smaller shapes for small problems and ranks above 32: see the launcher.
 //
+// Work division.  The launcher either gives every workgroup one whole output tile, or deals the
+// K tiles of all output tiles, numbered tile by tile, to the workgroups in equal contiguous runs,
+// so that every CU gets the same amount of work whatever the tile count.  A tile that a run
+// boundary cuts is summed from its parts in column order: the parts that do not start at the
+// tile's first column are written out as fp32 and counted in; the part that does adds them up
+// in order and writes Y (see the epilogue).  The result does not depend on timing.
+//
 // Per K tile the X tile (BM x 128 bf16) and the A tile (padded rank x 128 bf16) are brought from
 // global memory straight into LDS (global_load_lds_dwordx4, no registers), double-buffered, one
 // barrier per tile.  16-byte chunks are XOR-swizzled by row so that the b-operand reads of X
@@ -46,7 +53,9 @@ struct PrefillArgs {
     int row_bytes;
     int nt, mt;            // tiles along N and M
     int ntiles_k;          // ceil(K / 128)
-    int tiles_per_split;   // K tiles one workgroup walks; gridDim.y such ranges, each with its own M x N fp32 output
+    int per;               // work units (one K tile of one output tile) per workgroup; units are numbered tile by tile
+    uint32_t *arrived;     // per output tile: parts handed over so far (zero before and after a launch)
+    float *part;           // per workgroup: the accumulators of a part that does not start at the tile's first column
 };
 
 constexpr int kPfCopies = 8;
@@ -63,6 +72,21 @@ __device__ __forceinline__ void lds_direct_16(const void *gbase, uint32_t goff, 
     // these loads itself: s_waitcnt vmcnt(0) and a barrier before a buffer is read.
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_wave_base), "v"(goff), "s"(gbase) : "memory", "m0");
+}
+
+// Accumulators that pass from one workgroup to another through memory: 16-byte stores and loads at
+// agent scope (sc1: written through to, and read from, the level all XCDs share), so that the hand-over
+// needs no write-back or invalidation of a whole L2.  Written as assembly because the language
+// offers agent-scope atomic accesses of at most 8 bytes; the waits are placed by hand.
+__device__ __forceinline__ void store16_agent(float *p, f32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ f32x4 load16_agent(const float *p)
+{
+    f32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+    return v;
 }
 
 template <int BITS>
@@ -90,16 +114,16 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     const int c = lane & 15, g = lane >> 4;
     const int M = a.M, N = a.N, K = a.K;
 
-    // ---- tile of this workgroup: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
-    //      contiguous range of tiles (n fastest): its workgroups then share X panels in its L2 ----------
-    const int total = a.nt * a.mt;
-    const int per_xcd = (total + 7) / 8;
-    const int T = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || T >= total) return;
-    const int m_blk = (T / a.nt) * BM, n_blk = (T % a.nt) * BN;
+    // ---- work of this workgroup.  The work is cut into units, one K tile of one output tile each, numbered
+    //      tile by tile (n fastest); workgroup w takes units w per .. w per + per - 1, so a workgroup walks a
+    //      tail of one output tile, whole tiles, and a head of another.  Workgroups are dealt round-robin to
+    //      the 8 XCDs, so each XCD gets a contiguous run of ranges: its workgroups then share X panels in its L2.
+    const int total_units = a.nt * a.mt * a.ntiles_k;
+    const int wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    int unit = wg * a.per;
+    const int unit_end = min(unit + a.per, total_units);
+    if (unit >= unit_end) return;
     const int wn = wave % WN, wm = wave / WN;
-    const int n_wave = n_blk + 16 * R * wn;
-    const int m_wave = m_blk + 16 * MB * wm;
 
     // ---- level table --------------------------------------------------------------------------------
     for (int id = tid; id < NE * kPfCopies; id += NT) {
@@ -114,6 +138,15 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     if (K & 127)                                               // ragged last K tile: stale X must at least be finite
         for (int id = tid; id < 2 * XBUF / 16; id += NT) reinterpret_cast<u32x4 *>(Xs)[id] = u32x4{0u, 0u, 0u, 0u};
     __syncthreads();
+
+    while (unit < unit_end) {
+    // ---- this part: K tiles kt0 .. kt1 - 1 of output tile T ------------------------------------------------
+    const int T = unit / a.ntiles_k;
+    const int kt0 = unit - T * a.ntiles_k, kt1 = min(a.ntiles_k, kt0 + (unit_end - unit));
+    unit += kt1 - kt0;
+    const int m_blk = (T / a.nt) * BM, n_blk = (T % a.nt) * BN;
+    const int n_wave = n_blk + 16 * R * wn;
+    const int m_wave = m_blk + 16 * MB * wm;
 
     // ---- B operands of the scale MFMAs: rows n_wave + 16 rho + c, rank entries 32 s + 8 g .. ----------
     bf16x8 Bop[R][SS];
@@ -212,8 +245,6 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) acc[rho][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // this workgroup's range of K tiles (all of them unless K is split over gridDim.y)
-    const int kt0 = blockIdx.y * a.tiles_per_split, kt1 = min(kt0 + a.tiles_per_split, a.ntiles_k);
     uint32_t cw[R][BITS], cwn[R][BITS];
     stage(kt0, 0);
     load_codes(kt0, cw);
@@ -428,8 +459,57 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
     }
 
     // ---- epilogue: lane (c,g) holds token 16 mb + c, rows 16 rho + 4 g + {0..3} ------------------------
-    // (with K split, a.Y is the fp32 buffer of partial results and this range writes its own M x N part)
-    void *Yp = gridDim.y > 1 ? (void *)(reinterpret_cast<float *>(a.Y) + (size_t)blockIdx.y * M * N) : a.Y;
+    // A part that does not start at the tile's first column hands its accumulators over in memory (it is
+    // always the first part of its workgroup, so it waits for nothing); the part that does start there
+    // is the last one of its workgroup, collects the others in column order and writes Y.  The sum of a
+    // tile is therefore taken in a fixed order whatever the timing.
+    constexpr int kPartFloats = R * MB * NT * 4;
+    if (kt0 != 0) {
+        float *dst = a.part + (size_t)wg * kPartFloats + tid * 4;
+        asm volatile("" : "+v"(dst));        // (addresses are made here, not kept in registers over the K loop)
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) store16_agent(dst + (rho * MB + mb) * (NT * 4), acc[rho][mb]);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) __hip_atomic_fetch_add(a.arrived + T, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        continue;
+    }
+    if (kt1 != a.ntiles_k) {
+        const int others = (a.ntiles_k - kt1 + a.per - 1) / a.per;       // the workgroups after this one, up to the tile's end
+        if (tid == 0) {
+            // (bounded: the parts waited for are first parts of their workgroups and never wait themselves)
+            int spins = 0;
+            while ((int)__hip_atomic_load(a.arrived + T, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < others && ++spins < (1 << 21))
+                __builtin_amdgcn_s_sleep(8);
+            __hip_atomic_store(a.arrived + T, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
+        __syncthreads();
+        for (int j = 1; j <= others; ++j) {
+            const float *src = a.part + (size_t)(wg + j) * kPartFloats + tid * 4;
+            asm volatile("" : "+v"(src));
+            // (sixteen loads in flight: what the registers beside the accumulators hold; each wait is a
+            // round trip to memory)
+            constexpr int kBatch = (R * MB) % 16 == 0 ? 16 : 8;
+            static_assert((R * MB) % kBatch == 0, "whole batches");
+#pragma unroll
+            for (int b0 = 0; b0 < R * MB; b0 += kBatch) {
+                f32x4 t[kBatch];
+#pragma unroll
+                for (int i = 0; i < kBatch; ++i) t[i] = load16_agent(src + (b0 + i) * (NT * 4));
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int i = 0; i < kBatch; ++i) {
+                    asm volatile("" : "+v"(t[i]));               // (not before the wait)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[(b0 + i) / MB][(b0 + i) % MB][e] += t[i][e];
+                }
+            }
+        }
+    }
+    void *Yp = a.Y;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
         const int m = m_wave + 16 * mb + c;
@@ -457,6 +537,7 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             }
         }
     }
+    }   // parts of this workgroup
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -470,98 +551,87 @@ static int pf_ss(int r)
 
 bool prefill_fast_supported(const MatmulProblem &p) { return !p.f32fact && pf_ss(p.r) != 0; }
 
-// out[i] = sum over the K ranges of part[s][i], s increasing; four values per thread
-template <bool F32OUT>
-__global__ __launch_bounds__(256) void reduce_split_kernel(const float *__restrict__ part, void *__restrict__ Y, long count, int nparts)
-{
-    const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (i0 >= count) return;
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
-    if (i0 + 4 <= count) {
-        for (int p = 0; p < nparts; ++p) {
-            const f32x4 t = *reinterpret_cast<const f32x4 *>(part + (size_t)p * count + i0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) s[e] += t[e];
-        }
-    } else {
-        for (int p = 0; p < nparts; ++p)
-            for (int e = 0; e < 4; ++e)
-                if (i0 + e < count) s[e] += part[(size_t)p * count + i0 + e];
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        if (i0 + e >= count) break;
-        if (F32OUT) reinterpret_cast<float *>(Y)[i0 + e] = s[e];
-        else reinterpret_cast<uint16_t *>(Y)[i0 + e] = bf16_bits(s[e]);
-    }
-}
-
-// Tile shape and K split of a problem.  Tile shapes, largest first: 256 tokens x 256 rows (8 waves,
-// 4 slabs each), 256 x 128, 128 x 128 (4 waves) for at most 128 tokens.  Padded ranks above 32 take
-// 128-token tiles only (their B operands need the registers, their A tile the LDS): 8 waves side by
-// side along N (256 rows) when that still gives every CU a tile, else 4 waves (128 rows).  Where the
-// tiles would leave most CUs idle, K is cut into up to 4 ranges, each range a workgroup of its own
-// writing fp32 partial results that a second kernel adds in range order (deterministic).
+// Tile shape and the cut of the work.  Tile shapes: 256 tokens x 256 rows (8 waves of 32 rows x 256
+// tokens), 256 x 128 (8 waves), and for at most 128 tokens 128 x 256 (8 waves side by side) and
+// 128 x 128 (4 waves).  Padded ranks above 32 take 128-token tiles only (their B operands need the
+// registers, their A tile the LDS): 256 rows when that still gives every CU a tile, else 128.
+//
+// The work (output tiles x K tiles) is dealt to the CUs in equal contiguous runs of units, so that
+// a tile count that is no multiple of the CU count costs no half-empty last round (448 tiles of the
+// headline layer at 2048 tokens on 256 CUs: 56 K tiles per CU instead of 64).  A tile cut by a run
+// boundary is summed from its parts in column order (see the kernel's epilogue); the parts travel as
+// fp32 through `part`, one tile-sized buffer per workgroup.  Without that buffer (callers whose
+// workspace is too small for it) every workgroup takes one whole tile.
 struct PfPlan {
-    int ss, wm, R, wn, mb, splits, tiles_per_split, nt, mt;
+    int ss, wm, R, wn, mb, nt, mt;
+    int per, wgs;          // units per workgroup, workgroups that get any
+    size_t part_bytes;     // 0: whole tiles
 };
 
-// K ranges for `tiles` output tiles: as many as fill the chip, at most 4, at least four K tiles each
-static int pf_ranges(long tiles, int ntiles_k)
-{
-    long s = 256 / tiles;
-    if (s > 4) s = 4;
-    if (s > ntiles_k / 4) s = ntiles_k / 4;
-    return s < 1 ? 1 : (int)s;
-}
+constexpr int kPfCUs = 256;
 
-static PfPlan pf_plan(const MatmulProblem &p)
+static PfPlan pf_plan(const MatmulProblem &p, size_t avail)
 {
     PfPlan d;
     d.ss = pf_ss(p.r);
-    d.wm = 1; d.R = 2; d.wn = 4; d.mb = 8;
     const int ntiles_k = (p.K + 127) / 128;
-    int s = 1;
-    if (d.ss == 1) {
-        // Candidates (tokens x rows of a tile, measured time of one K tile of one workgroup):
-        //   256 x 256, eight waves of 32 rows x 256 tokens each    3.75 us   (no weight is dequantised twice
-        //             in a workgroup)
-        //   256 x 128, eight waves of 32 rows x 128 tokens         2.5 us
-        //   128 x 128, four waves, and 128 x 256, eight waves      2.3 us, 3.7 us   (up to 128 tokens)
-        // (256 x 192 with twelve waves, three per SIMD, was no faster per weight than 256 x 256 and has
-        // been dropped.)  Cost of a candidate: rounds of workgroups over 256 CUs x K tiles per range x
-        // that time, plus, with more than one range, the second kernel's traffic at 4 TB/s and 3 us.
-        struct Cand { int wm, R, wn, mb; double t; };
-        const Cand cands[4] = {{1, 2, 8, 16, 3.75}, {2, 2, 4, 8, 2.5},
-                               {1, 2, 4, 8, 2.3}, {1, 2, 8, 8, 3.7}};
-        double best = 1e30;
-        for (int i = 0; i < 4; ++i) {
-            const Cand &c = cands[i];
-            const int tokens = 16 * c.mb * c.wm;
-            if ((tokens == 128) != (p.M <= 128)) continue;
-            const long tiles = (long)((p.N + 16 * c.R * c.wn - 1) / (16 * c.R * c.wn)) * ((p.M + tokens - 1) / tokens);
-            const int sc = pf_ranges(tiles, ntiles_k);
-            const long rounds = (tiles * sc + 255) / 256;
-            double cost = (double)rounds * ((ntiles_k + sc - 1) / sc) * c.t;
-            if (sc > 1) cost += 3.0 + ((double)sc * 4.0 + 2.0) * p.M * p.N / 4.0e6;
-            if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; d.wn = c.wn; d.mb = c.mb; s = sc; }
+    // Candidates (tokens x rows of a tile) with the measured time of one K tile of one workgroup at
+    // 4 bits and rank 32, all CUs busy, clocks settled:
+    //   256 x 256, eight waves of 32 rows x 256 tokens each    3.45 us   (no weight is dequantised twice in a workgroup)
+    //   256 x 128, eight waves of 32 rows x 128 tokens         2.4 us
+    //   128 x 256, eight waves; 128 x 128, four waves          2.15 us, 1.75 us   (up to 128 tokens)
+    // Padded ranks of 64 and 128 take the last two shapes at 1.4 and 2 times the cost.
+    struct Cand { int wm, R, wn, mb; double t; };
+    const double rank_cost = d.ss == 1 ? 1.0 : d.ss == 2 ? 1.4 : 2.0;
+    const Cand small_rank[4] = {{1, 2, 8, 16, 3.45}, {2, 2, 4, 8, 2.4}, {1, 2, 8, 8, 2.15}, {1, 2, 4, 8, 1.75}};
+    const Cand large_rank[2] = {{1, 2, 8, 8, 2.15 * rank_cost}, {1, 2, 4, 8, 1.75 * rank_cost}};
+    const Cand *cands = d.ss == 1 ? small_rank : large_rank;
+    const int ncands = d.ss == 1 ? 4 : 2;
+    double best = 1e30;
+    d.wm = 1; d.R = 2; d.wn = 4; d.mb = 8; d.per = ntiles_k; d.part_bytes = 0;
+    for (int i = 0; i < ncands; ++i) {
+        const Cand &c = cands[i];
+        const int tokens = 16 * c.mb * c.wm, rows = 16 * c.R * c.wn;
+        if (d.ss == 1 && (tokens == 128) != (p.M <= 128)) continue;
+        const long tiles = (long)((p.N + rows - 1) / rows) * ((p.M + tokens - 1) / tokens);
+        const long units = tiles * ntiles_k;
+        const size_t tile_bytes = (size_t)tokens * rows * sizeof(float);
+        // whole tiles, dealt by the hardware in rounds
+        {
+            const double cost = (double)((tiles + kPfCUs - 1) / kPfCUs) * ntiles_k * c.t;
+            if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; d.wn = c.wn; d.mb = c.mb; d.per = ntiles_k; d.part_bytes = 0; }
         }
-    } else {
-        const long t = (long)((p.N + 255) / 256) * ((p.M + 127) / 128);
-        if (t >= 200) d.wn = 8;
-        s = pf_ranges((long)((p.N + 16 * d.R * d.wn - 1) / (16 * d.R * d.wn)) * ((p.M + 127) / 128), ntiles_k);
+        // equal runs of units over `wgs` workgroups.  Its price is the hand-over of the parts: measured
+        // 4 us + 1 us per 1.2 MB of parts written when the runs are shorter than a tile (every part is
+        // written and read at about the same time), half of that per MB when they are longer; and runs
+        // that are out of step with each other walk their K tiles about 8 % slower than whole tiles
+        // dealt in rounds do.
+        if (tiles * sizeof(uint32_t) > kZeroBytes || units > (1L << 30)) continue;
+        static const int kWgs[] = {256, 224, 192, 160, 128, 112, 96, 80, 64, 48, 32, 16, 8};
+        for (int wgs : kWgs) {
+            const int per = (int)((units + wgs - 1) / wgs);
+            if (per < 2 || (per % ntiles_k) == 0) continue;                      // (the second: whole tiles again)
+            const size_t bytes = (size_t)wgs * tile_bytes;
+            if (bytes > avail) continue;
+            long written = 0;                                                    // parts that start inside a tile
+            for (long b = per; b < units; b += per) written += (b % ntiles_k) != 0;
+            const double mb_written = (double)written * tile_bytes / 1048576.0;
+            const double cost = per >= ntiles_k ? per * c.t * 1.08 + 4.0 + mb_written / 2.4
+                                                : per * c.t + 4.0 + mb_written / 1.2;
+            if (cost < best) { best = cost; d.wm = c.wm; d.R = c.R; d.wn = c.wn; d.mb = c.mb; d.per = per; d.part_bytes = bytes; }
+        }
     }
-    d.nt = (p.N + 16 * d.R * d.wn - 1) / (16 * d.R * d.wn);
-    d.mt = (p.M + 16 * d.mb * d.wm - 1) / (16 * d.mb * d.wm);
-    d.tiles_per_split = (ntiles_k + s - 1) / s;
-    d.splits = (ntiles_k + d.tiles_per_split - 1) / d.tiles_per_split;
+    const int tokens = 16 * d.mb * d.wm, rows = 16 * d.R * d.wn;
+    d.nt = (p.N + rows - 1) / rows;
+    d.mt = (p.M + tokens - 1) / tokens;
+    const long units = (long)d.nt * d.mt * ntiles_k;
+    d.wgs = (int)((units + d.per - 1) / d.per);
     return d;
 }
 
-size_t prefill_fast_workspace_bytes(const MatmulProblem &p)
+size_t prefill_fast_workspace_bytes(const MatmulProblem &p, size_t limit)
 {
-    const PfPlan d = pf_plan(p);
-    return d.splits > 1 ? (size_t)d.splits * p.M * p.N * sizeof(float) : 0;
+    return pf_plan(p, limit).part_bytes;
 }
 
 template <int BITS, int SS, int WM, int R, int WN = 4, int MB = 8>
@@ -577,11 +647,11 @@ static hipError_t launch_pf_t(const PrefillArgs &a, dim3 grid, hipStream_t st)
     return hipGetLastError();
 }
 
-// `workspace`: prefill_fast_workspace_bytes(p) bytes (only used when K is split).
-hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStream_t st)
+// `part`: part_bytes bytes of scratch (what prefill_fast_workspace_bytes returned for a limit of at most
+// part_bytes), `zeroed`: kZeroBytes of device memory, zero when handed over and left at zero.
+hipError_t launch_prefill_fast(const MatmulProblem &p, void *part, size_t part_bytes, void *zeroed, hipStream_t st)
 {
-    const PfPlan d = pf_plan(p);
-    if (d.splits > 1 && !workspace) return hipErrorInvalidValue;
+    const PfPlan d = pf_plan(p, (part && zeroed) ? part_bytes : 0);
     const int ss = d.ss, wm = d.wm, wn = d.wn;
     PrefillArgs a;
     a.X = (const uint16_t *)p.X;
@@ -589,16 +659,17 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStrea
     a.codebook = p.codebook;
     a.B = (const uint16_t *)p.B;
     a.A = (const uint16_t *)p.A;
-    a.Y = d.splits > 1 ? workspace : p.Y;
+    a.Y = p.Y;
     a.M = p.M; a.N = p.N; a.K = p.K; a.r = p.r;
-    a.y_f32 = (p.f32out || d.splits > 1) ? 1 : 0;
+    a.y_f32 = p.f32out ? 1 : 0;
     a.row_bytes = p.K / 8 * p.bits;
     a.nt = d.nt;
     a.mt = d.mt;
     a.ntiles_k = (p.K + 127) / 128;
-    a.tiles_per_split = d.tiles_per_split;
-    const int total = a.nt * a.mt;
-    const dim3 grid(((total + 7) / 8) * 8, d.splits);
+    a.per = d.per;
+    a.arrived = (uint32_t *)zeroed;
+    a.part = (float *)part;
+    const dim3 grid(((d.wgs + 7) / 8) * 8);
     hipError_t e = hipErrorInvalidValue;
 #define LORDS_PCASE(B_, S_)                                                                     \
     if (p.bits == B_ && ss == S_) {                                                              \
@@ -611,12 +682,7 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, void *workspace, hipStrea
     LORDS_PCASE(3, 1) LORDS_PCASE(3, 2) LORDS_PCASE(3, 4)
     LORDS_PCASE(4, 1) LORDS_PCASE(4, 2) LORDS_PCASE(4, 4)
 #undef LORDS_PCASE
-    if (e != hipSuccess || d.splits == 1) return e;
-    const long count = (long)p.M * p.N;
-    const unsigned blocks = (unsigned)(((count + 3) / 4 + 255) / 256);
-    if (p.f32out) hipLaunchKernelGGL(reduce_split_kernel<true>, dim3(blocks), dim3(256), 0, st, (const float *)workspace, p.Y, count, d.splits);
-    else hipLaunchKernelGGL(reduce_split_kernel<false>, dim3(blocks), dim3(256), 0, st, (const float *)workspace, p.Y, count, d.splits);
-    return hipGetLastError();
+    return e;
 }
 
 }  // namespace lords

@@ -94,9 +94,20 @@ size_t decode_scratch(const lords::MatmulProblem &p)
     return with_tickets > lords::kTicketBytes ? with_tickets - lords::kTicketBytes : 0;
 }
 inline bool is_decode(lords_path path) { return path == LORDS_PATH_DECODE || path == LORDS_PATH_GEMV || path == LORDS_PATH_SMALLM; }
-inline lords_path resolve_path(lords_path path, int M)
+// Measured cross-over.  Up to 16 tokens the few-token kernels win, except at ranks above 32 on large
+// layers, where their time grows by several microseconds per token (28672 x 8192, rank 64: 73 / 95 /
+// 141 us at 4 / 8 / 16 tokens against 86 us for the large-M kernel; 4096 x 14336, rank 48: 37 / 57 us
+// at 8 / 16 tokens against 50 us).
+inline lords_path resolve_path(lords_path path, const lords::MatmulProblem &p)
 {
-    return path == LORDS_PATH_AUTO ? ((M <= 16) ? LORDS_PATH_DECODE : LORDS_PATH_PREFILL) : path;   // measured cross-over
+    if (path != LORDS_PATH_AUTO) return path;
+    if (p.M > 16) return LORDS_PATH_PREFILL;
+    if (p.r > 32 && lords::prefill_fast_supported(p)) {
+        const long weights = (long)p.N * p.K;
+        if (p.M >= 7 && weights >= (128L << 20)) return LORDS_PATH_PREFILL;
+        if (p.M >= 14 && p.K >= 8192) return LORDS_PATH_PREFILL;
+    }
+    return LORDS_PATH_DECODE;
 }
 
 // Bytes of workspace (front included) one checked problem needs on `path` (already resolved).  The
@@ -143,7 +154,7 @@ int plan_workspace(const lords::MatmulProblem &p, lords_path path, size_t extra,
 
 int run_matmul(const lords::MatmulProblem &p, lords_path path, void *stream)
 {
-    path = resolve_path(path, p.M);
+    path = resolve_path(path, p);
     if (path == LORDS_PATH_GEMV && !use_gemv(p, path)) return LORDS_ERR_UNSUPPORTED;
     WsView ws;
     const int rc = plan_workspace(p, path, 0, stream, &ws, nullptr);
@@ -319,7 +330,7 @@ size_t lords_workspace_bytes(int M, int N, int K, int r, int bits, lords_dtype f
     if (!lords::fused_rank_supported(r, f32fact)) return 0;
     if (M == 0) return kFront;
     lords::MatmulProblem p{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, M, N, K, r, bits, f32fact, true};
-    return matmul_need(p, resolve_path(path, M));
+    return matmul_need(p, resolve_path(path, p));
 }
 
 namespace {
@@ -339,7 +350,7 @@ int matmul_in(const void *X, const void *codes, const float *codebook, const voi
     const bool f32fact = factor_dtype == LORDS_F32;
     if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
     lords::MatmulProblem p{X, codes, codebook, B, A, Y, M, N, K, r, bits, f32fact, y_dtype == LORDS_F32};
-    path = resolve_path(path, M);
+    path = resolve_path(path, p);
     if (path == LORDS_PATH_GEMV && !use_gemv(p, path)) return LORDS_ERR_UNSUPPORTED;
     // (a caller's workspace must have the size the query gives; the static one is used as far as it goes)
     if (!ws.base || ws.bytes < matmul_need(p, path, ws_given ? kNoLimit : ws.bytes)) return LORDS_ERR_WORKSPACE;
@@ -446,7 +457,7 @@ int lords_gate_up(const void *X, const void *codes_gate, const void *B_gate, con
         const size_t tmp_bytes = (size_t)2 * mc * N * sizeof(float);
         const void *Xc = (const unsigned char *)X + (size_t)m0 * K * 2;
         lords::MatmulProblem pg{Xc, codes_gate, codebook, B_gate, A_gate, nullptr, mc, N, K, r, bits, f32fact, true};
-        const lords_path path = resolve_path(LORDS_PATH_AUTO, mc);
+        const lords_path path = resolve_path(LORDS_PATH_AUTO, pg);
         WsView ws;
         void *tmp = nullptr;
         int rc = plan_workspace(pg, path, tmp_bytes, stream, &ws, &tmp);
@@ -491,7 +502,7 @@ int lords_backward_input(const void *dY, const void *codes_t, const float *codeb
     const size_t esz = f32fact ? 4 : 2;
     const size_t at_bytes = ((size_t)K * r * esz + 255) & ~(size_t)255, bt_bytes = ((size_t)r * N * esz + 255) & ~(size_t)255;
     lords::MatmulProblem p{dY, codes_t, codebook, nullptr, nullptr, dX, M, K, N, r, bits, f32fact, dx_dtype == LORDS_F32};
-    const lords_path path = resolve_path(LORDS_PATH_AUTO, M);
+    const lords_path path = resolve_path(LORDS_PATH_AUTO, p);
     WsView ws;
     void *extra = nullptr;
     const int rc = plan_workspace(p, path, at_bytes + bt_bytes, stream, &ws, &extra);

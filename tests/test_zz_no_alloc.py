@@ -62,7 +62,7 @@ def test_noalloc_refuses_what_does_not_fit():
     import torch
     import paper_2601_22716_amd as L
     from tests import gpu_util
-    M, N, K, r, bits = 16, 28672, 8192, 64, 2                 # 32 MB of partial sums: beyond the 24 MiB array
+    M, N, K, r, bits = 16, 57344, 8192, 32, 4                 # 29 MB of partial sums: beyond the 24 MiB array
     assert L.lords_workspace_bytes(M, N, K, r, bits) > L.lords_noalloc_limit()
     cs = li.make_case("tiny", M=M, N=64, K=K, bits=bits, r=r, factor_dtype="bf16", seed=2)
     d = gpu_util.DeviceCase(cs)

@@ -3,6 +3,10 @@
 
 namespace lords {
 
+#ifdef LORDS_GV_STAMPS
+static unsigned long long *g_gv_stamps = nullptr;     // where the next launches report (see lords_debug_gemv_stamps)
+#endif
+
 static size_t gv_tree_nodes(int kblocks)
 {
     size_t n = 0;
@@ -83,6 +87,9 @@ hipError_t launch_decode_gemv(const MatmulProblem &p, void *zeroed, hipStream_t 
     a.y_f32 = p.f32out ? 1 : 0;
     a.row_bytes = p.K / 8 * p.bits;
     a.kblocks = d.kblocks;
+#ifdef LORDS_GV_STAMPS
+    a.stamps = g_gv_stamps;
+#endif
     const bool bvec = (p.r % 8) == 0;
     const dim3 grid(d.gx, 1, d.kblocks);
     switch (p.bits) {
@@ -94,3 +101,17 @@ hipError_t launch_decode_gemv(const MatmulProblem &p, void *zeroed, hipStream_t 
 }
 
 }  // namespace lords
+
+#ifdef LORDS_GV_STAMPS
+// Timing builds only: the next launches of the one-/two-token kernel write their time stamps
+// (100 MHz ticks; 16 per workgroup: phases 0..6 of wave 0, then of the last wave) to `buffer`
+// (device memory, 128 bytes per workgroup, at least 2048 workgroups; NULL: stop).  *workgroups
+// receives the grid size of the plan for that problem.
+extern "C" int lords_debug_gemv_stamps(void *buffer, int M, int N, int K, int r, int bits, int *workgroups)
+{
+    lords::g_gv_stamps = (unsigned long long *)buffer;
+    lords::GvPlan d;
+    if (workgroups) *workgroups = lords::gv_plan(M, N, K, r, bits, false, d) ? d.gx * d.kblocks : 0;
+    return 0;
+}
+#endif

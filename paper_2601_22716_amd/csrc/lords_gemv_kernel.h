@@ -40,14 +40,15 @@
 
 namespace lords {
 
+// Builds with -DLORDS_GV_STAMPS (liblords_stamps.so, see build.py and decode_timeline.py) record device
+// time stamps at the phase boundaries of the kernel: kept in registers and written when the kernel ends
+// (a store would queue behind the loads); wave 0 and the last wave of every workgroup report, into
+// GvArgs::stamps[workgroup][16].  Ordinary builds contain none of it.
 #ifdef LORDS_GV_STAMPS
-__device__ unsigned long long *gv_stamps;       // development builds: [workgroup][16] device time stamps
-// time stamps are kept in registers and written when the kernel ends (a store would queue behind the loads);
-// waves 0 and the last one of every workgroup report
 #define GV_STAMP(i) do { gv_t[i] = __builtin_amdgcn_s_memrealtime(); } while (0)
 #define GV_STAMP_DECL unsigned long long gv_t[8] = {}
-#define GV_STAMP_FLUSH(nw) do { if ((threadIdx.x & 63) == 0 && ((threadIdx.x >> 6) == 0 || (threadIdx.x >> 6) == (nw) - 1)) \
-    for (int i_ = 0; i_ < 8; ++i_) gv_stamps[((size_t)blockIdx.z * gridDim.x + blockIdx.x) * 16 + ((threadIdx.x >> 6) ? 8 : 0) + i_] = gv_t[i_]; } while (0)
+#define GV_STAMP_FLUSH(nw) do { if (a.stamps && (threadIdx.x & 63) == 0 && ((threadIdx.x >> 6) == 0 || (threadIdx.x >> 6) == (nw) - 1)) \
+    for (int i_ = 0; i_ < 8; ++i_) a.stamps[((size_t)blockIdx.z * gridDim.x + blockIdx.x) * 16 + ((threadIdx.x >> 6) ? 8 : 0) + i_] = gv_t[i_]; } while (0)
 #else
 #define GV_STAMP(i) do { } while (0)
 #define GV_STAMP_DECL do { } while (0)
@@ -88,6 +89,9 @@ struct GvArgs {
     int y_f32;
     int row_bytes;
     int kblocks;           // gridDim.z
+#ifdef LORDS_GV_STAMPS
+    unsigned long long *stamps;
+#endif
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));

@@ -10,21 +10,27 @@
 //
 // Work split.  A workgroup of eight waves owns a range of 16-row slabs and WK = 8 * 128 * G
 // consecutive columns: wave w owns the 128*G columns from kw + w*128*G on and walks down ALL slabs
-// of the workgroup.  The folded a-operands of a wave's columns (16*G*JT*MT registers) are loaded
-// once, straight from global memory in the layout the MFMA wants (eight consecutive columns of
-// one rank entry per lane), and stay in registers for the whole row stream; nothing but the level
-// table, the activations and the eight waves' row sums passes through LDS.  With G = 4 and rank
-// <= 32 a workgroup spans 4096 columns: the headline layers need no meeting of column blocks at
-// all.  Where K is wider than WK, the column blocks (gridDim.z of them) meet pairwise up a fixed
+// of the workgroup.  The folded a-operands of a wave's columns (16*G*JT*MT registers) are made
+// once and stay in registers for the whole row stream: the wave fetches its part of the A tile
+// with loads that take whole rows (the load unit of a CU pays per cache line touched, see below),
+// passes it through a staging buffer of its own in LDS to reach the layout the MFMA wants (eight
+// consecutive columns of one rank entry per lane), and folds the activation in on the way.  The
+// rows of B of all slabs are staged in LDS by the waves together, the level table is built by the
+// first four waves (one per SIMD); both are handed over through flags in LDS (release / acquire at
+// workgroup scope), so that the only barrier before the stream is the one that clears those flags,
+// taken when every wave is still at the start.  The planner (lords_gemv.hip) takes G = 1 wherever
+// that gives every CU one workgroup: 1024-column blocks, four of them on a 4096-column layer.
+// Where K is wider than WK, the column blocks (gridDim.z of them) meet pairwise up a fixed
 // binary tree through one atomic exchange per row and tree node: the first of a pair to arrive
 // leaves its sum in the slot and is done, the second takes it, adds, empties the slot and climbs.
 // The exchange carries the data itself, so no other memory has to be ordered around it (relaxed
 // device-scope atomics suffice), a hand-over costs one round trip, and because a + b = b + a the
 // result does not depend on who came first: results are run-to-run identical.
 //
-// Every load of the stream (codes and B rows of the first D slabs) is requested before the
-// set-up starts, so the set-up (level table, folded operands) runs under the first memory round
-// trip; later slabs are requested as registers come free.
+// Every load of the stream (the codes of the first D slabs) is requested before the set-up
+// starts, so the set-up (level table, folded operands, rows of B) runs under the first memory
+// round trip; later slabs are requested as registers come free.  The table look-ups run kGvAhead
+// steps ahead of the MFMAs that consume them, across slab boundaries.
 //
 // Lane mapping (v_mfma_f32_16x16x32_bf16; lane l = (c = l%16, g = l/16)): the lane holds the codes
 // of row n0+c at columns col(v, g) = kb + 32*LG*(4*(v/LG) + g) + 32*(v%LG), v = 0..G-1 (LG groups

@@ -341,12 +341,18 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     // their chunks (chunks beyond the flagged rounds before anything else): wait for all of them here,
     // once, so that the stream below is straight-line code.  Every wave sets its flags without
     // waiting for anybody, so these waits end.
-    for (int f = 0; f < kGvBuilders; ++f)
-        while (__hip_atomic_load(&bflag[kGvBRounds * kGvWaves + f], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) __builtin_amdgcn_s_sleep(1);
-    for (int qq = 0; qq < kGvBRounds; ++qq)
-        if (qq * kGvThreads < nbch)
-            for (int w = 0; w < kGvWaves; ++w)
-                while (__hip_atomic_load(&bflag[qq * kGvWaves + w], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) __builtin_amdgcn_s_sleep(1);
+    // One lane per flag, so that a poll is ONE LDS round trip (polled one after the other the twenty
+    // flags cost twenty dependent round trips, 1.2 us, even when all were set long ago).
+    {
+        static_assert(kGvFlags <= 64, "one lane per flag");
+        const bool mine = lane < kGvBRounds * kGvWaves ? (lane / kGvWaves) * kGvThreads < nbch : lane < kGvFlags;
+        while (true) {
+            const int v = mine ? __hip_atomic_load(&bflag[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : 1;
+            if (__builtin_amdgcn_ballot_w64(v == 0) == 0) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    }
     GV_STAMP(3);
     // ---- 4. the row stream.  A step = the four table reads of (slab, u, v) and its JT*MT MFMAs; the
     //         reads run kGvAhead steps ahead of the MFMAs that use them, across slab boundaries (every

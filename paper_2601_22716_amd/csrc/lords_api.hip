@@ -62,22 +62,23 @@ int get_workspace(size_t need, void *stream, WsView *out)
     return LORDS_OK;
 }
 
-// One token: the regrouped kernel of lords_gemv.hip wherever it takes the shape.  Two tokens: the same
-// kernel up to 32 M weights, the few-token kernel above (measured: 4096 x 4096 8.8 against 10.1 us,
-// 14336 x 4096 16.2 against 15.4 us).
+// One token: the regrouped kernel of lords_gemv.hip wherever it takes the shape.  Two tokens: the same,
+// except on layers above 32 M weights with at least as many rows as columns, where the few-token kernel
+// measured faster (us, regrouped / few-token: 14336 x 4096 rank 32 16.0 / 15.3, rank 48 21.8 / 19.7,
+// 28672 x 8192 rank 64 101 / 66; against 4096 x 14336 rank 32 17.1 / 17.8, rank 48 22.9 / 24.2,
+// 4096 x 4096 8.7 / 10.2).
 bool use_gemv(const lords::MatmulProblem &p, lords_path path)
 {
     if (path == LORDS_PATH_SMALLM) return false;
     if (path == LORDS_PATH_GEMV) return lords::decode_gemv_supported(p);
-    if (p.M == 2 && (long)p.N * p.K > (32L << 20)) return false;
+    if (p.M == 2 && (long)p.N * p.K > (32L << 20) && p.N >= p.K) return false;
     return lords::decode_gemv_supported(p);
 }
 
 // Which few-token kernel takes a problem, and the scratch it asks for behind the tickets.
-enum DecodeKind { kOne, kFew, kFast, kGeneral };
+enum DecodeKind { kFew, kFast, kGeneral };
 DecodeKind decode_kind(const lords::MatmulProblem &p)
 {
-    if (lords::decode_m1_supported(p)) return kOne;
     if (p.M > 1 && lords::decode_mx_supported(p)) return kFew;
     if (lords::decode_fast_supported(p)) return kFast;
     return kGeneral;
@@ -86,7 +87,6 @@ size_t decode_scratch(const lords::MatmulProblem &p)
 {
     size_t with_tickets;
     switch (decode_kind(p)) {
-        case kOne: with_tickets = lords::decode_m1_workspace_bytes(p); break;
         case kFew: with_tickets = lords::decode_mx_workspace_bytes(p); break;
         case kFast: with_tickets = lords::decode_fast_workspace_bytes(p); break;
         default: return lords::decode_workspace_bytes(p);
@@ -129,7 +129,6 @@ int launch_matmul(const lords::MatmulProblem &p, lords_path path, const WsView &
         if (use_gemv(p, path)) e = lords::launch_decode_gemv(p, ws.zeroed(), (hipStream_t)stream);
         else if (path == LORDS_PATH_GEMV) return LORDS_ERR_UNSUPPORTED;
         else switch (decode_kind(p)) {
-            case kOne: e = lords::launch_decode_m1(p, ws.tickets(), (hipStream_t)stream); break;
             case kFew: e = lords::launch_decode_mx(p, ws.tickets(), (hipStream_t)stream); break;
             case kFast: e = lords::launch_decode_fast(p, ws.tickets(), (hipStream_t)stream); break;
             default: e = lords::launch_decode(p, ws.scratch(), (hipStream_t)stream);
@@ -164,16 +163,17 @@ int run_matmul(const lords::MatmulProblem &p, lords_path path, void *stream)
 // Several matrices in ONE launch, if a kernel takes the case: a status, or -1 if none does.
 int run_batched(const lords::BatchedProblem &bp, void *stream)
 {
-    const bool one = lords::decode_m1_batched_supported(bp);
-    const bool few = !one && lords::decode_mx_batched_supported(bp);
-    if (!one && !few) return -1;
-    const size_t with_tickets = one ? lords::decode_m1_batched_workspace_bytes(bp) : lords::decode_mx_batched_workspace_bytes(bp);
+    if (lords::decode_gemv_batched_supported(bp)) {
+        WsView ws;
+        const int rc = get_workspace(kFront, stream, &ws);
+        if (rc != LORDS_OK) return rc;
+        return lords::launch_decode_gemv_batched(bp, ws.zeroed(), (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+    }
+    if (!lords::decode_mx_batched_supported(bp)) return -1;
     WsView ws;
-    const int rc = get_workspace(lords::kZeroBytes + with_tickets, stream, &ws);
+    const int rc = get_workspace(lords::kZeroBytes + lords::decode_mx_batched_workspace_bytes(bp), stream, &ws);
     if (rc != LORDS_OK) return rc;
-    const hipError_t e = one ? lords::launch_decode_m1_batched(bp, ws.tickets(), (hipStream_t)stream)
-                             : lords::launch_decode_mx_batched(bp, ws.tickets(), (hipStream_t)stream);
-    return e == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+    return lords::launch_decode_mx_batched(bp, ws.tickets(), (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
 }
 
 // ---- the entry point that allocates nothing: its scratch is this array, one copy per GPU ----

@@ -14,7 +14,8 @@ static size_t gv_tree_nodes(int kblocks)
     return n;
 }
 
-// Shape of the launch.  Returns false if no instantiation takes the case.
+// Shape of the launch for L matrices of N[l] rows that share K, rank, code width and activations.
+// Returns false if no instantiation takes the case.
 //
 // A workgroup spans 1024*G columns.  Every CU has to pull the A tile of its columns (64 bytes per
 // column) through its load unit, which takes about four cycles per 128-byte line, and to fold the
@@ -22,15 +23,18 @@ static size_t gv_tree_nodes(int kblocks)
 // (K / (1024 G) of them) then meet through one exchange per tree level, about a microsecond each.  Measured on
 // the Llama-3-8B/70B layer shapes, the narrowest block that still gives every CU one workgroup is
 // the fastest: G = 1 unless the workgroups would then hold more slabs than their LDS takes.
-static bool gv_plan(int M, int N, int K, int r, int bits, bool f32fact, GvPlan &d)
+// Matrix l gets gxl[l] row ranges of at most d.per slabs each; d.gx is their sum.
+static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32fact, GvPlan &d, int *gxl)
 {
-    if (f32fact || M < 1 || M > 2) return false;
+    if (f32fact || M < 1 || M > 2 || L < 1 || L > kGvMaxLayers) return false;
     const int tiles = (r + 15) / 16;
     d.jt = tiles <= 2 ? 2 : tiles <= 4 ? 4 : 0;
     d.MT = M;
     if (d.jt == 0 || d.jt * d.MT > 8) return false;
     const int gmax = 8 / (d.jt * d.MT) < 2 ? 8 / (d.jt * d.MT) : 2;       // operands within 128 registers
-    const int nslabs = (N + 15) / 16;
+    int nslabs[kGvMaxLayers];
+    long total = 0;
+    for (int l = 0; l < L; ++l) { nslabs[l] = (N[l] + 15) / 16; total += nslabs[l]; }
     for (int G = 1; G <= gmax; G *= 2) {
         d.G = G;
         d.LG = (G >= 2 && (K % 64) == 0) ? 2 : 1;
@@ -43,14 +47,30 @@ static bool gv_plan(int M, int N, int K, int r, int bits, bool f32fact, GvPlan &
         if (cap > (long)(stg / ((size_t)d.MT * 256))) cap = (long)(stg / ((size_t)d.MT * 256));
         if (cap > kGvMaxSlabs) cap = kGvMaxSlabs;
         if (cap < 1 || d.kblocks > 256) continue;
-        int gx = 256 / d.kblocks;                                        // one workgroup per CU
-        if (gx < 1) gx = 1;
-        if (gx > nslabs) gx = nslabs;
-        const int need = (int)((nslabs + cap - 1) / cap);
-        const bool fits = gx >= need;
-        if (!fits) gx = need;
-        d.gx = gx;
-        d.per = (nslabs + gx - 1) / gx;
+        int want = 256 / d.kblocks;                                      // one workgroup per CU
+        if (want < L) want = L;
+        // the smallest share per workgroup with which the matrices together need at most `want` row ranges
+        long per = (total + want - 1) / want;
+        if (per < 1) per = 1;
+        int sum = 0;
+        for (;; ++per) {
+            sum = 0;
+            for (int l = 0; l < L; ++l) sum += (int)((nslabs[l] + per - 1) / per);
+            if (sum <= want || per >= total) break;
+        }
+        const bool fits = per <= cap;
+        if (!fits) {
+            per = cap;
+            sum = 0;
+            for (int l = 0; l < L; ++l) sum += (int)((nslabs[l] + per - 1) / per);
+        }
+        d.gx = sum;
+        d.per = 0;
+        for (int l = 0; l < L; ++l) {
+            gxl[l] = (int)((nslabs[l] + per - 1) / per);
+            const int most = (nslabs[l] + gxl[l] - 1) / gxl[l];           // even shares: the largest one
+            if (most > d.per) d.per = most;
+        }
         const int dmax = gv_dmax(d.G, d.jt, d.MT, bits);
         d.ring = d.per > dmax;
         d.depth = d.ring ? dmax : gv_round_depth(d.per);
@@ -62,42 +82,87 @@ static bool gv_plan(int M, int N, int K, int r, int bits, bool f32fact, GvPlan &
     return false;
 }
 
+// bytes of exchange slots: the trees of all matrices, plus the slots where a gate/up pair meets
+static size_t gv_slot_bytes(const GvPlan &d, int M, const int *N, int L, bool act)
+{
+    size_t rows = 0;
+    for (int l = 0; l < L; ++l) rows += (size_t)N[l];
+    return (d.nodes * rows + (act ? (size_t)N[0] : 0)) * (size_t)M * sizeof(uint32_t);
+}
+
 bool decode_gemv_supported(const MatmulProblem &p)
 {
     GvPlan d;
-    if (!gv_plan(p.M, p.N, p.K, p.r, p.bits, p.f32fact, d)) return false;
-    return d.nodes * (size_t)p.M * p.N * sizeof(uint32_t) <= kZeroBytes;
+    int gxl[kGvMaxLayers];
+    if (!gv_plan(p.M, &p.N, 1, p.K, p.r, p.bits, p.f32fact, d, gxl)) return false;
+    return gv_slot_bytes(d, p.M, &p.N, 1, false) <= kZeroBytes;
 }
 
-hipError_t launch_decode_gemv(const MatmulProblem &p, void *zeroed, hipStream_t st)
+bool decode_gemv_batched_supported(const BatchedProblem &bp)
 {
     GvPlan d;
-    if (!gv_plan(p.M, p.N, p.K, p.r, p.bits, p.f32fact, d)) return hipErrorInvalidValue;
-    if (d.kblocks > 1 && !zeroed) return hipErrorInvalidValue;
+    int gxl[kGvMaxLayers];
+    if (bp.L > kGvMaxLayers || (bp.act && (bp.L != 2 || bp.N[0] != bp.N[1]))) return false;
+    if (!gv_plan(bp.M, bp.N, bp.L, bp.K, bp.r, bp.bits, bp.f32fact, d, gxl)) return false;
+    return gv_slot_bytes(d, bp.M, bp.N, bp.L, bp.act) <= kZeroBytes;
+}
+
+hipError_t launch_decode_gemv_batched(const BatchedProblem &bp, void *zeroed, hipStream_t st)
+{
+    GvPlan d;
+    int gxl[kGvMaxLayers];
+    if (bp.L > kGvMaxLayers || !gv_plan(bp.M, bp.N, bp.L, bp.K, bp.r, bp.bits, bp.f32fact, d, gxl)) return hipErrorInvalidValue;
+    if ((d.kblocks > 1 || bp.act) && !zeroed) return hipErrorInvalidValue;
     GvArgs a;
-    a.X = (const uint16_t *)p.X;
-    a.codebook = p.codebook;
-    a.codes = (const uint8_t *)p.codes;
-    a.A = (const uint16_t *)p.A;
-    a.B = (const uint16_t *)p.B;
-    a.Y = p.Y;
-    a.slots = (uint32_t *)zeroed;
-    a.M = p.M; a.N = p.N; a.K = p.K; a.r = p.r;
-    a.nslabs = (p.N + 15) / 16;
-    a.y_f32 = p.f32out ? 1 : 0;
-    a.row_bytes = p.K / 8 * p.bits;
+    a.X = (const uint16_t *)bp.X;
+    a.codebook = bp.codebook;
+    uint32_t *slots = (uint32_t *)zeroed;
+    int bx0 = 0;
+    for (int l = 0; l < kGvMaxLayers; ++l) {
+        const int s = l < bp.L ? l : 0;
+        GvLayer &ly = a.layer[l];
+        ly.codes = (const uint8_t *)bp.codes[s];
+        ly.A = (const uint16_t *)bp.A[s];
+        ly.B = (const uint16_t *)bp.B[s];
+        ly.Y = bp.Y[s];
+        ly.N = bp.N[s];
+        ly.nslabs = (bp.N[s] + 15) / 16;
+        ly.gx = gxl[s];
+        ly.slots = slots;
+        a.bx0[l] = l < bp.L ? bx0 : 0x7fffffff;
+        if (l < bp.L) {
+            bx0 += gxl[l];
+            if (slots) slots += d.nodes * (size_t)bp.M * bp.N[l];
+        }
+    }
+    a.pair_slots = slots;
+    a.L = bp.L;
+    a.act = bp.act ? 1 : 0;
+    a.M = bp.M; a.K = bp.K; a.r = bp.r;
+    a.y_f32 = bp.f32out ? 1 : 0;
+    a.row_bytes = bp.K / 8 * bp.bits;
     a.kblocks = d.kblocks;
 #ifdef LORDS_GV_STAMPS
     a.stamps = g_gv_stamps;
 #endif
-    const bool bvec = (p.r % 8) == 0;
+    const bool bvec = (bp.r % 8) == 0;
     const dim3 grid(d.gx, 1, d.kblocks);
-    switch (p.bits) {
+    switch (bp.bits) {
         case 2: return launch_gemv_2bit(a, d, bvec, grid, st);
         case 3: return launch_gemv_3bit(a, d, bvec, grid, st);
         case 4: return launch_gemv_4bit(a, d, bvec, grid, st);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_decode_gemv(const MatmulProblem &p, void *zeroed, hipStream_t st)
+{
+    BatchedProblem bp;
+    bp.X = p.X; bp.codebook = p.codebook;
+    for (int l = 0; l < kMaxBatch; ++l) { bp.codes[l] = p.codes; bp.B[l] = p.B; bp.A[l] = p.A; bp.Y[l] = p.Y; bp.N[l] = p.N; }
+    bp.L = 1; bp.M = p.M; bp.K = p.K; bp.r = p.r; bp.bits = p.bits;
+    bp.f32fact = p.f32fact; bp.f32out = p.f32out; bp.act = false;
+    return launch_decode_gemv_batched(bp, zeroed, st);
 }
 
 }  // namespace lords
@@ -111,7 +176,8 @@ extern "C" int lords_debug_gemv_stamps(void *buffer, int M, int N, int K, int r,
 {
     lords::g_gv_stamps = (unsigned long long *)buffer;
     lords::GvPlan d;
-    if (workgroups) *workgroups = lords::gv_plan(M, N, K, r, bits, false, d) ? d.gx * d.kblocks : 0;
+    int gxl[lords::kGvMaxLayers];
+    if (workgroups) *workgroups = lords::gv_plan(M, &N, 1, K, r, bits, false, d, gxl) ? d.gx * d.kblocks : 0;
     return 0;
 }
 #endif

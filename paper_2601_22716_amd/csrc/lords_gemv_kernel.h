@@ -82,16 +82,29 @@ constexpr int gv_dmax(int G, int JT, int MT, int bits)
 #define LORDS_GV_FIRST 1                  // slabs requested ahead of the A tile
 #endif
 
-struct GvArgs {
-    const uint16_t *X;     // M x K bf16
-    const float *codebook;
+// One quantised matrix of a launch.  A launch serves up to kGvMaxLayers matrices that read the same
+// activations (same K, rank and code width): matrix l gets the workgroups bx0[l] .. bx0[l] + gx - 1
+// of gridDim.x, each an even share of its slabs.
+constexpr int kGvMaxLayers = 8;
+struct GvLayer {
     const uint8_t *codes;
     const uint16_t *A;     // r x K bf16
     const uint16_t *B;     // N x r bf16
-    void *Y;
-    uint32_t *slots;       // [tree nodes][M][N] exchange slots, zero between calls
-    int M, N, K, r;
+    void *Y;               // M x N
+    uint32_t *slots;       // [tree nodes][M][N] exchange slots of this matrix, zero between calls
+    int N;
     int nslabs;            // ceil(N / 16)
+    int gx;                // workgroups along its rows
+};
+struct GvArgs {
+    const uint16_t *X;     // M x K bf16
+    const float *codebook;
+    GvLayer layer[kGvMaxLayers];
+    int bx0[kGvMaxLayers]; // first workgroup of each matrix (increasing)
+    uint32_t *pair_slots;  // act: [M][N] slots where the two matrices of a gate/up pair meet
+    int L;                 // matrices
+    int act;               // L == 2, equal shapes: Y = silu(matrix 0) * matrix 1, written to layer[0].Y
+    int M, K, r;
     int y_f32;
     int row_bytes;
     int kblocks;           // gridDim.z
@@ -137,9 +150,12 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     uint16_t *Bs = reinterpret_cast<uint16_t *>(smem + LUT_BYTES + kGvWaves * STG_BYTES + 256);  // [slabs*16][RP] rows of B
     const int kw = blockIdx.z * WK;                            // first column of the workgroup
     const int kb = kw + wave * KTW;                            // first column of this wave
-    const GvArgs &ly = a;
-    const int bx = (int)blockIdx.x, gxl = (int)gridDim.x;
-    const int N = a.N, K = a.K, r = a.r;
+    // the matrix this workgroup belongs to (wave-uniform: scalar registers)
+    int li = 0;
+    for (int l = 1; l < a.L; ++l) li = (int)blockIdx.x >= a.bx0[l] ? l : li;
+    const GvLayer &ly = a.layer[li];
+    const int bx = (int)blockIdx.x - a.bx0[li], gxl = ly.gx;
+    const int N = ly.N, K = a.K, r = a.r;
     const uint32_t laneoff = (uint32_t)lane * 4u;
     const int ngroups = K >> 5;
     // this workgroup's slabs: an even share of the matrix (the host keeps it within the LDS budget)
@@ -451,6 +467,20 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         }
         if (!mine) continue;
         void *Yout = ly.Y;
+        if (a.act) {
+            // gate/up pair: the two finished sums of a row meet in one more slot; the second to arrive
+            // knows which of the two it holds itself and writes silu(gate) * up
+            uint32_t *slot = a.pair_slots + (size_t)m * N + n;
+            uint32_t bits = __builtin_bit_cast(uint32_t, v);
+            if (bits == 0u) bits = 0x80000000u;
+            const uint32_t old = __hip_atomic_exchange(slot, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (old == 0u) continue;
+            __hip_atomic_store(slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float other = __builtin_bit_cast(float, old);
+            const float gate = li == 0 ? v : other, up = li == 0 ? other : v;
+            v = gate / (1.0f + __expf(-gate)) * up;
+            Yout = a.layer[0].Y;
+        }
         if (a.y_f32) reinterpret_cast<float *>(Yout)[(size_t)m * N + n] = v;
         else reinterpret_cast<uint16_t *>(Yout)[(size_t)m * N + n] = bf16_bits(v);
     }

@@ -75,13 +75,8 @@ constexpr size_t kZeroBytes = 4u << 20;
 bool decode_gemv_supported(const MatmulProblem &p);
 hipError_t launch_decode_gemv(const MatmulProblem &p, void *zeroed, hipStream_t st);
 
-// One-token path (lords_decode_m1.hip); same workspace convention as below.
-bool decode_m1_supported(const MatmulProblem &p);
-size_t decode_m1_workspace_bytes(const MatmulProblem &p);
-hipError_t launch_decode_m1(const MatmulProblem &p, void *workspace, hipStream_t st);
-
-// Several matrices applied to ONE activation vector in a single launch (lords_decode_m1.hip): same K,
-// rank, code width, level table and factor type (bf16), own N.  act: matrices 0 and 1 (same N) are a
+// Several matrices applied to the SAME activations in a single launch: same K, rank, code width, level
+// table and factor type (bf16), own N.  act: matrices 0 and 1 (same N) are a
 // gate/up pair and Y[0] receives silu(gate) * up; Y[1] is not written.
 constexpr int kMaxBatch = 8;
 struct BatchedProblem {
@@ -95,10 +90,10 @@ struct BatchedProblem {
     int L, M, K, r, bits;
     bool f32fact, f32out, act;
 };
-bool decode_m1_batched_supported(const BatchedProblem &p);
-size_t decode_m1_batched_workspace_bytes(const BatchedProblem &p);
-hipError_t launch_decode_m1_batched(const BatchedProblem &p, void *workspace, hipStream_t st);
-// The same for 2..16 tokens, ranks up to 64 (lords_decode_mx.hip).
+// One and two tokens, bf16 factors (lords_gemv.hip): all matrices in one launch; `zeroed` as for the single matrix.
+bool decode_gemv_batched_supported(const BatchedProblem &p);
+hipError_t launch_decode_gemv_batched(const BatchedProblem &p, void *zeroed, hipStream_t st);
+// The same for 2..16 tokens, ranks up to 64 (lords_decode_mx.hip); same workspace convention as below.
 bool decode_mx_batched_supported(const BatchedProblem &p);
 size_t decode_mx_batched_workspace_bytes(const BatchedProblem &p);
 hipError_t launch_decode_mx_batched(const BatchedProblem &p, void *workspace, hipStream_t st);

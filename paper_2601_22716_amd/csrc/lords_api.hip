@@ -94,19 +94,16 @@ size_t decode_scratch(const lords::MatmulProblem &p)
     return with_tickets > lords::kTicketBytes ? with_tickets - lords::kTicketBytes : 0;
 }
 inline bool is_decode(lords_path path) { return path == LORDS_PATH_DECODE || path == LORDS_PATH_GEMV || path == LORDS_PATH_SMALLM; }
-// Measured cross-over.  Up to 16 tokens the few-token kernels win, except at ranks above 32 on large
-// layers, where their time grows by several microseconds per token (28672 x 8192, rank 64: 73 / 95 /
-// 141 us at 4 / 8 / 16 tokens against 86 us for the large-M kernel; 4096 x 14336, rank 48: 37 / 57 us
-// at 8 / 16 tokens against 50 us).
+// Measured cross-over.  Up to 16 tokens the few-token kernels win (28672 x 8192, rank 64: 68 / 80 us at
+// 8 / 16 tokens against 87-90 us for the large-M kernel; 4096 x 14336, rank 48: 25 / 31 us against 50 us),
+// except at ranks 65..128, which the few-token family serves with its oldest kernel: there the large-M
+// kernel wins from two tokens on (28672 x 8192, rank 128: 219 against 117 us at two tokens, 235 against
+// 117 us at eight; 14336 x 4096: 71 against 48 us at two; one token: 124 against 117 us and 42 against 48 us).
 inline lords_path resolve_path(lords_path path, const lords::MatmulProblem &p)
 {
     if (path != LORDS_PATH_AUTO) return path;
     if (p.M > 16) return LORDS_PATH_PREFILL;
-    if (p.r > 32 && lords::prefill_fast_supported(p)) {
-        const long weights = (long)p.N * p.K;
-        if (p.M >= 7 && weights >= (128L << 20)) return LORDS_PATH_PREFILL;
-        if (p.M >= 14 && p.K >= 8192) return LORDS_PATH_PREFILL;
-    }
+    if (p.M >= 2 && p.r > 64 && lords::prefill_fast_supported(p)) return LORDS_PATH_PREFILL;
     return LORDS_PATH_DECODE;
 }
 

@@ -276,6 +276,12 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 s[0] += t[0]; s[1] += t[1]; s[2] += t[2]; s[3] += t[3];
             }
             if (m >= M) continue;
+            if (meet && (N & 3) == 0) {
+                // the lane's four sums are four neighbouring rows of one token: one 16-byte store
+                const int nb = row0 + (hf * ly.ns + i) * 16 + 4 * gl;
+                if (nb < N) store16_agent(ly.partial + ((size_t)blockIdx.z * M + m) * N + nb, s);
+                continue;
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int n = row0 + (hf * ly.ns + i) * 16 + 4 * gl + e;
@@ -321,6 +327,49 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
             for (int t = 0; t < nt; ++t) {
                 if (!flag[t]) continue;
                 const int row0 = (bx + (base + t) * gxl) * rows;
+                if ((N & 3) == 0) {
+                    // four neighbouring rows per thread, 16-byte loads, up to eight column blocks in flight
+                    for (int q = tid; q < M * (rows / 4); q += kMxThreads) {
+                        const int m = q / (rows / 4), n = row0 + 4 * (q - m * (rows / 4));
+                        if (n >= N) continue;
+                        auto add_blocks4 = [&](const float *P) __attribute__((always_inline)) -> f32x4 {
+                            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                            for (int z0 = 0; z0 < a.splits; z0 += 8) {
+                                f32x4 t8[8];
+#pragma unroll
+                                for (int u = 0; u < 8; ++u) {
+                                    const int z = min(z0 + u, a.splits - 1);
+                                    t8[u] = load16_agent(P + ((size_t)z * M + m) * N + n);
+                                }
+                                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+                                for (int u = 0; u < 8; ++u) {
+                                    asm volatile("" : "+v"(t8[u]));                  // (not before the wait)
+                                    if (z0 + u < a.splits) {
+                                        acc[0] += t8[u][0]; acc[1] += t8[u][1]; acc[2] += t8[u][2]; acc[3] += t8[u][3];
+                                    }
+                                }
+                            }
+                            return acc;
+                        };
+                        f32x4 s = add_blocks4(Pg);
+                        if (pair) {
+                            const f32x4 up = add_blocks4(Pu);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) s[e] = s[e] / (1.0f + __expf(-s[e])) * up[e];
+                        }
+                        if (a.y_f32) {
+                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(Yout) + (size_t)m * N + n) = s;
+                        } else {
+                            typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+                            u32x2 o;
+                            o[0] = (uint32_t)bf16_bits(s[0]) | ((uint32_t)bf16_bits(s[1]) << 16);
+                            o[1] = (uint32_t)bf16_bits(s[2]) | ((uint32_t)bf16_bits(s[3]) << 16);
+                            *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(Yout) + (size_t)m * N + n) = o;
+                        }
+                    }
+                    continue;
+                }
                 for (int q = tid; q < M * rows; q += kMxThreads) {
                     const int m = q / rows, n = row0 + (q - m * rows);
                     if (n >= N) continue;

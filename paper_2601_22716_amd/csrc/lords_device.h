@@ -101,4 +101,19 @@ __device__ __forceinline__ uint16_t factorB_bits(const Factors &f, int n, int jj
     return seg == 2 ? bf16_bits(x - bf16_to_f32(hi)) : hi;
 }
 
+// fp32 sums that pass from one workgroup to another through memory: 16-byte stores and loads at
+// agent scope (sc1: written through to, and read from, the level all XCDs share), so that the hand-over
+// needs no write-back or invalidation of a whole L2.  Written as assembly because the language
+// offers agent-scope atomic accesses of at most 8 bytes; the waits are placed by hand.
+__device__ __forceinline__ void store16_agent(float *p, f32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" :: "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ f32x4 load16_agent(const float *p)
+{
+    f32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+
 }  // namespace lords

@@ -296,9 +296,9 @@ def test_power_of_two_scaling_is_exact_at_full_size(gpu, name, M):
     cs = li.make_case(name, M=M, seed=72, signed_factors=True)
     d = gpu.DeviceCase(cs)
 
-    def run(X, B, A):
+    def run(X, B, A, codebook=None):
         Y = torch.full((M, cfg.N), float("nan"), dtype=torch.float32, device="cuda")
-        L.lords_matmul(X, d.codes, d.codebook, B, A, Y, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+        L.lords_matmul(X, d.codes, d.codebook if codebook is None else codebook, B, A, Y, M, cfg.N, cfg.K, cfg.r, cfg.bits)
         torch.cuda.synchronize()
         return Y
 
@@ -307,6 +307,10 @@ def test_power_of_two_scaling_is_exact_at_full_size(gpu, name, M):
     assert torch.equal(run(d.X, d.B * 8, d.A), Y0 * 8), "B scaled by 8"
     assert torch.equal(run(d.X, d.B, d.A * 0.25), Y0 * 0.25), "A scaled by 1/4"
     assert torch.equal(run(d.X * 0.0625, d.B, d.A), Y0 * 0.0625), "X scaled by 1/16"
+    # the level table, narrowed to 16 bits inside the kernels (fp16 or bf16): a global scale moved between
+    # the table and B changes nothing while the levels stay inside the fp16 range the header asks for
+    assert torch.equal(run(d.X, d.B * 2.0 ** -10, d.A, d.codebook * 1024.0), Y0), "levels x 2^10, B x 2^-10"
+    assert torch.equal(run(d.X, d.B * 64.0, d.A, d.codebook * 2.0 ** -6), Y0), "levels x 2^-6, B x 2^6"
     # (negating X is NOT such a scaling here: the matrix cores' internal sums are not sign-symmetric to
     #  the last bit, so -X gives -Y only up to rounding)
     Yn = run(-d.X, d.B, d.A)

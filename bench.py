@@ -218,9 +218,47 @@ def bench_other(args, L, li, torch):
             out.append({"workload": f"prefill M={M}", "us_per_launch": us, "value": fl / us / 1e6, "unit": "TFLOP/s",
                         "frac_of_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS})
         del sets, X, Y
+    out.extend(bench_repacked(args, L, li, torch))
     out.extend(bench_shared_input(args, L, li, torch))
     out.extend(bench_block(args, L, li, torch))
     out.extend(bench_backward(args, L, li, torch))
+    return out
+
+
+def bench_repacked(args, L, li, torch):
+    """The headline layer with its codes in the slab-tile layout (lords_repack, done once, offline):
+    the same product from a matrix whose wave-level loads are contiguous."""
+    name = "gateup_4b"
+    cfg = li.CONFIGS[name]
+    out = []
+    for M, steps in ((1, 400), (16, 100), (2048, 20)):
+        decode = M <= 32
+        nsets = int(-(-COLD_BYTES // (cfg.N * cfg.K * cfg.bits // 8))) if decode else 2
+        cs, sets, X, codebook = make_sets(name, M, nsets, li, torch)
+        tiled = []
+        for codes, B, A in sets:
+            t = torch.empty(L.lords_repack_bytes(cfg.N, cfg.K, cfg.bits), dtype=torch.uint8, device="cuda")
+            L.lords_repack(codes, t, cfg.N, cfg.K, cfg.bits)
+            tiled.append((t, B, A))
+        torch.cuda.synchronize()
+        del sets
+        Y = torch.zeros((M, cfg.N), dtype=torch.float32 if decode else torch.bfloat16, device="cuda")
+
+        def run_step(i):
+            t, B, A = tiled[i % nsets]
+            L.lords_matmul_repacked(X, t, codebook, B, A, Y, M, cfg.N, cfg.K, cfg.r, cfg.bits)
+
+        wall, ev_ms, mode, _ = time_steps(run_step, steps, 5, torch, use_graph=not args.no_graph)
+        us = ev_ms * 1e3 / steps
+        if decode:
+            ab = algorithmic_bytes(M, cfg.N, cfg.K, cfg.r, cfg.bits)
+            out.append({"workload": f"decode M={M}, codes in the slab-tile layout (lords_repack)", "us_per_launch": us, "launch_mode": mode,
+                        "value": ab / us / 1e3, "unit": "GB/s", "frac_of_hbm_peak": ab / us / 1e3 / HBM_PEAK_GBS})
+        else:
+            fl = 2.0 * M * cfg.N * cfg.K
+            out.append({"workload": f"prefill M={M}, codes in the slab-tile layout (lords_repack)", "us_per_launch": us, "launch_mode": mode,
+                        "value": fl / us / 1e6, "unit": "TFLOP/s", "frac_of_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS})
+        del tiled, X, Y
     return out
 
 

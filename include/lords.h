@@ -204,6 +204,28 @@ int lords_matmul_noalloc(const void *X, const void *codes, const float *codebook
                          int M, int N, int K, int r, int bits,
                          lords_dtype factor_dtype, lords_dtype y_dtype, void *stream);
 
+/* Slab-tile layout of the codes: an offline re-ordering of the packed matrix matched to the lane map of
+ * the matrix-core kernels (the paper's kernels are only said to be fused, Sec. 4.4; the layout is this
+ * build's).  The matrix is cut into slabs of 16 rows and column tiles of 128 columns; tile (s, t) is
+ * stored whole at byte (s * ceil(K/128) + t) * 256 * bits, and inside it the 32-code chunk (4 * bits
+ * bytes, as in the canonical row) of row 16 s + c, group 4 t + g sits at (16 g + c) * 4 * bits.  A wave
+ * that wants 16 rows x 128 columns then reads ONE contiguous piece in lane order, instead of 16 row
+ * segments two KB apart (measured on the one-token kernel: 13.6 -> 12.95 us on 14336 x 4096).  Rows
+ * >= N and groups >= K/32 of the last tiles are zero bytes.  Codes, levels and scales are unchanged.
+ *   lords_repack_bytes     size of the tiled buffer (host only; 0 for invalid arguments).
+ *   lords_repack           codes (N x K*bits/8, canonical) -> codes_tiled (device, lords_repack_bytes).
+ *   lords_matmul_repacked  lords_matmul_ex on a tiled matrix; same arguments, results and error order.
+ *                          Served by the one-/two-token, the few-token and the large-M kernel (bf16
+ *                          factors, rank <= 128); LORDS_ERR_UNSUPPORTED where a call would need one of
+ *                          the fallback kernels.  Uses the library's own workspace (see the preamble).
+ */
+size_t lords_repack_bytes(int N, int K, int bits);
+int lords_repack(const void *codes, void *codes_tiled, int N, int K, int bits, void *stream);
+int lords_matmul_repacked(const void *X, const void *codes_tiled, const float *codebook,
+                          const void *B, const void *A, void *Y,
+                          int M, int N, int K, int r, int bits,
+                          lords_dtype factor_dtype, lords_dtype y_dtype, void *stream, lords_path path);
+
 /* Several quantised matrices applied to the SAME activations: Y[l] = X W_hat[l]^T for l = 0 .. L-1.
  * Every linear layer of a transformer block carries its own codes and factors (Sec. 4.3; module
  * list of Table 7), and the query/key/value projections (and gate/up) read one input; at one token a

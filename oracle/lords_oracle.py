@@ -277,6 +277,25 @@ def block_init(W, codebook, r: int):
     return B, A
 
 
+def repack_codes(codes: np.ndarray, N: int, K: int, bits: int) -> np.ndarray:
+    """The slab-tile layout of the packed codes (a storage format of this build, not the paper's; the
+    paper's kernels are only said to be fused, Sec. 4.4): the matrix is cut into slabs of 16 rows and
+    column tiles of 128 columns; tile (s, t) is stored whole, tiles in the order s * ceil(K/128) + t; inside
+    a tile the 64 chunks of 32 codes (4*bits bytes, as they stand in the canonical row) are ordered
+    g * 16 + c for row 16 s + c and 32-code group 4 t + g.  Rows >= N and groups >= K/32 are zero bytes.
+    A pure permutation (plus padding): codes, levels and scales are those of the canonical rows."""
+    cb = 4 * bits                                          # bytes of a 32-code chunk
+    nslabs, nct = -(-N // 16), -(-K // 128)
+    out = np.zeros(nslabs * nct * 64 * cb, dtype=np.uint8)
+    for n in range(N):
+        s, c = divmod(n, 16)
+        for grp in range(K // 32):
+            t, g = divmod(grp, 4)
+            dst = (((s * nct + t) * 64) + g * 16 + c) * cb
+            out[dst:dst + cb] = codes[n, grp * cb:(grp + 1) * cb]
+    return out
+
+
 def rel_fro(got, want) -> float:
     want = np.asarray(want, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)

@@ -19,6 +19,7 @@ STATUS_NAMES = {0: "LORDS_OK", 1: "LORDS_ERR_NULL", 2: "LORDS_ERR_BITS", 3: "LOR
 EXPORTS = ["lords_version", "lords_status_string", "lords_row_bytes", "lords_equivalent_rank", "lords_mixed_schedule",
            "lords_unpack", "lords_dequant", "lords_quantize", "lords_block_init", "lords_matmul", "lords_matmul_ex",
            "lords_workspace_bytes", "lords_workspace_zero_bytes", "lords_matmul_ws", "lords_noalloc_limit", "lords_matmul_noalloc", "lords_probe_stream_read", "lords_probe_mfma_bf16",
+           "lords_repack_bytes", "lords_repack", "lords_matmul_repacked",
            "lords_matmul_batched", "lords_gate_up", "lords_transpose_codes", "lords_backward_input", "lords_backward_factors"]
 
 
@@ -77,6 +78,12 @@ def library():
         lib.lords_probe_mfma_bf16.argtypes = [ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
         lib.lords_noalloc_limit.restype = ctypes.c_size_t
         lib.lords_noalloc_limit.argtypes = []
+        lib.lords_repack_bytes.restype = ctypes.c_size_t
+        lib.lords_repack_bytes.argtypes = [ci, ci, ci]
+        lib.lords_repack.restype = ci
+        lib.lords_repack.argtypes = [vp, vp, ci, ci, ci, vp]
+        lib.lords_matmul_repacked.restype = ci
+        lib.lords_matmul_repacked.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci]
         lib.lords_quantize.restype = ci
         lib.lords_quantize.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp]
         lib.lords_block_init.restype = ci
@@ -217,6 +224,20 @@ def lords_matmul_ws(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int,
 def lords_matmul_noalloc(X, codes, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int, stream=None) -> None:
     _check(library().lords_matmul_noalloc(_ptr(X), _ptr(codes), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
                                           _dtype_code(B), _dtype_code(Y), _stream(stream)), "lords_matmul_noalloc")
+
+
+def lords_repack_bytes(N: int, K: int, bits: int) -> int:
+    return int(library().lords_repack_bytes(N, K, bits))
+
+
+def lords_repack(codes, codes_tiled, N: int, K: int, bits: int, stream=None) -> None:
+    _check(library().lords_repack(_ptr(codes), _ptr(codes_tiled), N, K, bits, _stream(stream)), "lords_repack")
+
+
+def lords_matmul_repacked(X, codes_tiled, codebook, B, A, Y, M: int, N: int, K: int, r: int, bits: int,
+                          path: int = LORDS_PATH_AUTO, stream=None) -> None:
+    _check(library().lords_matmul_repacked(_ptr(X), _ptr(codes_tiled), _ptr(codebook), _ptr(B), _ptr(A), _ptr(Y), M, N, K, r, bits,
+                                           _dtype_code(B), _dtype_code(Y), _stream(stream), path), "lords_matmul_repacked")
 
 
 def lords_probe_stream_read(buffer, sink, stream=None) -> None:

@@ -333,7 +333,7 @@ size_t lords_workspace_bytes(int M, int N, int K, int r, int bits, lords_dtype f
 namespace {
 int matmul_in(const void *X, const void *codes, const float *codebook, const void *B, const void *A, void *Y,
               int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype y_dtype, void *stream,
-              lords_path path, const WsView &ws, bool ws_given)
+              lords_path path, const WsView &ws, bool ws_given, bool tiled = false)
 {
     if (!X || !codes || !codebook || !B || !A || !Y) return LORDS_ERR_NULL;
     if (bad_bits(bits)) return LORDS_ERR_BITS;
@@ -347,8 +347,14 @@ int matmul_in(const void *X, const void *codes, const float *codebook, const voi
     const bool f32fact = factor_dtype == LORDS_F32;
     if (!lords::fused_rank_supported(r, f32fact)) return LORDS_ERR_UNSUPPORTED;
     lords::MatmulProblem p{X, codes, codebook, B, A, Y, M, N, K, r, bits, f32fact, y_dtype == LORDS_F32};
+    p.tiled = tiled;
     path = resolve_path(path, p);
     if (path == LORDS_PATH_GEMV && !use_gemv(p, path)) return LORDS_ERR_UNSUPPORTED;
+    if (tiled) {
+        // the slab-tile layout is read by the one-/two-token, the few-token and the large-M kernel only
+        const bool ok = is_decode(path) ? (use_gemv(p, path) || decode_kind(p) == kFew) : lords::prefill_fast_supported(p);
+        if (!ok) return LORDS_ERR_UNSUPPORTED;
+    }
     // (a caller's workspace must have the size the query gives; the static one is used as far as it goes)
     if (!ws.base || ws.bytes < matmul_need(p, path, ws_given ? kNoLimit : ws.bytes)) return LORDS_ERR_WORKSPACE;
     return launch_matmul(p, path, ws, stream);
@@ -363,6 +369,38 @@ int lords_matmul_ws(const void *X, const void *codes, const float *codebook, con
     ws.base = (unsigned char *)workspace;
     ws.bytes = workspace_bytes;
     return matmul_in(X, codes, codebook, B, A, Y, M, N, K, r, bits, factor_dtype, y_dtype, stream, path, ws, true);
+}
+
+size_t lords_repack_bytes(int N, int K, int bits)
+{
+    if (bad_bits(bits) || bad_nk(N, K)) return 0;
+    return (size_t)((N + 15) / 16) * (size_t)((K + 127) / 128) * 256u * (size_t)bits;
+}
+
+int lords_repack(const void *codes, void *codes_tiled, int N, int K, int bits, void *stream)
+{
+    if (!codes || !codes_tiled) return LORDS_ERR_NULL;
+    if (bad_bits(bits)) return LORDS_ERR_BITS;
+    if (bad_nk(N, K)) return LORDS_ERR_SHAPE;
+    if (misaligned(codes) || misaligned(codes_tiled)) return LORDS_ERR_ALIGN;
+    return lords::launch_repack(codes, codes_tiled, N, K, bits, (hipStream_t)stream) == hipSuccess ? LORDS_OK : LORDS_ERR_LAUNCH;
+}
+
+int lords_matmul_repacked(const void *X, const void *codes_tiled, const float *codebook, const void *B, const void *A, void *Y,
+                          int M, int N, int K, int r, int bits, lords_dtype factor_dtype, lords_dtype y_dtype,
+                          void *stream, lords_path path)
+{
+    // argument checks first (no workspace is touched for a bad call), then the library's own workspace
+    WsView none;
+    const int rc0 = matmul_in(X, codes_tiled, codebook, B, A, Y, M, N, K, r, bits, factor_dtype, y_dtype, stream, path, none, false, true);
+    if (rc0 != LORDS_ERR_WORKSPACE) return rc0;          // LORDS_OK only for M == 0
+    const bool f32fact = factor_dtype == LORDS_F32;
+    lords::MatmulProblem p{X, codes_tiled, codebook, B, A, Y, M, N, K, r, bits, f32fact, y_dtype == LORDS_F32};
+    p.tiled = true;
+    WsView ws;
+    const int rc = plan_workspace(p, resolve_path(path, p), 0, stream, &ws, nullptr);
+    if (rc != LORDS_OK) return rc;
+    return matmul_in(X, codes_tiled, codebook, B, A, Y, M, N, K, r, bits, factor_dtype, y_dtype, stream, path, ws, false, true);
 }
 
 size_t lords_noalloc_limit(void) { return kStaticBytes; }

@@ -114,6 +114,48 @@ static hipError_t launch_unpack_bits(const void *codes, uint8_t *idx, int N, int
     return hipGetLastError();
 }
 
+// Slab-tile layout of the codes (see lords_repack in the header): one thread per 32-code chunk of the
+// tiled buffer, chunks in storage order, so the writes are contiguous; chunks beyond the matrix are zero.
+template <int BITS>
+__global__ __launch_bounds__(256) void repack_kernel(const uint8_t *__restrict__ codes, uint8_t *__restrict__ tiled,
+                                                     int N, int K, int nct, long chunks)
+{
+    const long id = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= chunks) return;
+    const long tile = id >> 6;
+    const int ch = (int)(id & 63), g = ch >> 4, c = ch & 15;
+    const long s = tile / nct;
+    const int t = (int)(tile - s * nct);
+    const long n = s * 16 + c;
+    const int grp = 4 * t + g;
+    uint32_t w[BITS];
+#pragma unroll
+    for (int e = 0; e < BITS; ++e) w[e] = 0u;
+    if (n < N && grp < (K >> 5)) load_group<BITS>(codes + (size_t)n * (K / 8 * BITS) + (size_t)grp * (4 * BITS), w);
+    uint32_t *o = reinterpret_cast<uint32_t *>(tiled + (size_t)id * (4 * BITS));
+#pragma unroll
+    for (int e = 0; e < BITS; ++e) o[e] = w[e];
+}
+
+template <int BITS>
+static hipError_t launch_repack_bits(const void *codes, void *tiled, int N, int K, hipStream_t st)
+{
+    const int nct = (K + 127) / 128;
+    const long chunks = (long)((N + 15) / 16) * nct * 64;
+    hipLaunchKernelGGL(repack_kernel<BITS>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st,
+                       (const uint8_t *)codes, (uint8_t *)tiled, N, K, nct, chunks);
+    return hipGetLastError();
+}
+
+hipError_t launch_repack(const void *codes, void *tiled, int N, int K, int bits, hipStream_t st)
+{
+    switch (bits) {
+        case 2: return launch_repack_bits<2>(codes, tiled, N, K, st);
+        case 3: return launch_repack_bits<3>(codes, tiled, N, K, st);
+        default: return launch_repack_bits<4>(codes, tiled, N, K, st);
+    }
+}
+
 hipError_t launch_unpack(const void *codes, uint8_t *idx, int N, int K, int bits, hipStream_t st)
 {
     switch (bits) {

@@ -60,6 +60,8 @@ struct MxArgsT {
     int splits;            // gridDim.z
     int L;                 // matrices in this launch
     int act;               // 1: matrices 0 and 1 are a gate/up pair, Y of matrix 0 receives silu(gate) * up
+    int tiled;             // codes in the slab-tile layout (16 rows x 128 columns per tile, chunk 16 g + c of 4 * BITS bytes)
+    int nct;               // column tiles per slab, ceil(K / 128)
     MxLayer layer[NLAYERS];
 };
 typedef MxArgsT<1> MxArgs;
@@ -99,13 +101,21 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     uint32_t cw[kNS][G][BITS];
     bf16x8 Bop[kNS][SS];
     // (a request past the wave's last slab `last` repeats that slab: same cache lines, no new traffic)
-    auto issue = [&](int i, int first, int last) __attribute__((always_inline)) {
-        const int n = min(min(first + i, last) * 16 + c, N - 1);
+    // Byte offset of the lane's group v inside its row (canonical rows) or inside its slab's run of tiles
+    // (slab-tile layout: tile grp / 4, chunk 16 * (grp % 4) + row); and the step from slab to slab.
+    uint32_t voff[G];
 #pragma unroll
-        for (int v = 0; v < G; ++v) {
-            const int grp = min((kb >> 5) + G * g + v, ngroups - 1);
-            load_group<BITS>(ly.codes + (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS), cw[i][v]);
-        }
+    for (int v = 0; v < G; ++v) {
+        const int grp = min((kb >> 5) + G * g + v, ngroups - 1);
+        voff[v] = a.tiled ? (uint32_t)(((grp >> 2) * 64 + (grp & 3) * 16 + c) * (4 * BITS)) : (uint32_t)grp * (4 * BITS);
+    }
+    const size_t slab_bytes = a.tiled ? (size_t)a.nct * 64 * (4 * BITS) : 0;
+    auto issue = [&](int i, int first, int last) __attribute__((always_inline)) {
+        const int slab = min(first + i, last);
+        const int n = min(slab * 16 + c, N - 1);
+        const uint8_t *rowp = a.tiled ? ly.codes + (size_t)slab * slab_bytes : ly.codes + (size_t)n * a.row_bytes;
+#pragma unroll
+        for (int v = 0; v < G; ++v) load_group<BITS>(rowp + voff[v], cw[i][v]);
         if (BVEC) {
 #pragma unroll
             for (int s = 0; s < SS; ++s) {
@@ -488,6 +498,8 @@ hipError_t launch_decode_mx(const MatmulProblem &p, void *workspace, hipStream_t
         a.splits = d.splits;
         a.L = 1;
         a.act = 0;
+        a.tiled = p.tiled ? 1 : 0;
+        a.nct = (p.K + 127) / 128;
         MxLayer &ly = a.layer[0];
         ly.Y = p.f32out ? (void *)((float *)p.Y + (size_t)m0 * p.N) : (void *)((uint16_t *)p.Y + (size_t)m0 * p.N);
         ly.codes = (const uint8_t *)p.codes;
@@ -599,6 +611,8 @@ hipError_t launch_decode_mx_batched(const BatchedProblem &p, void *workspace, hi
     a.splits = d.splits;
     a.L = p.L;
     a.act = p.act ? 1 : 0;
+    a.tiled = p.tiled ? 1 : 0;
+    a.nct = (p.K + 127) / 128;
     for (int l = 0; l < kMaxBatch; ++l) {
         const int s = l < p.L ? l : 0;                      // unused entries: copies of the first
         MxLayer &ly = a.layer[l];

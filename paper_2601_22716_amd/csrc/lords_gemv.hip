@@ -24,7 +24,7 @@ static size_t gv_tree_nodes(int kblocks)
 // the Llama-3-8B/70B layer shapes, the narrowest block that still gives every CU one workgroup is
 // the fastest: G = 1 unless the workgroups would then hold more slabs than their LDS takes.
 // Matrix l gets gxl[l] row ranges of at most d.per slabs each; d.gx is their sum.
-static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32fact, GvPlan &d, int *gxl)
+static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32fact, bool tiled, GvPlan &d, int *gxl)
 {
     if (f32fact || M < 1 || M > 2 || L < 1 || L > kGvMaxLayers) return false;
     const int tiles = (r + 15) / 16;
@@ -37,7 +37,7 @@ static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32
     for (int l = 0; l < L; ++l) { nslabs[l] = (N[l] + 15) / 16; total += nslabs[l]; }
     for (int G = 1; G <= gmax; G *= 2) {
         d.G = G;
-        d.LG = (G >= 2 && (K % 64) == 0) ? 2 : 1;
+        d.LG = (G >= 2 && (K % 64) == 0 && !tiled) ? 2 : 1;               // (the slab-tile layout is read one 128-column tile at a time)
         const int wk = kGvWaves * 128 * G;
         d.kblocks = (K + wk - 1) / wk;
         // slabs a workgroup can take: its rows of B and its lane sums must fit LDS
@@ -94,7 +94,7 @@ bool decode_gemv_supported(const MatmulProblem &p)
 {
     GvPlan d;
     int gxl[kGvMaxLayers];
-    if (!gv_plan(p.M, &p.N, 1, p.K, p.r, p.bits, p.f32fact, d, gxl)) return false;
+    if (!gv_plan(p.M, &p.N, 1, p.K, p.r, p.bits, p.f32fact, p.tiled, d, gxl)) return false;
     return gv_slot_bytes(d, p.M, &p.N, 1, false) <= kZeroBytes;
 }
 
@@ -103,7 +103,7 @@ bool decode_gemv_batched_supported(const BatchedProblem &bp)
     GvPlan d;
     int gxl[kGvMaxLayers];
     if (bp.L > kGvMaxLayers || (bp.act && (bp.L != 2 || bp.N[0] != bp.N[1]))) return false;
-    if (!gv_plan(bp.M, bp.N, bp.L, bp.K, bp.r, bp.bits, bp.f32fact, d, gxl)) return false;
+    if (!gv_plan(bp.M, bp.N, bp.L, bp.K, bp.r, bp.bits, bp.f32fact, bp.tiled, d, gxl)) return false;
     return gv_slot_bytes(d, bp.M, bp.N, bp.L, bp.act) <= kZeroBytes;
 }
 
@@ -111,7 +111,7 @@ hipError_t launch_decode_gemv_batched(const BatchedProblem &bp, void *zeroed, hi
 {
     GvPlan d;
     int gxl[kGvMaxLayers];
-    if (bp.L > kGvMaxLayers || !gv_plan(bp.M, bp.N, bp.L, bp.K, bp.r, bp.bits, bp.f32fact, d, gxl)) return hipErrorInvalidValue;
+    if (bp.L > kGvMaxLayers || !gv_plan(bp.M, bp.N, bp.L, bp.K, bp.r, bp.bits, bp.f32fact, bp.tiled, d, gxl)) return hipErrorInvalidValue;
     if ((d.kblocks > 1 || bp.act) && !zeroed) return hipErrorInvalidValue;
     GvArgs a;
     a.X = (const uint16_t *)bp.X;
@@ -142,6 +142,8 @@ hipError_t launch_decode_gemv_batched(const BatchedProblem &bp, void *zeroed, hi
     a.y_f32 = bp.f32out ? 1 : 0;
     a.row_bytes = bp.K / 8 * bp.bits;
     a.kblocks = d.kblocks;
+    a.tiled = bp.tiled ? 1 : 0;
+    a.nct = (bp.K + 127) / 128;
 #ifdef LORDS_GV_STAMPS
     a.stamps = g_gv_stamps;
 #endif
@@ -162,6 +164,7 @@ hipError_t launch_decode_gemv(const MatmulProblem &p, void *zeroed, hipStream_t 
     for (int l = 0; l < kMaxBatch; ++l) { bp.codes[l] = p.codes; bp.B[l] = p.B; bp.A[l] = p.A; bp.Y[l] = p.Y; bp.N[l] = p.N; }
     bp.L = 1; bp.M = p.M; bp.K = p.K; bp.r = p.r; bp.bits = p.bits;
     bp.f32fact = p.f32fact; bp.f32out = p.f32out; bp.act = false;
+    bp.tiled = p.tiled;
     return launch_decode_gemv_batched(bp, zeroed, st);
 }
 
@@ -177,7 +180,7 @@ extern "C" int lords_debug_gemv_stamps(void *buffer, int M, int N, int K, int r,
     lords::g_gv_stamps = (unsigned long long *)buffer;
     lords::GvPlan d;
     int gxl[lords::kGvMaxLayers];
-    if (workgroups) *workgroups = lords::gv_plan(M, &N, 1, K, r, bits, false, d, gxl) ? d.gx * d.kblocks : 0;
+    if (workgroups) *workgroups = lords::gv_plan(M, &N, 1, K, r, bits, false, false, d, gxl) ? d.gx * d.kblocks : 0;
     return 0;
 }
 #endif

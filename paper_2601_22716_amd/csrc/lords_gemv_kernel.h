@@ -108,6 +108,8 @@ struct GvArgs {
     int y_f32;
     int row_bytes;
     int kblocks;           // gridDim.z
+    int tiled;             // codes in the slab-tile layout (16 rows x 128 columns per tile, lane-ordered): LG = 1 only
+    int nct;               // column tiles per slab, ceil(K / 128)
 #ifdef LORDS_GV_STAMPS
     unsigned long long *stamps;
 #endif
@@ -174,11 +176,25 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 // HL: lane (c, g) fetches chunk 2g + c/8 of row 8h + c%8; otherwise its own LG groups of row c
                 const int n = min(slab * 16 + (HL ? 8 * h + (c & 7) : c), N - 1);
                 const int grp = HL ? min((kb >> 5) + 8 * vv + 2 * g + (c >> 3), ngroups - 1) : min((kb >> 5) + LG * (4 * vv + g), ngroups - LG);
-                const uint32_t *q = reinterpret_cast<const uint32_t *>(ly.codes + (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS));
+                // (slab-tile layout: the wave's load is one contiguous piece, chunk = lane; rows >= N and
+                //  column tiles beyond K are zero padding there)
+                size_t off = (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS);
+                if constexpr (LG == 1) {                   // (the planner gives the slab-tile layout to LG = 1 kernels only)
+                    const size_t toff = (((size_t)min(slab, ly.nslabs - 1) * a.nct + min((kb >> 7) + vv, a.nct - 1)) * 64 + lane) * (4 * BITS);
+                    off = a.tiled ? toff : off;
+                }
+                const uint32_t *q = reinterpret_cast<const uint32_t *>(ly.codes + off);
                 if (DW == 4) {
                     const u32x4 t = *reinterpret_cast<const u32x4 *>(q);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) cw[slot][vv][h][e] = t[e];
+                } else if (DW == 3) {
+                    // (one 12-byte load into a vector value: three separate dword loads made the compiler
+                    //  keep the whole ring of codes in scratch memory in some instantiations)
+                    typedef uint32_t u32x3 __attribute__((ext_vector_type(3), aligned(4)));
+                    const u32x3 t = *reinterpret_cast<const u32x3 *>(q);
+#pragma unroll
+                    for (int e = 0; e < 3; ++e) cw[slot][vv][h][e] = t[e];
                 } else {
 #pragma unroll
                     for (int e = 0; e < DW; ++e) cw[slot][vv][h][e] = q[e];
@@ -378,7 +394,9 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     for (int i0 = 0; i0 < (RING ? nsw : 1); i0 += D) {
         u32x4 wq[kGvAhead + 1];
         f32x4 acc[JT][MT];
-#pragma unroll
+        // (unrolled in full whatever its size: the ring slots and the look-up queue are register arrays, and
+        //  an index left to run time sends them to scratch memory)
+#pragma clang loop unroll(full)
         for (int gs = 0; gs < TOT + kGvAhead; ++gs) {
             if (gs < TOT) {
                 const int d = gs / STEPS, u = (gs % STEPS) / G, v = gs % G;

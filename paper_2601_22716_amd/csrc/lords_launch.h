@@ -27,6 +27,7 @@ inline hipError_t allow_dynamic_lds(LdsOptIn &state, const void *func, size_t by
 }
 
 hipError_t launch_unpack(const void *codes, uint8_t *idx, int N, int K, int bits, hipStream_t st);
+hipError_t launch_repack(const void *codes, void *tiled, int N, int K, int bits, hipStream_t st);
 
 hipError_t launch_dequant(const void *codes, const float *codebook, const void *B, const void *A, void *W,
                           int N, int K, int r, int bits, bool f32fact, bool f32out, hipStream_t st);
@@ -61,6 +62,8 @@ struct MatmulProblem {
     void *Y;                // M x N
     int M, N, K, r, bits;
     bool f32fact, f32out;
+    bool tiled = false;     // `codes` is in the slab-tile layout (lords_repack): tile (slab s, column tile t) at
+                            // (s * ceil(K/128) + t) * 256 * bits bytes, chunk (row c, group g) at (16 g + c) * 4 * bits inside
 };
 
 // The front of the per-device workspace is reserved for arrival tickets (always zero between calls).
@@ -89,6 +92,7 @@ struct BatchedProblem {
     int N[kMaxBatch];
     int L, M, K, r, bits;
     bool f32fact, f32out, act;
+    bool tiled = false;     // every codes[l] is in the slab-tile layout (see MatmulProblem)
 };
 // One and two tokens, bf16 factors (lords_gemv.hip): all matrices in one launch; `zeroed` as for the single matrix.
 bool decode_gemv_batched_supported(const BatchedProblem &p);

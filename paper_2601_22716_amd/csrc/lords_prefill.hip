@@ -53,6 +53,7 @@ struct PrefillArgs {
     int row_bytes;
     int nt, mt;            // tiles along N and M
     int ntiles_k;          // ceil(K / 128)
+    int tiled;             // codes in the slab-tile layout: tile (slab, K tile) contiguous, chunk = 16 g + c
     int per;               // work units (one K tile of one output tile) per workgroup; units are numbered tile by tile
     uint32_t *arrived;     // per output tile: parts handed over so far (zero before and after a launch)
     float *part;           // per workgroup: the accumulators of a part that does not start at the tile's first column
@@ -214,14 +215,24 @@ __global__ __launch_bounds__(64 * WN * WM) __attribute__((amdgpu_waves_per_eu(WN
             }
         }
     };
+    // Codes of K tile kt, row n, lane group g: canonical rows: n * row_bytes + (4 kt + g) * 4 BITS (clamped
+    // into the row for a ragged last tile); slab-tile layout: the tile (n / 16, kt) is contiguous and the
+    // lane's chunk is 16 g + n % 16.  Either way: a per-row base, a step per K tile, an offset per lane.
     const int ngroups = K >> 5;
-    auto load_codes = [&](int kt, uint32_t (&cw)[R][BITS]) {
+    const uint8_t *crow[R];
 #pragma unroll
-        for (int rho = 0; rho < R; ++rho) {
-            const int n = min(n_wave + 16 * rho + c, N - 1);
-            const int grp = min(kt * 4 + g, ngroups - 1);
-            load_group<BITS>(a.codes + (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS), cw[rho]);
-        }
+    for (int rho = 0; rho < R; ++rho) {
+        const int n = min(n_wave + 16 * rho + c, N - 1);
+        crow[rho] = a.tiled ? a.codes + ((size_t)(n >> 4) * a.ntiles_k * 64 + (n & 15)) * (4 * BITS)
+                            : a.codes + (size_t)n * a.row_bytes;
+    }
+    const uint32_t cstep = a.tiled ? 64u * 4 * BITS : 4u * 4 * BITS;
+    const uint32_t cgoff = a.tiled ? (uint32_t)g * 16 * 4 * BITS : (uint32_t)g * 4 * BITS;
+    const uint32_t cmax = a.tiled ? 0xffffffffu : (uint32_t)(ngroups - 1) * 4 * BITS;
+    auto load_codes = [&](int kt, uint32_t (&cw)[R][BITS]) {
+        const uint32_t off = min((uint32_t)kt * cstep + cgoff, cmax);
+#pragma unroll
+        for (int rho = 0; rho < R; ++rho) load_group<BITS>(crow[rho] + off, cw[rho]);
     };
 
     f32x4 acc[R][MB];
@@ -651,6 +662,7 @@ hipError_t launch_prefill_fast(const MatmulProblem &p, void *part, size_t part_b
     a.nt = d.nt;
     a.mt = d.mt;
     a.ntiles_k = (p.K + 127) / 128;
+    a.tiled = p.tiled ? 1 : 0;
     a.per = d.per;
     a.arrived = (uint32_t *)zeroed;
     a.part = (float *)part;

@@ -255,6 +255,46 @@ def ptr_array(vals):
     return arr
 
 
+def test_repack_queries_and_argument_checks():
+    """Host-side only: the size of the slab-tile buffer and the argument order of lords_repack and
+    lords_matmul_repacked (NULL -> BITS -> SHAPE -> ALIGN -> DTYPE -> (M == 0) -> UNSUPPORTED); no launch."""
+    from oracle import lords_oracle as onp
+    import numpy as np
+    for (n, k, b) in ((1, 32, 4), (16, 128, 2), (17, 160, 3), (37, 288, 4), (14336, 4096, 4), (28672, 8192, 2)):
+        assert L.lords_repack_bytes(n, k, b) == -(-n // 16) * -(-k // 128) * 256 * b
+    assert L.lords_repack_bytes(37, 288, 3) == onp.repack_codes(np.zeros((37, 288 * 3 // 8), dtype=np.uint8), 37, 288, 3).size
+    for bad in ((0, 64, 4), (4, 48, 4), (4, 64, 5)):
+        assert L.lords_repack_bytes(*bad) == 0
+    f = L.library().lords_repack
+    assert f(None, P, 4, 64, 4, None) == 1 and f(P, None, 4, 64, 4, None) == 1
+    assert f(P, P, 4, 64, 7, None) == 2
+    assert f(P, P, 0, 64, 4, None) == 3 and f(P, P, 4, 40, 4, None) == 3
+    assert f(P + 4, P, 4, 64, 4, None) == 4 and f(P, P + 2, 4, 64, 4, None) == 4
+    assert f(None, P + 1, 0, 48, 7, None) == 1 and f(P + 1, P, 0, 48, 7, None) == 2 and f(P + 1, P, 0, 48, 4, None) == 3
+    g = L.library().lords_matmul_repacked
+    ok = [P, P, P, P, P, P, 1, 8, 64, 4, 4, 0, 1, None, 0]
+    for i in range(6):
+        a = list(ok); a[i] = None
+        assert g(*a) == 1
+    a = list(ok); a[10] = 0
+    assert g(*a) == 2
+    for i, v in ((6, -1), (7, 0), (8, 16), (9, 0)):
+        a = list(ok); a[i] = v
+        assert g(*a) == 3
+    a = list(ok); a[1] = P + 2
+    assert g(*a) == 4
+    a = list(ok); a[11] = 3
+    assert g(*a) == 5
+    a = list(ok); a[14] = 9
+    assert g(*a) == 5
+    a = list(ok); a[6] = 0
+    assert g(*a) == 0                                        # M == 0: nothing to do
+    a = list(ok); a[11] = 1                                  # fp32 factors belong to kernels that read canonical rows only
+    assert g(*a) == 7
+    a = list(ok); a[9] = 200                                 # so do ranks above 128
+    assert g(*a) == 7
+
+
 def test_matmul_batched_argument_checks():
     f = L.library().lords_matmul_batched
     three = lambda: ptr_array([P, P, P])

@@ -250,7 +250,7 @@ def test_matmul_full_size_sampled(gpu, name, M):
         np.testing.assert_array_equal(got[rows], oc.unpack_codes(cs.codes[rows], cs.K, cs.bits))
 
 
-@pytest.mark.parametrize("name,M", [("gateup_4b", 1), ("qproj_4b", 4), ("qproj_4b", 64)])
+@pytest.mark.parametrize("name,M", [("gateup_4b", 1), ("qproj_4b", 4), ("qproj_4b", 64), ("down_4b", 2048), ("gateup_4b", 256)])
 def test_matmul_in_a_hip_graph_replays_identically(gpu, name, M):
     """bench.py times the calls as HIP-graph replays: a captured call must give, on every replay, with
     the program's own eager calls and synchronisations in between, exactly what the eager call gives

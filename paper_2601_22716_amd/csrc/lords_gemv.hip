@@ -35,6 +35,9 @@ static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32
     int nslabs[kGvMaxLayers];
     long total = 0;
     for (int l = 0; l < L; ++l) { nslabs[l] = (N[l] + 15) / 16; total += nslabs[l]; }
+    // (the kernel addresses the codes of a matrix with 32-bit byte offsets, in either layout)
+    for (int l = 0; l < L; ++l)
+        if ((size_t)nslabs[l] * 16 * (size_t)((K + 127) / 128) * 16 * (size_t)bits >= ((size_t)1 << 32) - 64) return false;
     for (int G = 1; G <= gmax; G *= 2) {
         d.G = G;
         d.LG = (G >= 2 && (K % 64) == 0 && !tiled) ? 2 : 1;               // (the slab-tile layout is read one 128-column tile at a time)
@@ -126,8 +129,8 @@ hipError_t launch_decode_gemv_batched(const BatchedProblem &bp, void *zeroed, hi
         ly.B = (const uint16_t *)bp.B[s];
         ly.Y = bp.Y[s];
         ly.N = bp.N[s];
-        ly.nslabs = (bp.N[s] + 15) / 16;
-        ly.gx = gxl[s];
+        ly.share = (bp.N[s] + 15) / 16 / gxl[s];
+        ly.extra = (bp.N[s] + 15) / 16 % gxl[s];
         ly.slots = slots;
         a.bx0[l] = l < bp.L ? bx0 : 0x7fffffff;
         if (l < bp.L) {

@@ -93,14 +93,13 @@ struct GvLayer {
     void *Y;               // M x N
     uint32_t *slots;       // [tree nodes][M][N] exchange slots of this matrix, zero between calls
     int N;
-    int nslabs;            // ceil(N / 16)
-    int gx;                // workgroups along its rows
+    int share, extra;      // slabs per workgroup: ceil(N / 16) = gx * share + extra, the first `extra` workgroups take one more
 };
 struct GvArgs {
+    // (what every launch reads comes first, within the first cache lines of the argument block; the other
+    //  matrices of a shared launch follow)
     const uint16_t *X;     // M x K bf16
     const float *codebook;
-    GvLayer layer[kGvMaxLayers];
-    int bx0[kGvMaxLayers]; // first workgroup of each matrix (increasing)
     uint32_t *pair_slots;  // act: [M][N] slots where the two matrices of a gate/up pair meet
     int L;                 // matrices
     int act;               // L == 2, equal shapes: Y = silu(matrix 0) * matrix 1, written to layer[0].Y
@@ -113,6 +112,8 @@ struct GvArgs {
 #ifdef LORDS_GV_STAMPS
     unsigned long long *stamps;
 #endif
+    GvLayer layer[kGvMaxLayers];
+    int bx0[kGvMaxLayers]; // first workgroup of each matrix (increasing)
 };
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -122,7 +123,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 // groups per lane.  LG: groups per load.  MT: tokens.  D: slabs whose loads are in flight.
 // RING: a workgroup may hold more than D slabs (slots are refilled).  BVEC: rows of B can be read with
 // 16-byte loads.
-template <int BITS, int JT, int G, int LG, int MT, int D, bool RING, bool BVEC>
+template <int BITS, int JT, int G, int LG, int MT, int D, bool RING, bool BVEC, bool MULTI>
 __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemv_kernel(GvArgs a)
 {
     // A load unit is LG groups of 32 codes per lane.  HL: the unit is fetched as TWO loads of eight
@@ -152,37 +153,60 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     uint16_t *Bs = reinterpret_cast<uint16_t *>(smem + LUT_BYTES + kGvWaves * STG_BYTES + 256);  // [slabs*16][RP] rows of B
     const int kw = blockIdx.z * WK;                            // first column of the workgroup
     const int kb = kw + wave * KTW;                            // first column of this wave
-    // the matrix this workgroup belongs to (wave-uniform: scalar registers)
-    int li = 0;
-    for (int l = 1; l < a.L; ++l) li = (int)blockIdx.x >= a.bx0[l] ? l : li;
-    const GvLayer &ly = a.layer[li];
-    const int bx = (int)blockIdx.x - a.bx0[li], gxl = ly.gx;
+    // The matrix this workgroup belongs to (wave-uniform: scalar registers).  A launch of one matrix (MULTI
+    // false) finds everything at fixed places among the kernel arguments, with the first fetch; only a launch
+    // of several matrices pays a second, dependent fetch (for one matrix that chain cost 0.2 to 0.4 us).
+    int li = 0, bx_first = 0;
+    GvLayer ly = a.layer[0];
+    if constexpr (MULTI) {
+        for (int l = 1; l < a.L; ++l) li = (int)blockIdx.x >= a.bx0[l] ? l : li;
+        ly = a.layer[li];
+        bx_first = a.bx0[li];
+    }
+    const int bx = (int)blockIdx.x - bx_first;
     const int N = ly.N, K = a.K, r = a.r;
     const uint32_t laneoff = (uint32_t)lane * 4u;
     const int ngroups = K >> 5;
-    // this workgroup's slabs: an even share of the matrix (the host keeps it within the LDS budget)
-    const int s0 = (int)(((long)ly.nslabs * bx) / gxl);
-    const int nsw = (int)(((long)ly.nslabs * (bx + 1)) / gxl) - s0;
+    // this workgroup's slabs: an even share of the matrix (the host keeps it within the LDS budget), from
+    // a quotient and remainder the host worked out (a division here is a hundred dependent scalar instructions)
+    const int s0 = bx * ly.share + min(bx, ly.extra);
+    const int nsw = ly.share + (bx < ly.extra ? 1 : 0);
     const int last = s0 + max(nsw, 1) - 1;
 
     // Code loads of one slab into ring slot `slot`, branch-free (addresses clamped into the array):
     // codes of columns >= K meet zero a-operands, rows >= N are dropped at the store.
+    // One form of address serves both layouts, so that a load of the stream costs a scalar multiply and three
+    // vector operations: byte offset = min(slab * cstep + cbase, cmax) + ccol (32 bits: the host keeps the code
+    // array below 4 GB), with the lane's share worked out once, here.
+    //   rows of K codes: cstep = 16 rows, cbase = the lane's row within the slab (HL: lane (c, g) fetches chunk
+    //     2g + c/8 of row 8h + c%8; otherwise its own LG groups of row c), cmax = row N - 1, ccol = the group;
+    //   slab tiles (LG = 1): the wave's load is one contiguous piece, chunk = lane; cstep = a slab of tiles,
+    //     cbase = tile and lane, no clamp (rows >= N and column tiles beyond K are zero padding there).
+    const uint32_t cstep = a.tiled ? (uint32_t)a.nct * (256u * BITS) : 16u * (uint32_t)a.row_bytes;
+    const uint32_t cmax = a.tiled ? 0xFFFFFFFFu : (uint32_t)(N - 1) * (uint32_t)a.row_bytes;
+    uint32_t cbase[NV][NH], ccol[NV][NH];
+#pragma unroll
+    for (int vv = 0; vv < NV; ++vv)
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            const int grp = HL ? min((kb >> 5) + 8 * vv + 2 * g + (c >> 3), ngroups - 1) : min((kb >> 5) + LG * (4 * vv + g), ngroups - LG);
+            cbase[vv][h] = (uint32_t)(HL ? 8 * h + (c & 7) : c) * (uint32_t)a.row_bytes;
+            ccol[vv][h] = (uint32_t)grp * (4u * BITS);
+            if constexpr (LG == 1) {                       // (the planner gives the slab-tile layout to LG = 1 kernels only)
+                if (a.tiled) {
+                    cbase[vv][h] = ((uint32_t)min((kb >> 7) + vv, a.nct - 1) * 64u + (uint32_t)lane) * (4u * BITS);
+                    ccol[vv][h] = 0u;
+                }
+            }
+        }
     uint32_t cw[D][NV][NH][DW];
     auto issue = [&](int slot, int slab) __attribute__((always_inline)) {
+        const uint32_t sbase = (uint32_t)slab * cstep;
 #pragma unroll
         for (int vv = 0; vv < NV; ++vv)
 #pragma unroll
             for (int h = 0; h < NH; ++h) {
-                // HL: lane (c, g) fetches chunk 2g + c/8 of row 8h + c%8; otherwise its own LG groups of row c
-                const int n = min(slab * 16 + (HL ? 8 * h + (c & 7) : c), N - 1);
-                const int grp = HL ? min((kb >> 5) + 8 * vv + 2 * g + (c >> 3), ngroups - 1) : min((kb >> 5) + LG * (4 * vv + g), ngroups - LG);
-                // (slab-tile layout: the wave's load is one contiguous piece, chunk = lane; rows >= N and
-                //  column tiles beyond K are zero padding there)
-                size_t off = (size_t)n * a.row_bytes + (size_t)grp * (4 * BITS);
-                if constexpr (LG == 1) {                   // (the planner gives the slab-tile layout to LG = 1 kernels only)
-                    const size_t toff = (((size_t)min(slab, ly.nslabs - 1) * a.nct + min((kb >> 7) + vv, a.nct - 1)) * 64 + lane) * (4 * BITS);
-                    off = a.tiled ? toff : off;
-                }
+                const uint32_t off = min(sbase + cbase[vv][h], cmax) + ccol[vv][h];
                 const uint32_t *q = reinterpret_cast<const uint32_t *>(ly.codes + off);
                 if (DW == 4) {
                     const u32x4 t = *reinterpret_cast<const u32x4 *>(q);
@@ -485,7 +509,7 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         }
         if (!mine) continue;
         void *Yout = ly.Y;
-        if (a.act) {
+        if (MULTI && a.act) {
             // gate/up pair: the two finished sums of a row meet in one more slot; the second to arrive
             // knows which of the two it holds itself and writes silu(gate) * up
             uint32_t *slot = a.pair_slots + (size_t)m * N + n;
@@ -524,9 +548,16 @@ template <int BITS, int JT, int G, int LG, int MT, int D, bool RING, bool BVEC>
 static hipError_t launch_gv_t(const GvArgs &a, dim3 grid, size_t smem, hipStream_t st)
 {
     static LdsOptIn lds_opt_in;
-    const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC>), kGvLdsLimit);
+    if (a.L > 1) {
+        static LdsOptIn lds_opt_in_multi;
+        const hipError_t e = allow_dynamic_lds(lds_opt_in_multi, reinterpret_cast<const void *>(&gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, true>), kGvLdsLimit);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, true>), grid, dim3(kGvThreads), smem, st, a);
+        return hipGetLastError();
+    }
+    const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, false>), kGvLdsLimit);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC>), grid, dim3(kGvThreads), smem, st, a);
+    hipLaunchKernelGGL((gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, false>), grid, dim3(kGvThreads), smem, st, a);
     return hipGetLastError();
 }
 

@@ -9,10 +9,12 @@ over all workgroups of all launches, when each phase boundary is reached, counte
 stamp of the launch.  The stamps are s_memrealtime ticks (100 MHz, 10 ns), kept in registers and
 written when a workgroup ends; wave 0 and the last wave of each workgroup report.
 
-Boundaries: 0 kernel entered; 1 flags cleared, rows of B and level table requested / built, all
-code loads issued; 2 A tile fetched, folded with x and laid out as MFMA operands; 3 B rows and
-table seen complete (LDS flags); 4 row stream done (look-ups + MFMAs over all slabs); 5 barrier
-behind the stream; 6 sums over ranks and waves, hand-over between column blocks, Y written.
+Boundaries: 0 kernel entered; 1 flags cleared, rows of B requested, level table built (the four builder
+waves only); 2 first slab, activations, A tile and the other slabs of the ring requested, the wave's
+rows of B arrived and staged in LDS; 3 A tile arrived, folded with x and laid out as MFMA operands,
+rows of B and table of ALL waves seen complete (LDS flags); 4 row stream done (look-ups + MFMAs over
+all slabs); 5 barrier behind the stream; 6 sums over ranks and waves, hand-over between column blocks,
+Y written.
 """
 from __future__ import annotations
 
@@ -26,7 +28,7 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, os.path.dirname(HERE))
 
-NAMES = ["entered", "tables+loads issued", "A tile folded", "B rows/table ready", "stream done", "barrier", "end"]
+NAMES = ["entered", "B asked, table built", "loads out, B staged", "A folded, flags seen", "stream done", "barrier", "end"]
 
 
 def main() -> int:

@@ -76,8 +76,7 @@ static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32
         }
         const int dmax = gv_dmax(d.G, d.jt, d.MT, bits);
         d.ring = d.per > dmax;
-        d.depth = d.ring ? dmax : gv_round_depth(d.per);
-        if (d.depth > dmax) { d.depth = dmax; d.ring = d.per > dmax; }
+        d.depth = d.ring ? gv_ring_depth(d.per, dmax) : gv_round_depth(d.per);
         d.smem = lut + kGvWaves * stg + 256 + (size_t)d.per * b_slab;
         d.nodes = gv_tree_nodes(d.kblocks);
         if (fits || G == gmax) return true;

@@ -561,10 +561,21 @@ static hipError_t launch_gv_t(const GvArgs &a, dim3 grid, size_t smem, hipStream
     return hipGetLastError();
 }
 
-// Ring depths built without refill: 1, 2, 3, 4, 6, 8 (a workgroup with fewer slabs than slots repeats
-// its last one); with refill the largest the registers allow.  Ranks that are not a multiple of 8
-// (element-wise B loads) only get depth 2.
-constexpr int gv_round_depth(int per) { return per <= 4 ? per : per <= 6 ? 6 : 8; }
+// Ring depths built without refill: 1 .. 8 (a workgroup with fewer slabs than slots repeats its last one).
+// With refill every pass computes all slots of the ring, also those beyond the workgroup's last slab, and the
+// row stream is bound by instruction issue, not by the arrival of the codes: of the three deepest rings the
+// registers allow, the one whose last pass idles the fewest slots is taken (14 slabs: two passes of 7, not
+// 8 + 6 of 8), the deeper on ties.  Ranks that are not a multiple of 8 (element-wise B loads) only get depth 2.
+constexpr int gv_round_depth(int per) { return per <= 8 ? per : 8; }
+constexpr int gv_ring_depth(int per, int dmax)
+{
+    int best = dmax, waste = (dmax - per % dmax) % dmax;
+    for (int D = dmax - 1; D >= dmax - 2 && D >= 2; --D) {
+        const int w = (D - per % D) % D;
+        if (w < waste) { best = D; waste = w; }
+    }
+    return best;
+}
 
 template <int BITS, int JT, int G, int LG, int MT>
 static hipError_t launch_gv_d(const GvArgs &a, dim3 grid, const GvPlan &d, bool bvec, hipStream_t st)
@@ -574,10 +585,15 @@ static hipError_t launch_gv_d(const GvArgs &a, dim3 grid, const GvPlan &d, bool 
         if (d.ring) return launch_gv_t<BITS, JT, G, LG, MT, 2, true, false>(a, grid, d.smem, st);
         return launch_gv_t<BITS, JT, G, LG, MT, 2, false, false>(a, grid, d.smem, st);
     }
-    if (d.ring) return launch_gv_t<BITS, JT, G, LG, MT, DM, true, true>(a, grid, d.smem, st);
+    if (d.ring) {
+        if constexpr (DM >= 4) if (d.depth == DM - 2) return launch_gv_t<BITS, JT, G, LG, MT, DM - 2, true, true>(a, grid, d.smem, st);
+        if constexpr (DM >= 3) if (d.depth == DM - 1) return launch_gv_t<BITS, JT, G, LG, MT, DM - 1, true, true>(a, grid, d.smem, st);
+        if (d.depth == DM) return launch_gv_t<BITS, JT, G, LG, MT, DM, true, true>(a, grid, d.smem, st);
+        return hipErrorInvalidValue;
+    }
 #define LORDS_GVD(D_) \
     if constexpr (D_ <= DM) if (d.depth == D_) return launch_gv_t<BITS, JT, G, LG, MT, D_, false, true>(a, grid, d.smem, st);
-    LORDS_GVD(1) LORDS_GVD(2) LORDS_GVD(3) LORDS_GVD(4) LORDS_GVD(6) LORDS_GVD(8)
+    LORDS_GVD(1) LORDS_GVD(2) LORDS_GVD(3) LORDS_GVD(4) LORDS_GVD(5) LORDS_GVD(6) LORDS_GVD(7) LORDS_GVD(8)
 #undef LORDS_GVD
     return hipErrorInvalidValue;
 }

@@ -137,6 +137,22 @@ def test_matmul_decode_many_rows(gpu, N, K, r, M):
     check_y(Y, want, "Y")
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("M", [1, 2])
+@pytest.mark.parametrize("per", [5, 7, 9, 10, 13, 14, 16, 17])
+def test_matmul_one_token_ring_depths(gpu, bits, M, per):
+    """K = 256 is one column block, so 256 workgroups share the rows: `per` slabs of 16 rows each.  Up to 8 slabs a
+    workgroup holds them all (depths 5 and 7 here), beyond that a ring of 6, 7 or 8 slots is refilled: every depth
+    and a ragged last slab."""
+    import paper_2601_22716_amd as L
+    N = 4096 * per - 5
+    say(f"matmul one-token ring: {per} slabs per workgroup, bits={bits} M={M} N={N}")
+    cs = li.make_case("tiny", M=M, N=N, K=256, bits=bits, r=32, factor_dtype="bf16", seed=40 + per)
+    Y = gpu.DeviceCase(cs).matmul(path=L.LORDS_PATH_DECODE)
+    want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, bits)
+    check_y(Y, want, "Y")
+
+
 @pytest.mark.parametrize("M", [1, 17, 40, 130, 300])
 def test_matmul_parity_ragged_tokens(gpu, M):
     import paper_2601_22716_amd as L

@@ -63,15 +63,15 @@ int get_workspace(size_t need, void *stream, WsView *out)
 }
 
 // One token: the regrouped kernel of lords_gemv.hip wherever it takes the shape.  Two tokens: the same,
-// except on layers above 32 M weights with at least as many rows as columns, where the few-token kernel
-// measured faster (us, regrouped / few-token: 14336 x 4096 rank 32 16.0 / 15.3, rank 48 21.8 / 19.7,
-// 28672 x 8192 rank 64 101 / 66; against 4096 x 14336 rank 32 17.1 / 17.8, rank 48 22.9 / 24.2,
-// 4096 x 4096 8.7 / 10.2).
+// except at ranks above 32 on layers above 32 M weights with at least as many rows as columns, where the
+// few-token kernel measured faster (us, regrouped / few-token: 14336 x 4096 rank 48 20.9 / 19.6,
+// 28672 x 8192 rank 64 85 / 66; against 14336 x 4096 rank 32 14.7 / 15.4, 4096 x 14336 rank 32 16.7 / 17.8,
+// rank 48 22.3 / 24.6, 4096 x 4096 8.3 / 10.2, 6144 x 4096 10.1 / 11.1).
 bool use_gemv(const lords::MatmulProblem &p, lords_path path)
 {
     if (path == LORDS_PATH_SMALLM) return false;
     if (path == LORDS_PATH_GEMV) return lords::decode_gemv_supported(p);
-    if (p.M == 2 && (long)p.N * p.K > (32L << 20) && p.N >= p.K) return false;
+    if (p.M == 2 && p.r > 32 && (long)p.N * p.K > (32L << 20) && p.N >= p.K) return false;
     return lords::decode_gemv_supported(p);
 }
 

@@ -28,7 +28,7 @@ static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32
 {
     if (f32fact || M < 1 || M > 2 || L < 1 || L > kGvMaxLayers) return false;
     const int tiles = (r + 15) / 16;
-    d.jt = tiles <= 2 ? 2 : tiles <= 4 ? 4 : 0;
+    d.jt = tiles <= 2 ? 2 : (tiles == 3 && M == 1) ? 3 : tiles <= 4 ? 4 : 0;    // (three tiles at one token: the smaller staging unit leaves two tokens too little room for their lane sums)
     d.MT = M;
     if (d.jt == 0 || d.jt * d.MT > 8) return false;
     const int gmax = 8 / (d.jt * d.MT) < 2 ? 8 / (d.jt * d.MT) : 2;       // operands within 128 registers
@@ -44,7 +44,7 @@ static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32
         const int wk = kGvWaves * 128 * G;
         d.kblocks = (K + wk - 1) / wk;
         // slabs a workgroup can take: its rows of B and its lane sums must fit LDS
-        const size_t lut = (size_t)(1 << (2 * bits)) * 256, stg = (size_t)gv_unit_rows(d.LG) * (128 * d.LG + 8) * 2;
+        const size_t lut = (size_t)(1 << (2 * bits)) * 256, stg = (size_t)gv_unit_rows(d.LG, d.jt) * (128 * d.LG + 8) * 2;
         const size_t b_slab = (size_t)16 * 16 * d.jt * 2;
         long cap = (long)((kGvLdsLimit - 256 - lut - kGvWaves * stg) / b_slab);
         if (cap > (long)(stg / ((size_t)d.MT * 256))) cap = (long)(stg / ((size_t)d.MT * 256));

@@ -70,7 +70,7 @@ constexpr int kGvFlags = 2 * kGvWaves + kGvBuilders;   // LDS flags: B rows stag
 constexpr int kGvBRounds = 2;             // 16-byte chunks of B a thread holds in registers until they are staged
 constexpr int kGvMaxG = 4;                // widest column range of a wave: 128*G columns
 // rows of a staging unit of the A tile: two tiles, or one where the units are many or wide (LDS room)
-constexpr int gv_unit_rows(int lg) { return lg == 2 ? 16 : 32; }
+constexpr int gv_unit_rows(int lg, int jt) { return (lg == 2 || (jt & 1)) ? 16 : 32; }   // (three tiles: one at a time)
 
 // most ring slots (slabs in flight) of an instantiation: eight where 64 registers hold the operands,
 // with 128 what the remaining registers take (G*bits per slab)
@@ -119,7 +119,7 @@ struct GvArgs {
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-// BITS: code width.  JT: 16-row a-operand tiles (one per 16 rank entries, 2 or 4).  G: 32-code
+// BITS: code width.  JT: 16-row a-operand tiles (one per 16 rank entries: 2, 3 or 4).  G: 32-code
 // groups per lane.  LG: groups per load.  MT: tokens.  D: slabs whose loads are in flight.
 // RING: a workgroup may hold more than D slabs (slots are refilled).  BVEC: rows of B can be read with
 // 16-byte loads.
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     constexpr int QW = 4 * JT, BW = QW / 2;                 // rank entries / dwords of B per lane and slab
     constexpr int RP = 16 * JT, BCH = RP / 8;               // padded rank; 16-byte chunks of a staged B row
     // staging of the A tile: units of UR tile rows x PCOL columns, one buffer per wave
-    constexpr int UR = gv_unit_rows(LG), TPU = UR / 16; // rows and tiles of a unit
+    constexpr int UR = gv_unit_rows(LG, JT), TPU = UR / 16; // rows and tiles of a unit
     constexpr int PCOL = 128 * LG, NUC = G / LG, NUR = JT / TPU;
     constexpr int CPRW = PCOL / 8, RPI = 64 / CPRW, NLD = UR / RPI;    // 16-byte chunks per row, rows per load, loads per unit
     constexpr int SST = PCOL + 8;                           // staged row stride in bf16
@@ -442,11 +442,21 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 if (cs % STEPS == STEPS - 1) {
                     // the slab is complete: accumulator element e of tile t is T[n][QW*g + 4t + e]; weigh with the lane's run of B
                     uint32_t Bq[BW];
+                    if constexpr (BW % 4 == 0) {
 #pragma unroll
-                    for (int h = 0; h < BW / 4; ++h) {
-                        const u32x4 t = *reinterpret_cast<const u32x4 *>(Bs + (min(i, nsw - 1) * 16 + c) * RP + QW * g + 8 * h);
+                        for (int h = 0; h < BW / 4; ++h) {
+                            const u32x4 t = *reinterpret_cast<const u32x4 *>(Bs + (min(i, nsw - 1) * 16 + c) * RP + QW * g + 8 * h);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) Bq[4 * h + e] = t[e];
+                            for (int e = 0; e < 4; ++e) Bq[4 * h + e] = t[e];
+                        }
+                    } else {                               // (three tiles: runs of 24 bytes, 8-byte aligned)
+                        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+                        for (int h = 0; h < BW / 2; ++h) {
+                            const u32x2 t = *reinterpret_cast<const u32x2 *>(Bs + (min(i, nsw - 1) * 16 + c) * RP + QW * g + 4 * h);
+                            Bq[2 * h] = t[0];
+                            Bq[2 * h + 1] = t[1];
+                        }
                     }
 #pragma unroll
                     for (int m = 0; m < MT; ++m) {
@@ -606,6 +616,7 @@ static hipError_t launch_gv_bits(const GvArgs &a, const GvPlan &d, bool bvec, di
     LORDS_GVCASE(2, 1, 1, 1) LORDS_GVCASE(2, 2, 2, 1) LORDS_GVCASE(2, 2, 1, 1)
     LORDS_GVCASE(4, 1, 1, 1) LORDS_GVCASE(4, 2, 2, 1) LORDS_GVCASE(4, 2, 1, 1)
     LORDS_GVCASE(2, 1, 1, 2) LORDS_GVCASE(2, 2, 2, 2) LORDS_GVCASE(2, 2, 1, 2) LORDS_GVCASE(4, 1, 1, 2)
+    LORDS_GVCASE(3, 1, 1, 1) LORDS_GVCASE(3, 2, 2, 1) LORDS_GVCASE(3, 2, 1, 1)
 #undef LORDS_GVCASE
     return hipErrorInvalidValue;
 }

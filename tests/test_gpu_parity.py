@@ -153,6 +153,21 @@ def test_matmul_one_token_ring_depths(gpu, bits, M, per):
     check_y(Y, want, "Y")
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("r", [40, 48, 56])
+@pytest.mark.parametrize("per", [3, 7, 10, 14])
+def test_matmul_one_token_three_and_four_rank_tiles(gpu, bits, r, per):
+    """Ranks 33..48 take three 16-entry rank tiles per slab at one token (runs of 24 bytes of B per lane), ranks
+    49..64 four; with and without a refilled ring, ragged last slab."""
+    import paper_2601_22716_amd as L
+    N = 4096 * per - 3
+    say(f"matmul one-token rank tiles: r={r} bits={bits} {per} slabs per workgroup N={N}")
+    cs = li.make_case("tiny", M=1, N=N, K=256, bits=bits, r=r, factor_dtype="bf16", seed=70 + per + r)
+    Y = gpu.DeviceCase(cs).matmul(path=L.LORDS_PATH_GEMV)
+    want = onp.matmul(cs.X_f32, cs.codes, cs.codebook, cs.B_f32, cs.A_f32, bits)
+    check_y(Y, want, "Y")
+
+
 @pytest.mark.parametrize("M", [1, 17, 40, 130, 300])
 def test_matmul_parity_ragged_tokens(gpu, M):
     import paper_2601_22716_amd as L

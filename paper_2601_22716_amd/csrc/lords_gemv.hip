@@ -38,7 +38,11 @@ static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32
     // (the kernel addresses the codes of a matrix with 32-bit byte offsets, in either layout)
     for (int l = 0; l < L; ++l)
         if ((size_t)nslabs[l] * 16 * (size_t)((K + 127) / 128) * 16 * (size_t)bits >= ((size_t)1 << 32) - 64) return false;
-    for (int G = 1; G <= gmax; G *= 2) {
+    // (2-bit codes: a lane's two groups of a 2048-column block come with one 16-byte load and no lane swap, and on
+    //  layers of 32 M weights and more the wider block measured 3-4 % faster at one token: 14336 x 4096 11.8 -> 11.3 us,
+    //  4096 x 14336 13.6 -> 13.1; smaller layers lose, 4096 x 4096 6.9 -> 7.5)
+    const int g_first = (bits == 2 && M == 1 && L == 1 && gmax >= 2 && total * 16 * (long)K >= (32L << 20)) ? 2 : 1;
+    for (int G = g_first; G <= gmax; G *= 2) {
         d.G = G;
         d.LG = (G >= 2 && (K % 64) == 0 && !tiled) ? 2 : 1;               // (the slab-tile layout is read one 128-column tile at a time)
         const int wk = kGvWaves * 128 * G;

@@ -19,7 +19,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblords.so")
-SOURCES = ["lords_api.hip", "lords_probe.hip", "lords_basic.hip", "lords_quant.hip", "lords_fused.hip", "lords_decode.hip", "lords_gemv.hip", "lords_gemv_b2.hip", "lords_gemv_b3.hip", "lords_gemv_b4.hip", "lords_decode_mx.hip", "lords_prefill.hip", "lords_backward.hip"]
+SOURCES = ["lords_api.hip", "lords_probe.hip", "lords_basic.hip", "lords_quant.hip", "lords_fused.hip", "lords_decode.hip", "lords_gemv.hip", "lords_gemv_b2.hip", "lords_gemv_b2q.hip", "lords_gemv_b3.hip", "lords_gemv_b4.hip", "lords_decode_mx.hip", "lords_prefill.hip", "lords_backward.hip"]
 HEADERS = ["lords_device.h", "lords_launch.h", "lords_decode_common.h", "lords_gemv_kernel.h", os.path.join("..", "..", "include", "lords.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -24,8 +24,9 @@ static size_t gv_tree_nodes(int kblocks)
 // the Llama-3-8B/70B layer shapes, the narrowest block that still gives every CU one workgroup is
 // the fastest: G = 1 unless the workgroups would then hold more slabs than their LDS takes.
 // Matrix l gets gxl[l] row ranges of at most d.per slabs each; d.gx is their sum.
-static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32fact, bool tiled, GvPlan &d, int *gxl)
+static bool gv_plan_table(int M, const int *N, int L, int K, int r, int bits, bool f32fact, bool tiled, bool quad, GvPlan &d, int *gxl, bool *fits_out)
 {
+    d.quad = quad;
     if (f32fact || M < 1 || M > 2 || L < 1 || L > kGvMaxLayers) return false;
     const int tiles = (r + 15) / 16;
     d.jt = tiles <= 2 ? 2 : (tiles == 3 && M == 1) ? 3 : tiles <= 4 ? 4 : 0;    // (three tiles at one token: the smaller staging unit leaves two tokens too little room for their lane sums)
@@ -48,7 +49,8 @@ static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32
         const int wk = kGvWaves * 128 * G;
         d.kblocks = (K + wk - 1) / wk;
         // slabs a workgroup can take: its rows of B and its lane sums must fit LDS
-        const size_t lut = (size_t)(1 << (2 * bits)) * 256, stg = (size_t)gv_unit_rows(d.LG, d.jt) * (128 * d.LG + 8) * 2;
+        const size_t lut = (size_t)(quad ? 256 : 1 << (2 * bits)) * 256,           // (quad: entries of four 2-bit codes)
+                      stg = (size_t)gv_unit_rows(d.LG, d.jt) * (128 * d.LG + 8) * 2;
         const size_t b_slab = (size_t)16 * 16 * d.jt * 2;
         long cap = (long)((kGvLdsLimit - 256 - lut - kGvWaves * stg) / b_slab);
         if (cap > (long)(stg / ((size_t)d.MT * 256))) cap = (long)(stg / ((size_t)d.MT * 256));
@@ -83,9 +85,18 @@ static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32
         d.depth = d.ring ? gv_ring_depth(d.per, dmax) : gv_round_depth(d.per);
         d.smem = lut + kGvWaves * stg + 256 + (size_t)d.per * b_slab;
         d.nodes = gv_tree_nodes(d.kblocks);
-        if (fits || G == gmax) return true;
+        if (fits || G == gmax) { *fits_out = fits; return true; }
     }
     return false;
+}
+
+// 2-bit codes are looked up four at a time (a 64 KB table instead of 4 KB) where every workgroup's slabs still fit
+// beside the larger table; otherwise, and at 3 and 4 bits, two at a time.
+static bool gv_plan(int M, const int *N, int L, int K, int r, int bits, bool f32fact, bool tiled, GvPlan &d, int *gxl)
+{
+    bool fits = false;
+    if (bits == 2 && gv_plan_table(M, N, L, K, r, bits, f32fact, tiled, true, d, gxl, &fits) && fits) return true;
+    return gv_plan_table(M, N, L, K, r, bits, f32fact, tiled, false, d, gxl, &fits);
 }
 
 // bytes of exchange slots: the trees of all matrices, plus the slots where a gate/up pair meets
@@ -156,7 +167,7 @@ hipError_t launch_decode_gemv_batched(const BatchedProblem &bp, void *zeroed, hi
     const bool bvec = (bp.r % 8) == 0;
     const dim3 grid(d.gx, 1, d.kblocks);
     switch (bp.bits) {
-        case 2: return launch_gemv_2bit(a, d, bvec, grid, st);
+        case 2: return d.quad ? launch_gemv_2bit_quads(a, d, bvec, grid, st) : launch_gemv_2bit(a, d, bvec, grid, st);
         case 3: return launch_gemv_3bit(a, d, bvec, grid, st);
         case 4: return launch_gemv_4bit(a, d, bvec, grid, st);
         default: return hipErrorInvalidValue;

@@ -122,8 +122,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 // BITS: code width.  JT: 16-row a-operand tiles (one per 16 rank entries: 2, 3 or 4).  G: 32-code
 // groups per lane.  LG: groups per load.  MT: tokens.  D: slabs whose loads are in flight.
 // RING: a workgroup may hold more than D slabs (slots are refilled).  BVEC: rows of B can be read with
-// 16-byte loads.
-template <int BITS, int JT, int G, int LG, int MT, int D, bool RING, bool BVEC, bool MULTI>
+// 16-byte loads.  MULTI: the launch serves several matrices.  QT: 2-bit codes looked up four at a time.
+template <int BITS, int JT, int G, int LG, int MT, int D, bool RING, bool BVEC, bool MULTI, bool QT = false>
 __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemv_kernel(GvArgs a)
 {
     // A load unit is LG groups of 32 codes per lane.  HL: the unit is fetched as TWO loads of eight
@@ -134,7 +134,13 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     constexpr bool HL = BITS != 2 && LG == 2;
     constexpr int NV = G / LG, NH = HL ? 2 : 1, DW = HL ? BITS : LG * BITS;    // units per slab; loads per unit; dwords per load
     constexpr int KTW = 128 * G, WK = kGvWaves * KTW;
-    constexpr int NL = 1 << BITS, NE = 1 << (2 * BITS);
+    // QUAD (2-bit codes): the table is indexed by a byte of four codes and holds four bf16 levels per entry, 32
+    // copies of 8 bytes (lanes l and l + 32 share a copy; an 8-byte read serves them in different cycles): half
+    // the address operations and half the LDS reads per weight of the pair table, which at 2 bits would be as
+    // many per weight as at 4 bits, so that a 2-bit layer would take as long as a 4-bit one.
+    constexpr bool QUAD = QT;
+    static_assert(!QT || BITS == 2, "the table of code quadruples is for 2-bit codes");
+    constexpr int NL = 1 << BITS, NE = QUAD ? 256 : 1 << (2 * BITS);
     constexpr int QW = 4 * JT, BW = QW / 2;                 // rank entries / dwords of B per lane and slab
     constexpr int RP = 16 * JT, BCH = RP / 8;               // padded rank; 16-byte chunks of a staged B row
     // staging of the A tile: units of UR tile rows x PCOL columns, one buffer per wave
@@ -165,7 +171,7 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     }
     const int bx = (int)blockIdx.x - bx_first;
     const int N = ly.N, K = a.K, r = a.r;
-    const uint32_t laneoff = (uint32_t)lane * 4u;
+    const uint32_t laneoff = QUAD ? (uint32_t)(lane & 31) * 8u : (uint32_t)lane * 4u;
     const int ngroups = K >> 5;
     // this workgroup's slabs: an even share of the matrix (the host keeps it within the LDS budget), from
     // a quotient and remainder the host worked out (a division here is a hundred dependent scalar instructions)
@@ -280,6 +286,24 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         float cb[NL];
 #pragma unroll
         for (int i = 0; i < NL; ++i) cb[i] = a.codebook[i];                  // uniform addresses: scalar loads
+        if constexpr (QUAD) {
+            // entry idx = (t >> 4) + 16 * it, a byte of four codes: dword 0 = levels of codes 0, 1 (idx & 15, the
+            // same in every pass), dword 1 = levels of codes 2, 3 (idx >> 4 = it); thread t writes copies
+            // 2 (t & 15) and 2 (t & 15) + 1
+            const int x = (tid >> 4) & 15;
+            float l0 = cb[0], l1 = cb[0];
+#pragma unroll
+            for (int i = 1; i < NL; ++i) {
+                l0 = (x & 3) == i ? cb[i] : l0;
+                l1 = (x >> 2) == i ? cb[i] : l1;
+            }
+            const uint32_t pv0 = bf16_bits(l0) | ((uint32_t)bf16_bits(l1) << 16);
+#pragma unroll
+            for (int it = 0; it < 16; ++it) {
+                const uint32_t pv1 = bf16_bits(cb[it & 3]) | ((uint32_t)bf16_bits(cb[it >> 2]) << 16);
+                *reinterpret_cast<u32x4 *>(lut32 + ((tid >> 4) + 16 * it) * 64 + 4 * (tid & 15)) = u32x4{pv0, pv1, pv0, pv1};
+            }
+        } else {
         // entry (hi << BITS) | lo as a bf16 pair, once per lane.  Builder thread t writes four lanes'
         // copies of entry (t >> 4) + 16 * it: its low code is the same in every pass, its high code
         // the same for the whole wave
@@ -300,6 +324,7 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 const uint32_t pv = lo | ((uint32_t)bf16_bits(hi) << 16);
                 *reinterpret_cast<u32x4 *>(lut32 + idx * 64 + 4 * (tid & 15)) = u32x4{pv, pv, pv, pv};
             }
+        }
         }
         if (lane == 0) __hip_atomic_store(&bflag[kGvBRounds * kGvWaves + wave], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
@@ -427,7 +452,20 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 uint32_t gw[BITS];
                 group_words(d, v, gw);
 #pragma unroll
-                for (int p = 0; p < 4; ++p) wq[gs % (kGvAhead + 1)][p] = lds_load_u32(pair_addr<BITS>(gw, 4 * u + p, laneoff));
+                for (int p = 0; p < 4; ++p) {
+                    if constexpr (QUAD) {
+                        if (p < 2) {                   // bytes 2u, 2u + 1 of the group's eight: codes 8u .. 8u + 7
+                            const int b = 2 * u + p;
+                            const uint32_t ad = __builtin_amdgcn_perm(gw[b >> 2], laneoff, 0x0C0C0000u | ((4u + (b & 3)) << 8));
+                            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                            const u32x2 t = *reinterpret_cast<const __attribute__((address_space(3))) u32x2 *>((uintptr_t)ad);
+                            wq[gs % (kGvAhead + 1)][2 * p] = t[0];
+                            wq[gs % (kGvAhead + 1)][2 * p + 1] = t[1];
+                        }
+                    } else {
+                        wq[gs % (kGvAhead + 1)][p] = lds_load_u32(pair_addr<BITS>(gw, 4 * u + p, laneoff));
+                    }
+                }
             }
             if (gs >= kGvAhead) {
                 const int cs = gs - kGvAhead, d = cs / STEPS, u = (cs % STEPS) / G, v = cs % G;
@@ -550,24 +588,25 @@ struct GvPlan {
     int per;           // most slabs of one workgroup
     int depth;         // ring slots (template D)
     bool ring;         // a workgroup has more slabs than ring slots: slots are refilled
+    bool quad;         // 2-bit codes: the 64 KB table of code quadruples (where the slabs still fit beside it)
     size_t smem;       // dynamic LDS bytes
     size_t nodes;      // exchange-tree nodes
 };
 
-template <int BITS, int JT, int G, int LG, int MT, int D, bool RING, bool BVEC>
+template <int BITS, int JT, int G, int LG, int MT, int D, bool RING, bool BVEC, bool QT = false>
 static hipError_t launch_gv_t(const GvArgs &a, dim3 grid, size_t smem, hipStream_t st)
 {
     static LdsOptIn lds_opt_in;
     if (a.L > 1) {
         static LdsOptIn lds_opt_in_multi;
-        const hipError_t e = allow_dynamic_lds(lds_opt_in_multi, reinterpret_cast<const void *>(&gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, true>), kGvLdsLimit);
+        const hipError_t e = allow_dynamic_lds(lds_opt_in_multi, reinterpret_cast<const void *>(&gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, true, QT>), kGvLdsLimit);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, true>), grid, dim3(kGvThreads), smem, st, a);
+        hipLaunchKernelGGL((gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, true, QT>), grid, dim3(kGvThreads), smem, st, a);
         return hipGetLastError();
     }
-    const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, false>), kGvLdsLimit);
+    const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, false, QT>), kGvLdsLimit);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, false>), grid, dim3(kGvThreads), smem, st, a);
+    hipLaunchKernelGGL((gemv_kernel<BITS, JT, G, LG, MT, D, RING, BVEC, false, QT>), grid, dim3(kGvThreads), smem, st, a);
     return hipGetLastError();
 }
 
@@ -587,32 +626,32 @@ constexpr int gv_ring_depth(int per, int dmax)
     return best;
 }
 
-template <int BITS, int JT, int G, int LG, int MT>
+template <int BITS, int JT, int G, int LG, int MT, bool QT = false>
 static hipError_t launch_gv_d(const GvArgs &a, dim3 grid, const GvPlan &d, bool bvec, hipStream_t st)
 {
     constexpr int DM = gv_dmax(G, JT, MT, BITS);
     if (!bvec) {
-        if (d.ring) return launch_gv_t<BITS, JT, G, LG, MT, 2, true, false>(a, grid, d.smem, st);
-        return launch_gv_t<BITS, JT, G, LG, MT, 2, false, false>(a, grid, d.smem, st);
+        if (d.ring) return launch_gv_t<BITS, JT, G, LG, MT, 2, true, false, QT>(a, grid, d.smem, st);
+        return launch_gv_t<BITS, JT, G, LG, MT, 2, false, false, QT>(a, grid, d.smem, st);
     }
     if (d.ring) {
-        if constexpr (DM >= 4) if (d.depth == DM - 2) return launch_gv_t<BITS, JT, G, LG, MT, DM - 2, true, true>(a, grid, d.smem, st);
-        if constexpr (DM >= 3) if (d.depth == DM - 1) return launch_gv_t<BITS, JT, G, LG, MT, DM - 1, true, true>(a, grid, d.smem, st);
-        if (d.depth == DM) return launch_gv_t<BITS, JT, G, LG, MT, DM, true, true>(a, grid, d.smem, st);
+        if constexpr (DM >= 4) if (d.depth == DM - 2) return launch_gv_t<BITS, JT, G, LG, MT, DM - 2, true, true, QT>(a, grid, d.smem, st);
+        if constexpr (DM >= 3) if (d.depth == DM - 1) return launch_gv_t<BITS, JT, G, LG, MT, DM - 1, true, true, QT>(a, grid, d.smem, st);
+        if (d.depth == DM) return launch_gv_t<BITS, JT, G, LG, MT, DM, true, true, QT>(a, grid, d.smem, st);
         return hipErrorInvalidValue;
     }
 #define LORDS_GVD(D_) \
-    if constexpr (D_ <= DM) if (d.depth == D_) return launch_gv_t<BITS, JT, G, LG, MT, D_, false, true>(a, grid, d.smem, st);
+    if constexpr (D_ <= DM) if (d.depth == D_) return launch_gv_t<BITS, JT, G, LG, MT, D_, false, true, QT>(a, grid, d.smem, st);
     LORDS_GVD(1) LORDS_GVD(2) LORDS_GVD(3) LORDS_GVD(4) LORDS_GVD(5) LORDS_GVD(6) LORDS_GVD(7) LORDS_GVD(8)
 #undef LORDS_GVD
     return hipErrorInvalidValue;
 }
 
-template <int BITS>
+template <int BITS, bool QT = false>
 static hipError_t launch_gv_bits(const GvArgs &a, const GvPlan &d, bool bvec, dim3 grid, hipStream_t st)
 {
 #define LORDS_GVCASE(J_, G_, L_, M_) \
-    if (d.jt == J_ && d.G == G_ && d.LG == L_ && d.MT == M_) return launch_gv_d<BITS, J_, G_, L_, M_>(a, grid, d, bvec, st);
+    if (d.jt == J_ && d.G == G_ && d.LG == L_ && d.MT == M_) return launch_gv_d<BITS, J_, G_, L_, M_, QT>(a, grid, d, bvec, st);
     LORDS_GVCASE(2, 1, 1, 1) LORDS_GVCASE(2, 2, 2, 1) LORDS_GVCASE(2, 2, 1, 1)
     LORDS_GVCASE(4, 1, 1, 1) LORDS_GVCASE(4, 2, 2, 1) LORDS_GVCASE(4, 2, 1, 1)
     LORDS_GVCASE(2, 1, 1, 2) LORDS_GVCASE(2, 2, 2, 2) LORDS_GVCASE(2, 2, 1, 2) LORDS_GVCASE(4, 1, 1, 2)
@@ -621,7 +660,8 @@ static hipError_t launch_gv_bits(const GvArgs &a, const GvPlan &d, bool bvec, di
     return hipErrorInvalidValue;
 }
 
-// defined in lords_gemv_b2.hip, lords_gemv_b3.hip, lords_gemv_b4.hip
+// defined in lords_gemv_b2.hip, lords_gemv_b2q.hip, lords_gemv_b3.hip, lords_gemv_b4.hip
+hipError_t launch_gemv_2bit_quads(const GvArgs &a, const GvPlan &d, bool bvec, dim3 grid, hipStream_t st);
 hipError_t launch_gemv_2bit(const GvArgs &a, const GvPlan &d, bool bvec, dim3 grid, hipStream_t st);
 hipError_t launch_gemv_3bit(const GvArgs &a, const GvPlan &d, bool bvec, dim3 grid, hipStream_t st);
 hipError_t launch_gemv_4bit(const GvArgs &a, const GvPlan &d, bool bvec, dim3 grid, hipStream_t st);

@@ -158,7 +158,7 @@ def bench_decode(args, L, li, torch):
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": counter_traffic()[0]["decode"],
                      "traffic_taken_at": counter_traffic()[1],
-                     "kernel": "lords::gemv_kernel<4,2,1,1,1,7,true,true,false> (bits, tiles, G, LG, tokens, ring, refill, 16-byte B loads, several matrices)",
+                     "kernel": "lords::gemv_kernel<4,2,1,1,1,7,true,true,false,false> (bits, tiles, G, LG, tokens, ring, refill, 16-byte B loads, several matrices, quadruple table)",
                      "us_per_launch": ev_per_launch * 1e6},
     }
     return out, cs, sets[0], X, codebook

@@ -172,6 +172,10 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     const int bx = (int)blockIdx.x - bx_first;
     const int N = ly.N, K = a.K, r = a.r;
     const uint32_t laneoff = QUAD ? (uint32_t)(lane & 31) * 8u : (uint32_t)lane * 4u;
+    // (the mask of a bf16 pair's upper half, kept in a vector register: a logic operation whose operands are all
+    //  vector registers issues every 2.3 clocks per SIMD, with a literal or scalar operand every 4)
+    uint32_t himask = 0xFFFF0000u;
+    asm volatile("" : "+v"(himask));
     const int ngroups = K >> 5;
     // this workgroup's slabs: an even share of the matrix (the host keeps it within the LDS budget), from
     // a quotient and remainder the host worked out (a division here is a hundred dependent scalar instructions)
@@ -396,7 +400,7 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     xl[e] = __builtin_bit_cast(float, xr[uc][m][e] << 16);
-                    xh[e] = __builtin_bit_cast(float, xr[uc][m][e] & 0xFFFF0000u);
+                    xh[e] = __builtin_bit_cast(float, xr[uc][m][e] & himask);
                 }
 #pragma unroll
                 for (int q = 0; q < NLD; ++q) {
@@ -404,7 +408,7 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const f32x2 pr = {__builtin_bit_cast(float, Araw[uc][ur][q][e] << 16) * xl[e],
-                                          __builtin_bit_cast(float, Araw[uc][ur][q][e] & 0xFFFF0000u) * xh[e]};
+                                          __builtin_bit_cast(float, Araw[uc][ur][q][e] & himask) * xh[e]};
                         o[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));   // one v_cvt_pk_bf16_f32
                     }
                     *reinterpret_cast<u32x4 *>(stage + (((q + rot) % NLD) * RPI + rsub) * SST + 8 * ch) = o;
@@ -505,7 +509,7 @@ __global__ __launch_bounds__(kGvThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                             for (int e = 0; e < 4; ++e) {
                                 const float sv = acc[t][m][e];
                                 const int q = 4 * t + e;                       // position in the lane's run
-                                const uint32_t raw = (q & 1) ? (Bq[q >> 1] & 0xFFFF0000u) : (Bq[q >> 1] << 16);
+                                const uint32_t raw = (q & 1) ? (Bq[q >> 1] & himask) : (Bq[q >> 1] << 16);
                                 const float bv = __builtin_bit_cast(float, raw);
                                 if (e & 1) y1 = __builtin_fmaf(sv, bv, y1);
                                 else y0 = __builtin_fmaf(sv, bv, y0);

@@ -76,8 +76,8 @@ typedef enum {
     LORDS_PATH_DECODE = 1,   /* memory-bound small-M family, the kernel picked by M: GEMV where it applies, else SMALLM */
     LORDS_PATH_PREFILL = 2,  /* bf16 MFMA GEMM with the dequantised tile as operand */
     LORDS_PATH_MFMA = 2,     /* (the same) */
-    LORDS_PATH_GEMV = 3,     /* the one-/two-token kernel alone: M <= 2, bf16 factors, rank <= 64 (two tokens: <= 32 at
-                                most shapes), LORDS_ERR_UNSUPPORTED otherwise */
+    LORDS_PATH_GEMV = 3,     /* the one-/two-token kernel alone: M <= 2, bf16 factors, rank <= 64,
+                                LORDS_ERR_UNSUPPORTED otherwise */
     LORDS_PATH_SMALLM = 4    /* the few-token kernels alone (16 tokens per pass over the codes), any M */
 } lords_path;
 

@@ -77,8 +77,6 @@ def test_forced_kernels_agree_with_the_oracle(gpu, bits, r, M):
     """GEMV, SMALLM and MFMA forced on the same small layer (ragged N, K over several column blocks)."""
     import paper_2601_22716_amd as L
     N, K = 403, 2592
-    if M == 2 and r > 32:
-        pytest.skip("two tokens: the one-/two-token kernel takes ranks up to 32")
     say(f"forced kernels bits={bits} r={r} M={M}")
     cs = li.make_case("tiny", M=M, N=N, K=K, bits=bits, r=r, factor_dtype="bf16", seed=77, signed_factors=True)
     d = gpu.DeviceCase(cs)

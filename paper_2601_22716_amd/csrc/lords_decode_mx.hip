@@ -70,7 +70,11 @@ typedef MxArgsT<kMaxBatch> MxMultiArgs;
 template <int BITS, int SS, int G, bool BVEC, bool MULTI = false>
 __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_mx_kernel(MxArgsT<MULTI ? kMaxBatch : 1> a)
 {
-    constexpr int KT = 128 * G, WK = 4 * KT, AST = WK + 8, NL = 1 << BITS, NE = 1 << (2 * BITS), CPR = WK / 8;
+    // QUAD (2-bit codes): the table is indexed by a byte of four codes and holds four fp16 levels per entry, 32
+    // copies of 8 bytes (lanes l and l + 32 share a copy; an 8-byte read serves them in different cycles): half the
+    // address operations and LDS reads per weight of a pair table.
+    constexpr bool QUAD = BITS == 2;
+    constexpr int KT = 128 * G, WK = 4 * KT, AST = WK + 8, NL = 1 << BITS, NE = QUAD ? 256 : 1 << (2 * BITS), CPR = WK / 8;
     constexpr int LUT_BYTES = NE * 256, A_BYTES = SS * 32 * AST * 2;
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t *As = reinterpret_cast<uint16_t *>(smem + LUT_BYTES);        // [SS*32][AST], then X [16][AST], then sums
@@ -90,7 +94,7 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     const int gxl = MULTI ? ly.gxn : (int)gridDim.x;
     const bool meet = a.splits > 1 || (MULTI && a.act);       // column blocks (and a gate/up pair) meet in the workspace
     const int N = ly.N, K = a.K, M = a.M, r = a.r;
-    const uint32_t laneoff = (uint32_t)lane * 4u;
+    const uint32_t laneoff = QUAD ? (uint32_t)(lane & 31) * 8u : (uint32_t)lane * 4u;
     const int ngroups = K >> 5;
 
     // Loads of slab i of the current chunk, branch-free (addresses clamped into the arrays) so that
@@ -163,8 +167,18 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         const int id = tid + kMxThreads * it, idx = (id >> 4) & (NE - 1);
-        lo[it] = a.codebook[idx & (NL - 1)];
-        hi[it] = a.codebook[idx >> BITS];
+        // (QUAD: levels of codes 0, 1 of the entry's four here, of codes 2, 3 below)
+        lo[it] = a.codebook[QUAD ? (idx & 3) : (idx & (NL - 1))];
+        hi[it] = a.codebook[QUAD ? ((idx >> 2) & 3) : (idx >> BITS)];
+    }
+    float lo2[QUAD ? NIT : 1], hi2[QUAD ? NIT : 1];
+    if constexpr (QUAD) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int id = tid + kMxThreads * it, idx = (id >> 4) & (NE - 1);
+            lo2[it] = a.codebook[(idx >> 4) & 3];
+            hi2[it] = a.codebook[idx >> 6];
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -187,6 +201,13 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                 h[0] = (_Float16)lo[it];
                 h[1] = (_Float16)hi[it];
                 const uint32_t pv = __builtin_bit_cast(uint32_t, h);
+                if constexpr (QUAD) {
+                    f16x2 h2;
+                    h2[0] = (_Float16)lo2[it];
+                    h2[1] = (_Float16)hi2[it];
+                    const uint32_t pv2 = __builtin_bit_cast(uint32_t, h2);
+                    *reinterpret_cast<u32x4 *>(lut32 + idx * 64 + 4 * q) = u32x4{pv, pv2, pv, pv2};     // copies 2q, 2q + 1
+                } else
                 *reinterpret_cast<u32x4 *>(lut32 + idx * 64 + 4 * q) = u32x4{pv, pv, pv, pv};
             }
         }
@@ -245,6 +266,25 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                         for (int uu = 0; uu < 2; ++uu) {
                             const int u = 2 * hh + uu;
                             bf16x8 W;
+                            if constexpr (QUAD) {
+#pragma unroll
+                                for (int q2 = 0; q2 < 2; ++q2) {               // bytes 2u, 2u + 1 of the group's eight: codes 8u .. 8u + 7
+                                    const int b = 2 * u + q2;
+                                    const uint32_t ad = __builtin_amdgcn_perm(cw[i][v][b >> 2], laneoff, 0x0C0C0000u | ((4u + (b & 3)) << 8));
+                                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                                    const u32x2 t = *reinterpret_cast<const __attribute__((address_space(3))) u32x2 *>((uintptr_t)ad);
+#pragma unroll
+                                    for (int hq = 0; hq < 2; ++hq) {
+                                        // (the word is picked by name: a bit cast of the subscripted element t[hq]
+                                        // compiled to element 0 for both)
+                                        const f16x2 h = __builtin_bit_cast(f16x2, hq == 0 ? t.x : t.y);
+                                        const int e0 = 4 * q2 + 2 * hq, e1 = e0 + 1;
+                                        const float s0 = S[2 * uu + (e0 >> 2)][e0 & 3], s1 = S[2 * uu + (e1 >> 2)][e1 & 3];
+                                        W[e0] = (__bf16)__builtin_fmaf((float)h[0], s0, 0.0f);
+                                        W[e1] = (__bf16)__builtin_fmaf((float)h[1], s1, 0.0f);
+                                    }
+                                }
+                            } else
 #pragma unroll
                             for (int pp = 0; pp < 4; ++pp) {
                                 const uint32_t ad = pair_addr<BITS>(cw[i][v], 4 * u + pp, laneoff);
@@ -472,7 +512,7 @@ template <int BITS, int SS, int G, bool BVEC, bool MULTI>
 static hipError_t launch_mx_t(const MxArgsT<MULTI ? kMaxBatch : 1> &a, dim3 grid, hipStream_t st)
 {
     constexpr int WK = 4 * 128 * G, AST = WK + 8;
-    const size_t smem = (size_t)(1 << (2 * BITS)) * 256 + (size_t)SS * 32 * AST * 2 + kMxTickets * sizeof(int);
+    const size_t smem = (size_t)(BITS == 2 ? 256 : 1 << (2 * BITS)) * 256 + (size_t)SS * 32 * AST * 2 + kMxTickets * sizeof(int);   // (2 bits: entries of four codes)
     static LdsOptIn lds_opt_in;
     if (smem > 48 * 1024) {
         const hipError_t e = allow_dynamic_lds(lds_opt_in, reinterpret_cast<const void *>(&decode_mx_kernel<BITS, SS, G, BVEC, MULTI>), smem);

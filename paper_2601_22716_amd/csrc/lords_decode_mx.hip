@@ -26,6 +26,7 @@
 //   it holds (columns kb + 32*(G*g+v) ...).
 //   product MFMA u of group v: a-operand = the lane's 8 dequantised weights 8u..8u+7 of the
 //   group, b-operand = X[c][the same 8 columns]; D[i][j] with i <-> row, j <-> token.
+#include <type_traits>
 #include "lords_decode_common.h"
 
 namespace lords {
@@ -382,23 +383,35 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                     for (int q = tid; q < M * (rows / 4); q += kMxThreads) {
                         const int m = q / (rows / 4), n = row0 + 4 * (q - m * (rows / 4));
                         if (n >= N) continue;
+                        // ZB column blocks in one round trip, added in order.  Straight-line code per count: blocks
+                        // beyond the last are not loaded at all (every device-coherent load costs its full price,
+                        // also when it repeats an address), and no load's target register is merged with another
+                        // value before the wait.
+                        auto add_batch = [&](const float *P, int z0, auto zb, f32x4 &acc) __attribute__((always_inline)) {
+                            constexpr int ZB = decltype(zb)::value;
+                            f32x4 tz[ZB];
+#pragma unroll
+                            for (int u = 0; u < ZB; ++u) tz[u] = load16_agent(P + ((size_t)(z0 + u) * M + m) * N + n);
+                            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+                            for (int u = 0; u < ZB; ++u) {
+                                asm volatile("" : "+v"(tz[u]));                      // (not before the wait)
+                                acc[0] += tz[u][0]; acc[1] += tz[u][1]; acc[2] += tz[u][2]; acc[3] += tz[u][3];
+                            }
+                        };
                         auto add_blocks4 = [&](const float *P) __attribute__((always_inline)) -> f32x4 {
                             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-                            for (int z0 = 0; z0 < a.splits; z0 += 8) {
-                                f32x4 t8[8];
-#pragma unroll
-                                for (int u = 0; u < 8; ++u) {
-                                    const int z = min(z0 + u, a.splits - 1);
-                                    t8[u] = load16_agent(P + ((size_t)z * M + m) * N + n);
-                                }
-                                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-                                for (int u = 0; u < 8; ++u) {
-                                    asm volatile("" : "+v"(t8[u]));                  // (not before the wait)
-                                    if (z0 + u < a.splits) {
-                                        acc[0] += t8[u][0]; acc[1] += t8[u][1]; acc[2] += t8[u][2]; acc[3] += t8[u][3];
-                                    }
-                                }
+                            int z0 = 0;
+                            for (; z0 + 8 <= a.splits; z0 += 8) add_batch(P, z0, std::integral_constant<int, 8>{}, acc);
+                            switch (a.splits - z0) {
+                            case 7: add_batch(P, z0, std::integral_constant<int, 7>{}, acc); break;
+                            case 6: add_batch(P, z0, std::integral_constant<int, 6>{}, acc); break;
+                            case 5: add_batch(P, z0, std::integral_constant<int, 5>{}, acc); break;
+                            case 4: add_batch(P, z0, std::integral_constant<int, 4>{}, acc); break;
+                            case 3: add_batch(P, z0, std::integral_constant<int, 3>{}, acc); break;
+                            case 2: add_batch(P, z0, std::integral_constant<int, 2>{}, acc); break;
+                            case 1: add_batch(P, z0, std::integral_constant<int, 1>{}, acc); break;
+                            default: break;
                             }
                             return acc;
                         };

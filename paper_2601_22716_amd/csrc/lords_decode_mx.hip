@@ -43,7 +43,7 @@ struct MxLayer {
     const uint16_t *B;     // N x r bf16
     void *Y;
     float *partial;        // [splits][M][N] fp32, used when the column blocks meet in the workspace
-    unsigned *counters;    // one ticket per chunk, zero between calls
+    unsigned *counters;    // `parts` tickets per chunk, zero between calls
     int N;
     int nslabs;            // ceil(N / 16)
     int ns;                // slabs per wave per chunk, <= kNS
@@ -63,6 +63,7 @@ struct MxArgsT {
     int act;               // 1: matrices 0 and 1 are a gate/up pair, Y of matrix 0 receives silu(gate) * up
     int tiled;             // codes in the slab-tile layout (16 rows x 128 columns per tile, chunk 16 g + c of 4 * BITS bytes)
     int nct;               // column tiles per slab, ceil(K / 128)
+    int parts;             // tickets per chunk: the chunk's outputs are read back in `parts` shares, each with a ticket of its own
     MxLayer layer[NLAYERS];
 };
 typedef MxArgsT<1> MxArgs;
@@ -79,7 +80,6 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
     constexpr int LUT_BYTES = NE * 256, A_BYTES = SS * 32 * AST * 2;
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t *As = reinterpret_cast<uint16_t *>(smem + LUT_BYTES);        // [SS*32][AST], then X [16][AST], then sums
-    int *flag = reinterpret_cast<int *>(smem + LUT_BYTES + A_BYTES);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
@@ -364,34 +364,54 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
         void *Yout = pair ? a.layer[0].Y : ly.Y;
         const int rows = 2 * ly.ns * 16;
         const int niter = (ly.nchunks - bx + gxl - 1) / gxl;
-        for (int base = 0; base < niter; base += kMxTickets) {
-            const int nt = min(kMxTickets, niter - base);
-            if (tid < nt) {
-                const int ch = bx + (base + tid) * gxl;
-                const unsigned old = __hip_atomic_fetch_add(&ly.counters[ch], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const int last = (old == arrivals - 1u);
-                // every other workgroup of this chunk has passed: hand the ticket back at zero
-                if (last) __hip_atomic_store(&ly.counters[ch], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                flag[tid] = last;
-            }
-            __syncthreads();
-            for (int t = 0; t < nt; ++t) {
-                if (!flag[t]) continue;
-                const int row0 = (bx + (base + t) * gxl) * rows;
-                if ((N & 3) == 0) {
-                    // four neighbouring rows per thread, 16-byte loads, up to eight column blocks in flight
-                    for (int q = tid; q < M * (rows / 4); q += kMxThreads) {
+        // Who reads the sums back.  The outputs of a chunk are cut into P shares with a ticket each, and share p
+        // belongs to the workgroups of rank p (mod P) among those that meet in the chunk.  A workgroup first takes
+        // the tickets of the shares of others, and only then, one round trip later, those of its own: workgroups that
+        // end at about the same time thus each arrive last at their own shares, and the read-back (which runs at
+        // the rate of one CU's device-coherent loads) is spread over all of them instead of falling to the slowest
+        // alone.  Whatever the timing, every ticket is taken exactly once by each workgroup and the last taker reads
+        // the share back: a workgroup that is late inherits the shares of those that have left.
+        const int P = a.parts;
+        const int rank = (int)blockIdx.z + ((pair && li == 1) ? a.splits : 0);
+        const int mine = rank % P;
+        const bool vec = (N & 3) == 0;
+        const int T = vec ? M * (rows / 4) : M * rows;            // outputs (of four rows, or of one) per chunk
+        const int ipp = (T + P - 1) / P;                          // the largest share
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        i32x4 *ent = reinterpret_cast<i32x4 *>(As);               // one entry per ticket of a batch (the sums' region is free now)
+        for (int phase = 0; phase < 2; ++phase) {
+            const int np = phase == 0 ? P - 1 : 1;                // shares per chunk in this phase
+            const int ntot = niter * np;
+            for (int base = 0; base < ntot; base += kMxTickets) {
+                const int nt = min(kMxTickets, ntot - base);
+                if (tid < nt) {
+                    const int idx = base + tid, it = idx / np, pi = idx - it * np;
+                    const int part = phase == 0 ? (pi < mine ? pi : pi + 1) : mine;
+                    unsigned *tk = &ly.counters[(size_t)(bx + it * gxl) * P + part];
+                    const unsigned old = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const int last = (old == arrivals - 1u);
+                    // every other workgroup of this chunk has passed: hand the ticket back at zero
+                    if (last) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    // (won, first output of the share, one past its last, first row of the chunk; 32-bit quotients)
+                    ent[tid] = i32x4{last, (int)((unsigned)(part * T) / (unsigned)P), (int)((unsigned)((part + 1) * T) / (unsigned)P),
+                                     (bx + it * gxl) * rows};
+                }
+                __syncthreads();
+                // output q of a chunk whose first row is row0: the column blocks added in order, Y written
+                auto reduce_item = [&](int q, int row0) __attribute__((always_inline)) {
+                    if (vec) {
+                        // four neighbouring rows, 16-byte loads, up to eight column blocks in flight
                         const int m = q / (rows / 4), n = row0 + 4 * (q - m * (rows / 4));
-                        if (n >= N) continue;
+                        if (n >= N) return;
                         // ZB column blocks in one round trip, added in order.  Straight-line code per count: blocks
                         // beyond the last are not loaded at all (every device-coherent load costs its full price,
                         // also when it repeats an address), and no load's target register is merged with another
                         // value before the wait.
-                        auto add_batch = [&](const float *P, int z0, auto zb, f32x4 &acc) __attribute__((always_inline)) {
+                        auto add_batch = [&](const float *Pp, int z0, auto zb, f32x4 &acc) __attribute__((always_inline)) {
                             constexpr int ZB = decltype(zb)::value;
                             f32x4 tz[ZB];
 #pragma unroll
-                            for (int u = 0; u < ZB; ++u) tz[u] = load16_agent(P + ((size_t)(z0 + u) * M + m) * N + n);
+                            for (int u = 0; u < ZB; ++u) tz[u] = load16_agent(Pp + ((size_t)(z0 + u) * M + m) * N + n);
                             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
                             for (int u = 0; u < ZB; ++u) {
@@ -399,51 +419,49 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                                 acc[0] += tz[u][0]; acc[1] += tz[u][1]; acc[2] += tz[u][2]; acc[3] += tz[u][3];
                             }
                         };
-                        auto add_blocks4 = [&](const float *P) __attribute__((always_inline)) -> f32x4 {
+                        auto add_blocks4 = [&](const float *Pp) __attribute__((always_inline)) -> f32x4 {
                             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
                             int z0 = 0;
-                            for (; z0 + 8 <= a.splits; z0 += 8) add_batch(P, z0, std::integral_constant<int, 8>{}, acc);
+                            for (; z0 + 8 <= a.splits; z0 += 8) add_batch(Pp, z0, std::integral_constant<int, 8>{}, acc);
                             switch (a.splits - z0) {
-                            case 7: add_batch(P, z0, std::integral_constant<int, 7>{}, acc); break;
-                            case 6: add_batch(P, z0, std::integral_constant<int, 6>{}, acc); break;
-                            case 5: add_batch(P, z0, std::integral_constant<int, 5>{}, acc); break;
-                            case 4: add_batch(P, z0, std::integral_constant<int, 4>{}, acc); break;
-                            case 3: add_batch(P, z0, std::integral_constant<int, 3>{}, acc); break;
-                            case 2: add_batch(P, z0, std::integral_constant<int, 2>{}, acc); break;
-                            case 1: add_batch(P, z0, std::integral_constant<int, 1>{}, acc); break;
+                            case 7: add_batch(Pp, z0, std::integral_constant<int, 7>{}, acc); break;
+                            case 6: add_batch(Pp, z0, std::integral_constant<int, 6>{}, acc); break;
+                            case 5: add_batch(Pp, z0, std::integral_constant<int, 5>{}, acc); break;
+                            case 4: add_batch(Pp, z0, std::integral_constant<int, 4>{}, acc); break;
+                            case 3: add_batch(Pp, z0, std::integral_constant<int, 3>{}, acc); break;
+                            case 2: add_batch(Pp, z0, std::integral_constant<int, 2>{}, acc); break;
+                            case 1: add_batch(Pp, z0, std::integral_constant<int, 1>{}, acc); break;
                             default: break;
                             }
                             return acc;
                         };
-                        f32x4 s = add_blocks4(Pg);
+                        f32x4 sv = add_blocks4(Pg);
                         if (pair) {
                             const f32x4 up = add_blocks4(Pu);
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) s[e] = s[e] / (1.0f + __expf(-s[e])) * up[e];
+                            for (int e4 = 0; e4 < 4; ++e4) sv[e4] = sv[e4] / (1.0f + __expf(-sv[e4])) * up[e4];
                         }
                         if (a.y_f32) {
-                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(Yout) + (size_t)m * N + n) = s;
+                            *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(Yout) + (size_t)m * N + n) = sv;
                         } else {
                             typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
                             u32x2 o;
-                            o[0] = (uint32_t)bf16_bits(s[0]) | ((uint32_t)bf16_bits(s[1]) << 16);
-                            o[1] = (uint32_t)bf16_bits(s[2]) | ((uint32_t)bf16_bits(s[3]) << 16);
+                            o[0] = (uint32_t)bf16_bits(sv[0]) | ((uint32_t)bf16_bits(sv[1]) << 16);
+                            o[1] = (uint32_t)bf16_bits(sv[2]) | ((uint32_t)bf16_bits(sv[3]) << 16);
                             *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(Yout) + (size_t)m * N + n) = o;
                         }
+                        return;
                     }
-                    continue;
-                }
-                for (int q = tid; q < M * rows; q += kMxThreads) {
                     const int m = q / rows, n = row0 + (q - m * rows);
-                    if (n >= N) continue;
-                    auto add_blocks = [&](const float *P) __attribute__((always_inline)) -> float {
+                    if (n >= N) return;
+                    auto add_blocks = [&](const float *Pp) __attribute__((always_inline)) -> float {
                         float acc = 0.f;
                         for (int z0 = 0; z0 < a.splits; z0 += 8) {
                             float t8[8];
 #pragma unroll
                             for (int u = 0; u < 8; ++u) {
                                 const int z = min(z0 + u, a.splits - 1);
-                                t8[u] = __hip_atomic_load(&P[((size_t)z * M + m) * N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                t8[u] = __hip_atomic_load(&Pp[((size_t)z * M + m) * N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             }
 #pragma unroll
                             for (int u = 0; u < 8; ++u)
@@ -451,17 +469,32 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
                         }
                         return acc;
                     };
-                    float s = add_blocks(Pg);
+                    float sc = add_blocks(Pg);
                     if (pair) {
                         // SwiGLU gate: silu(gate) * up on the fp32 sums, one rounding at the store
                         const float up = add_blocks(Pu);
-                        s = s / (1.0f + __expf(-s)) * up;
+                        sc = sc / (1.0f + __expf(-sc)) * up;
                     }
-                    if (a.y_f32) reinterpret_cast<float *>(Yout)[(size_t)m * N + n] = s;
-                    else reinterpret_cast<uint16_t *>(Yout)[(size_t)m * N + n] = bf16_bits(s);
+                    if (a.y_f32) reinterpret_cast<float *>(Yout)[(size_t)m * N + n] = sc;
+                    else reinterpret_cast<uint16_t *>(Yout)[(size_t)m * N + n] = bf16_bits(sc);
+                };
+                if (P == 1) {
+                    for (int t = 0; t < nt; ++t) {
+                        const i32x4 d = ent[t];
+                        if (!d[0]) continue;
+                        for (int q = tid; q < T; q += kMxThreads) reduce_item(q, d[3]);
+                    }
+                } else {
+                    // all shares won in this batch at once: item j = (ticket of the batch, output of its share)
+                    for (int j = tid; j < nt * ipp; j += kMxThreads) {
+                        const int e = (int)((unsigned)j / (unsigned)ipp);
+                        const i32x4 d = ent[e];
+                        const int q = d[1] + (j - e * ipp);
+                        if (d[0] && q < d[2]) reduce_item(q, d[3]);
+                    }
                 }
+                __syncthreads();                               // the flags are rewritten by the next batch
             }
-            __syncthreads();                               // the flags are rewritten by the next batch
         }
     }
 }
@@ -470,8 +503,22 @@ __global__ __launch_bounds__(kMxThreads) __attribute__((amdgpu_waves_per_eu(2, 2
 // host side
 // ---------------------------------------------------------------------------------------------
 struct MxPlan {
-    int ss, G, WK, splits, ns, nchunks, gx;
+    int ss, G, WK, splits, ns, nchunks, gx, parts;
 };
+
+// Read-back shares per chunk: one per workgroup that meets in a chunk, at most 32, and no more than the ticket
+// array holds.  Taking the tickets in two rounds costs a round trip (measured 1.5 us at 4 tokens on 14336 x 4096,
+// where a last arriver reads 14 KB back, 0.4 us at 16 tokens, 57 KB) and pays from about 200 KB per last arriver
+// (16 tokens: 14336 x 4096 at rank 48 22.4 -> 20.3 us, 4096 x 14336 at rank 32 20.3 -> 18.3): one share, i.e. the
+// last arriver alone, below 128 KB.  `splits * splits * M * N / 64` bytes: splits * M * N * 4 in all, read by
+// 256 / splits workgroups.
+static int mx_parts(int arrivals, size_t chunks, int splits, int M, int N)
+{
+    if ((size_t)splits * splits * M * N / 64 < ((size_t)128 << 10)) return 1;
+    int parts = arrivals < 32 ? arrivals : 32;
+    while (parts > 1 && chunks * (size_t)parts * sizeof(unsigned) > kTicketBytes) parts /= 2;
+    return parts < 1 ? 1 : parts;
+}
 
 static int mx_ss(const MatmulProblem &p)
 {
@@ -503,6 +550,7 @@ static MxPlan mx_plan(const MatmulProblem &p)
     d.ns = mx_slabs_per_chunk(nslabs, 2 * gx);
     d.nchunks = (nslabs + 2 * d.ns - 1) / (2 * d.ns);
     d.gx = gx < d.nchunks ? gx : d.nchunks;
+    d.parts = mx_parts(d.splits, (size_t)d.nchunks, d.splits, p.M < 16 ? p.M : 16, p.N);
     return d;
 }
 
@@ -549,6 +597,7 @@ hipError_t launch_decode_mx(const MatmulProblem &p, void *workspace, hipStream_t
         a.y_f32 = p.f32out ? 1 : 0;
         a.row_bytes = p.K / 8 * p.bits;
         a.splits = d.splits;
+        a.parts = d.parts;
         a.L = 1;
         a.act = 0;
         a.tiled = p.tiled ? 1 : 0;
@@ -584,7 +633,7 @@ hipError_t launch_decode_mx(const MatmulProblem &p, void *workspace, hipStream_t
 // batched launch: several matrices, the same (up to 16) tokens
 // ---------------------------------------------------------------------------------------------
 struct MxBatchPlan {
-    int ss, G, splits, total_gx;
+    int ss, G, splits, total_gx, parts;
     int ns[kMaxBatch], nchunks[kMaxBatch], gx0[kMaxBatch], gxn[kMaxBatch];
     size_t ticket0[kMaxBatch], partial0[kMaxBatch];           // offsets in tickets / floats
     size_t tickets, partial_floats;
@@ -635,6 +684,9 @@ static bool mx_batch_plan(const BatchedProblem &p, MxBatchPlan &d)
         d.partial_floats += (size_t)d.splits * p.M * p.N[l];
     }
     d.total_gx = x0;
+    int nmax = 0;
+    for (int l = 0; l < p.L; ++l) nmax = p.N[l] > nmax ? p.N[l] : nmax;
+    d.parts = mx_parts(p.act ? 2 * d.splits : d.splits, d.tickets, d.splits, p.M, nmax);
     return d.tickets * sizeof(unsigned) <= kTicketBytes;
 }
 
@@ -662,6 +714,7 @@ hipError_t launch_decode_mx_batched(const BatchedProblem &p, void *workspace, hi
     a.y_f32 = p.f32out ? 1 : 0;
     a.row_bytes = p.K / 8 * p.bits;
     a.splits = d.splits;
+    a.parts = d.parts;
     a.L = p.L;
     a.act = p.act ? 1 : 0;
     a.tiled = p.tiled ? 1 : 0;
@@ -673,7 +726,7 @@ hipError_t launch_decode_mx_batched(const BatchedProblem &p, void *workspace, hi
         ly.A = (const uint16_t *)p.A[s];
         ly.B = (const uint16_t *)p.B[s];
         ly.Y = p.Y[s];
-        ly.counters = (unsigned *)workspace + d.ticket0[s];
+        ly.counters = (unsigned *)workspace + d.ticket0[s] * d.parts;
         ly.partial = (float *)((unsigned char *)workspace + kTicketBytes) + d.partial0[s];
         ly.N = p.N[s];
         ly.nslabs = (p.N[s] + 15) / 16;

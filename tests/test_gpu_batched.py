@@ -281,6 +281,39 @@ def test_full_size_gate_up_sampled(gpu, M):
     check_h(H[np.ix_(toks, rows)], G, U, f"{toks.size} tokens x {rows.size} rows")
 
 
+def test_full_size_gate_up_shared_read_back(gpu):
+    """A gate/up pair whose partial sums are large enough for the few-token kernel to share a chunk's read-back out
+    among the workgroups that meet in it (14336 x 4096, 3 bits, rank 48, 16 tokens: 8 column blocks per matrix, 16
+    shares per chunk); sampled rows against the oracle."""
+    N, K, r, bits, M = 14336, 4096, 48, 3, 16
+    say(f"full-size gate/up rank 48 M={M}")
+    cg, cu = gate_up_cases(N, K, r, bits, M, seed=19)
+    H = run_gate_up(gpu, cg, cu, M)
+    assert np.isfinite(H).all()
+    rows = np.unique(np.concatenate([[0, 3, 4, N - 1], np.random.default_rng(92).integers(0, N, 126)]))
+    toks = np.arange(M)
+    G, U = oracle_products(cg, cu, bits, rows=rows, toks=toks)
+    check_h(H[np.ix_(toks, rows)], G, U, f"{toks.size} tokens x {rows.size} rows")
+    H2 = run_gate_up(gpu, cg, cu, M)
+    np.testing.assert_array_equal(H, H2)
+
+
+def test_full_size_batched_shared_read_back(gpu):
+    """Two matrices of many column blocks sharing X at 16 tokens (4096 x 14336 each, 4 bits, rank 32: 14 column
+    blocks, 14 shares per chunk) in one launch: sampled rows against the oracle, and the same as matrix by matrix."""
+    Ns, K, r, bits, M = [4096, 4096], 14336, 32, 4, 16
+    say(f"full-size batched Ns={Ns} K={K} M={M}")
+    cases = layers_sharing_x(Ns, K, r, bits, M, seed=18)
+    dev, Ys = run_batched(gpu, cases, M)
+    rng = np.random.default_rng(81)
+    for l, (c, Y) in enumerate(zip(cases, Ys)):
+        rows = np.unique(np.concatenate([[0, c.N - 1], rng.integers(0, c.N, 100)]))
+        want = onp.matmul_rows(cases[0].X_f32, c.codes, c.codebook, c.B_f32, c.A_f32, bits, rows)
+        check(Y[:, rows], want, f"matrix {l}, {rows.size} rows")
+        same_as_single(Y, dev[l].matmul(X=dev[0].X, M=M), M, f"matrix {l}")
+
+
+
 def test_workspace_bytes_lent_to_gate_up_stay_clear_of_the_tickets(gpu):
     """The two-product form of lords_gate_up borrows workspace for its fp32 products.  A case whose
     own kernels need no workspace (a single column split) must not be given the front of the buffer,
